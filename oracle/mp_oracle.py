@@ -1,0 +1,305 @@
+"""TEST INFRASTRUCTURE, NOT PRODUCT CODE: Python face of the fp64 CPU oracle.
+
+Loads ``libmp_oracle.so`` (plain C, built from ``mp_oracle.c`` by :func:`build`) and adds the
+orchestration that is easier to read in numpy than in C: the blockwise / two-level index
+construction (Sec. 3.1, 3.3, 3.4 of the paper) and the online cluster update (Sec. 3.3).
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may
+import this module.  It imports nothing from the GPU package.
+
+All arrays are float64 numpy arrays holding bf16-representable values (inputs are bf16 tensors
+widened exactly); cluster ids are int32.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mp_oracle.c")
+_LIB = os.path.join(_HERE, "libmp_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (no GPU code, no HIP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+_dp = C.POINTER(C.c_double)
+_ip = C.POINTER(C.c_int32)
+_bp = C.POINTER(C.c_uint8)
+
+
+def _d(a):
+    return None if a is None else a.ctypes.data_as(_dp)
+
+
+def _i(a):
+    return None if a is None else a.ctypes.data_as(_ip)
+
+
+def _b(a):
+    return None if a is None else a.ctypes.data_as(_bp)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.mpo_round_bf16.restype = C.c_double
+        _lib.mpo_round_bf16.argtypes = [C.c_double]
+        _lib.mpo_decode_unit.restype = C.c_int
+        _lib.mpo_decode_batch.restype = C.c_int
+        _lib.mpo_num_threads.restype = C.c_int
+    return _lib
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def num_threads() -> int:
+    return int(lib().mpo_num_threads())
+
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """Element-wise round-to-nearest-even of fp64 to bf16 values (returned as fp64)."""
+    x = _f64(x)
+    out = np.empty_like(x)
+    lib().mpo_round_bf16_array(_d(x), _d(out), C.c_int64(x.size))
+    return out
+
+
+def full_attention(q, K, V, scale):
+    """Textbook softmax attention of G query rows over all n keys.  Returns (out [G,d], lse [G])."""
+    q, K, V = _f64(q), _f64(K), _f64(V)
+    G, d = q.shape
+    n = K.shape[0]
+    out = np.zeros((G, d))
+    lse = np.zeros(G)
+    lib().mpo_full_attention(_d(q), _d(K), _d(V), C.c_int(G), C.c_int(n), C.c_int(d), C.c_double(scale),
+                             _d(out), _d(lse))
+    return out, lse
+
+
+def decode_unit(q, cl, key_budget, coarse_budget=0, Kx=None, Vx=None, scale=None, mp_terms=True):
+    """One Multipole Attention decode step for one unit (Eq. 1, Eq. 2, Sec. 3.4).
+
+    ``cl`` is a clustering dict as produced by :func:`cluster_unit` or
+    :func:`clustering_from_assignment`.  Returns a dict with out, lse, promising, selected, r_c,
+    r_f, n_sel_keys.
+    """
+    q = _f64(q)
+    G, d = q.shape
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    K, V = _f64(cl["K"]), _f64(cl["V"])
+    n = K.shape[0]
+    fot = _i32(cl["fine_of_token"])
+    Kc_f, Vc_f, N_f = _f64(cl["Kc_f"]), _f64(cl["Vc_f"]), _i32(cl["N_f"])
+    Cf = N_f.shape[0]
+    levels = int(cl["levels"])
+    if levels == 2:
+        cof, Kc_c, Vc_c, N_c = _i32(cl["coarse_of_fine"]), _f64(cl["Kc_c"]), _f64(cl["Vc_c"]), _i32(cl["N_c"])
+        Cc = N_c.shape[0]
+    else:
+        cof = Kc_c = Vc_c = N_c = None
+        Cc = 0
+    nx = 0 if Kx is None else int(np.asarray(Kx).shape[0])
+    Kx = _f64(Kx) if nx else None
+    Vx = _f64(Vx) if nx else None
+    out = np.zeros((G, d))
+    lse = np.zeros(G)
+    promising = np.zeros(max(Cc, 1), dtype=np.uint8)
+    selected = np.zeros(max(Cf, 1), dtype=np.uint8)
+    r_c = np.full(max(Cc, 1), np.nan)
+    r_f = np.full(max(Cf, 1), np.nan)
+    nsel = C.c_int64(0)
+    rc = lib().mpo_decode_unit(
+        _d(q), C.c_int(G), C.c_int(d), C.c_double(scale), _d(K), _d(V), C.c_int(n), _i(fot),
+        C.c_int(Cf), _d(Kc_f), _d(Vc_f), _i(N_f), C.c_int(levels), C.c_int(Cc), _i(cof), _d(Kc_c), _d(Vc_c),
+        _i(N_c), _d(Kx), _d(Vx), C.c_int(nx), C.c_int64(int(key_budget)), C.c_int64(int(coarse_budget)),
+        C.c_int(1 if mp_terms else 0), _d(out), _d(lse), _b(promising), _b(selected), _d(r_c), _d(r_f),
+        C.byref(nsel))
+    if rc != 0:
+        raise ValueError("clustering is inconsistent (N_f / N_c do not match the assignments)")
+    return dict(out=out, lse=lse, promising=promising[:Cc], selected=selected[:Cf], r_c=r_c[:Cc],
+                r_f=r_f[:Cf], n_sel_keys=int(nsel.value))
+
+
+def assign(X, Cn):
+    """Nearest-centroid assignment, squared Euclidean distance, ties to the lowest index."""
+    X, Cn = _f64(X), _f64(Cn)
+    a = np.zeros(X.shape[0], dtype=np.int32)
+    lib().mpo_assign(_d(X), C.c_int(X.shape[0]), _d(Cn), C.c_int(Cn.shape[0]), C.c_int(X.shape[1]), _i(a))
+    return a
+
+
+def member_sums(X, a, k):
+    X, a = _f64(X), _i32(a)
+    S = np.zeros((k, X.shape[1]))
+    cnt = np.zeros(k, dtype=np.int32)
+    lib().mpo_member_sums(_d(X), C.c_int(X.shape[0]), _i(a), C.c_int(k), C.c_int(X.shape[1]), _d(S), _i(cnt))
+    return S, cnt
+
+
+def lloyd(X, init_idx, iters):
+    """Lloyd k-means from explicit seeds; returns (centroids bf16-valued [k,d], assignment, counts)."""
+    X, init_idx = _f64(X), _i32(init_idx)
+    k = init_idx.shape[0]
+    Cn = np.zeros((k, X.shape[1]))
+    a = np.zeros(X.shape[0], dtype=np.int32)
+    cnt = np.zeros(k, dtype=np.int32)
+    lib().mpo_lloyd(_d(X), C.c_int(X.shape[0]), C.c_int(X.shape[1]), _i(init_idx), C.c_int(k), C.c_int(iters),
+                    _d(Cn), _i(a), _i(cnt))
+    return Cn, a, cnt
+
+
+def lloyd_from(X, Cn, iters):
+    """Lloyd iterations continuing from the given centroids; returns (centroids, assignment, counts)."""
+    X = _f64(X)
+    Cn = _f64(Cn).copy()
+    k = Cn.shape[0]
+    a = np.zeros(X.shape[0], dtype=np.int32)
+    cnt = np.zeros(k, dtype=np.int32)
+    lib().mpo_lloyd_from(_d(X), C.c_int(X.shape[0]), C.c_int(X.shape[1]), C.c_int(k), C.c_int(iters), _d(Cn),
+                         _i(a), _i(cnt))
+    return Cn, a, cnt
+
+
+# --------------------------------------------------------------------------------------------
+# Blockwise, hierarchical index construction (Sec. 3.3 blocks of W tokens with a final block of
+# alpha .. W+alpha tokens; Sec. 3.4 second level obtained by clustering the fine centroids).
+# --------------------------------------------------------------------------------------------
+
+def plan_blocks(n_tokens, block_w, block_alpha, n_fine, n_coarse):
+    """Token ranges and per-block cluster counts.
+
+    Blocks hold W tokens except the last, which holds between alpha and W+alpha-1 tokens (all of
+    them when there are fewer than W+alpha, or when block_w == 0).  The per-unit totals n_fine and
+    n_coarse are shared out in proportion to the token ranges by cumulative integer division, so
+    that the counts sum exactly to the totals.
+    """
+    if block_w <= 0 or n_tokens < block_w + block_alpha:
+        bounds = [0, n_tokens]
+    else:
+        m = (n_tokens - block_alpha) // block_w
+        bounds = [i * block_w for i in range(m + 1)] + [n_tokens]
+    blocks = []
+    for b in range(len(bounds) - 1):
+        t0, t1 = bounds[b], bounds[b + 1]
+        f0, f1 = (n_fine * t0) // n_tokens, (n_fine * t1) // n_tokens
+        c0, c1 = (n_coarse * t0) // n_tokens, (n_coarse * t1) // n_tokens
+        blocks.append(dict(t0=t0, t1=t1, f0=f0, f1=f1, c0=c0, c1=c1))
+    return blocks
+
+
+def _mean_bf16(S, cnt):
+    out = np.zeros_like(S)
+    nz = cnt > 0
+    out[nz] = round_bf16(S[nz] / cnt[nz, None].astype(np.float64))
+    return out
+
+
+def finalize_block(Kb, Vb, a_fine, Cf_kmeans, parent, kc, Cc_kmeans):
+    """Renumber a block's fine clusters so that the children of each coarse cluster are contiguous
+    (stable in the old id), and compute the stored tables: key/value centroid = mean of the member
+    keys/values (Sec. 3.1, 3.2) rounded to bf16; an empty cluster keeps its k-means centroid as
+    key centroid, a zero value centroid, and N = 0."""
+    kf = Cf_kmeans.shape[0]
+    if parent is None:
+        order = np.arange(kf)
+    else:
+        order = np.argsort(parent, kind="stable")
+    new_of_old = np.empty(kf, dtype=np.int32)
+    new_of_old[order] = np.arange(kf, dtype=np.int32)
+    a_new = new_of_old[a_fine]
+    Sk, N_f = member_sums(Kb, a_new, kf)
+    Sv, _ = member_sums(Vb, a_new, kf)
+    Kc_f = _mean_bf16(Sk, N_f)
+    Kc_f[N_f == 0] = Cf_kmeans[order][N_f == 0]
+    Vc_f = _mean_bf16(Sv, N_f)
+    res = dict(fine_of_token=a_new, Kc_f=Kc_f, Vc_f=Vc_f, N_f=N_f, Sk_f=Sk, Sv_f=Sv)
+    if parent is not None:
+        cof = parent[order].astype(np.int32)
+        a_coarse = cof[a_new]
+        Skc, N_c = member_sums(Kb, a_coarse, kc)
+        Svc, _ = member_sums(Vb, a_coarse, kc)
+        Kc_c = _mean_bf16(Skc, N_c)
+        Kc_c[N_c == 0] = Cc_kmeans[N_c == 0]
+        Vc_c = _mean_bf16(Svc, N_c)
+        res.update(coarse_of_fine=cof, Kc_c=Kc_c, Vc_c=Vc_c, N_c=N_c)
+    return res
+
+
+def cluster_block(Kb, Vb, init_fine, init_coarse, iters, levels):
+    """k-means on one block's keys, then (two-level) k-means on the resulting fine centroids."""
+    Cf_km, a, _ = lloyd(Kb, init_fine, iters)
+    if levels == 2:
+        Cc_km, parent, _ = lloyd(Cf_km, init_coarse, iters)
+        return finalize_block(Kb, Vb, a, Cf_km, parent, len(init_coarse), Cc_km)
+    return finalize_block(Kb, Vb, a, Cf_km, None, 0, None)
+
+
+def _concat_blocks(K, V, levels, blocks, parts):
+    cl = dict(K=K, V=V, levels=levels, blocks=[dict(b) for b in blocks])
+    fot = np.zeros(K.shape[0], dtype=np.int32)
+    for b, p in zip(blocks, parts):
+        fot[b["t0"]:b["t1"]] = p["fine_of_token"] + b["f0"]
+    cl["fine_of_token"] = fot
+    for key in ("Kc_f", "Vc_f", "N_f"):
+        cl[key] = np.concatenate([p[key] for p in parts], axis=0)
+    if levels == 2:
+        cl["coarse_of_fine"] = np.concatenate([p["coarse_of_fine"] + b["c0"] for b, p in zip(blocks, parts)])
+        for key in ("Kc_c", "Vc_c", "N_c"):
+            cl[key] = np.concatenate([p[key] for p in parts], axis=0)
+    return cl
+
+
+def cluster_unit(K, V, blocks, init_fine, init_coarse, iters, levels):
+    """Build the clustered index of one unit.
+
+    blocks: from :func:`plan_blocks`.  init_fine: int32 [n_fine], block-local token indices of the
+    seeds, laid out block after block; init_coarse: int32 [n_coarse], block-local fine-cluster
+    indices of the coarse seeds (ignored for one level).
+    """
+    K, V = _f64(K), _f64(V)
+    parts = []
+    for b in blocks:
+        Kb, Vb = K[b["t0"]:b["t1"]], V[b["t0"]:b["t1"]]
+        fi = _i32(init_fine[b["f0"]:b["f1"]])
+        ci = _i32(init_coarse[b["c0"]:b["c1"]]) if levels == 2 else None
+        parts.append(cluster_block(Kb, Vb, fi, ci, iters, levels))
+    return _concat_blocks(K, V, levels, blocks, parts)
+
+
+def clustering_from_assignment(K, V, fine_of_token, n_fine, coarse_of_fine=None, n_coarse=0):
+    """Stored tables for a given assignment (single block, ids used as given): centroid = bf16(mean
+    of members); empty clusters get zero centroids and N = 0."""
+    K, V = _f64(K), _f64(V)
+    fot = _i32(fine_of_token)
+    Sk, N_f = member_sums(K, fot, n_fine)
+    Sv, _ = member_sums(V, fot, n_fine)
+    cl = dict(K=K, V=V, levels=1 if coarse_of_fine is None else 2, fine_of_token=fot,
+              Kc_f=_mean_bf16(Sk, N_f), Vc_f=_mean_bf16(Sv, N_f), N_f=N_f,
+              blocks=[dict(t0=0, t1=K.shape[0], f0=0, f1=n_fine, c0=0, c1=n_coarse)])
+    if coarse_of_fine is not None:
+        cof = _i32(coarse_of_fine)
+        ac = cof[fot]
+        Skc, N_c = member_sums(K, ac, n_coarse)
+        Svc, _ = member_sums(V, ac, n_coarse)
+        cl.update(coarse_of_fine=cof, Kc_c=_mean_bf16(Skc, N_c), Vc_c=_mean_bf16(Svc, N_c), N_c=N_c)
+    return cl
