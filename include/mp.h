@@ -1,0 +1,243 @@
+/*
+ * mp.h -- C ABI of the MI355X (gfx950) Multipole Attention decode library.
+ *
+ * The library implements, on one GPU, the decode hot path of Multipole Attention
+ * (arXiv 2506.13059): a clustered key/value index per (sequence, KV head), centroid scoring
+ * (coarse level, then fine level), budgeted selection of clusters, exact softmax attention over
+ * the selected clusters' keys, and one centroid term per remaining cluster inside the same softmax.
+ *
+ * General conventions
+ *   - "unit" u = b * n_kv_heads + kv_head.  Query head h uses KV head h / G with
+ *     G = n_q_heads / n_kv_heads (grouped-query attention, Sec. 3.1 last paragraph).
+ *   - Every pointer documented "device" is a device pointer the caller owns (for instance the
+ *     data_ptr() of a torch tensor); pointers documented "host" are ordinary host memory.
+ *     Tensors are dense, row-major, in the stated shape.  bf16 = bfloat16.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device work is
+ *     enqueued on it and the call returns without waiting for the GPU, unless stated otherwise.
+ *   - Every function returns an mp_status.  On any status other than MP_OK nothing has been
+ *     enqueued and the context is unchanged; mp_last_error() gives a readable message.
+ *     No C++ exception crosses this boundary.
+ *   - head_dim must be 128.  1 <= G <= 8.
+ *   - A context may be used from one host thread at a time; calls on the same context that
+ *     overlap on the GPU (different streams without ordering) race on its workspace.
+ */
+#ifndef MP_H_
+#define MP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mp_ctx mp_ctx;
+
+typedef enum {
+    MP_OK = 0,
+    MP_EINVAL = 1,    /* bad argument: null pointer, size out of range, unsupported shape      */
+    MP_ENOMEM = 2,    /* device or host allocation failed                                       */
+    MP_ESTATE = 3,    /* call order: decode / update / getters before an index exists           */
+    MP_ECAPACITY = 4, /* tokens or clusters beyond the capacities given at mp_create            */
+    MP_EHIP = 5       /* a HIP runtime call failed; the message carries hipGetErrorString       */
+} mp_status;
+
+typedef struct {
+    int32_t batch;         /* B >= 1                                                            */
+    int32_t n_q_heads;     /* Hq, multiple of n_kv_heads                                        */
+    int32_t n_kv_heads;    /* Hkv >= 1                                                          */
+    int32_t head_dim;      /* must be 128                                                       */
+    int32_t max_tokens;    /* capacity: clustered tokens per unit                               */
+    int32_t levels;        /* 1 = fine clusters only (Sec. 3.1-3.2), 2 = coarse + fine (Sec. 3.4) */
+    int32_t max_fine;      /* capacity: fine clusters per unit (<= 65536)                       */
+    int32_t max_coarse;    /* capacity: coarse clusters per unit (0 allowed when levels == 1)   */
+    int32_t block_w;       /* W of Sec. 3.3: clustering block length; 0 = one block             */
+    int32_t block_alpha;   /* alpha of Sec. 3.3: the last block holds alpha .. W+alpha-1 tokens */
+    int32_t max_tail;      /* capacity: unclustered newest tokens per unit passed to decode     */
+    float softmax_scale;   /* multiplies every q.k and q.centroid product; 0 => 1/sqrt(head_dim) */
+} mp_config;
+
+/* Create a context: allocates the clustered KV cache, the index tables and all workspaces on the
+ * current HIP device (sizes follow the capacities in cfg).  *out receives the context.
+ * Errors: MP_EINVAL (bad cfg, checked before any HIP call), MP_ENOMEM, MP_EHIP. */
+mp_status mp_create(const mp_config* cfg, mp_ctx** out);
+
+/* Free everything the context owns.  Synchronises the device first.  NULL is allowed. */
+void mp_destroy(mp_ctx* ctx);
+
+/* Message of the last failing call on this context (or, with ctx == NULL, of the last failing
+ * mp_create / context-free call on this thread).  Never NULL; valid until the next call. */
+const char* mp_last_error(const mp_ctx* ctx);
+
+/* Device bytes the context holds (cache + tables + workspace). */
+size_t mp_device_bytes(const mp_ctx* ctx);
+
+/* ---------------------------------------------------------------------------------------------
+ * Block plan (Sec. 3.3): clustering runs in blocks of block_w tokens; the last block holds the
+ * remaining block_alpha .. block_w+block_alpha-1 tokens (all tokens if there are fewer than
+ * block_w+block_alpha, or if block_w == 0).  n_fine / n_coarse (totals per unit) are split over
+ * the blocks by cumulative integer division: block [t0,t1) owns fine ids
+ * [n_fine*t0/n_tokens, n_fine*t1/n_tokens), coarse ids likewise.
+ *
+ * Writes up to max_blocks entries of 6 int32 {t0, t1, f0, f1, c0, c1} to `out` (host) and returns
+ * the number of blocks (also when out == NULL); returns -1 on invalid arguments.
+ * ------------------------------------------------------------------------------------------- */
+int32_t mp_plan_blocks(int32_t n_tokens, int32_t block_w, int32_t block_alpha, int32_t n_fine,
+                       int32_t n_coarse, int32_t* out, int32_t max_blocks);
+
+/* ---------------------------------------------------------------------------------------------
+ * mp_cluster_kv -- build the clustered index for tokens [0, n_tokens) of every unit
+ * (Sec. 3.1: k-means on the keys, key centroid = mean of the member keys; Sec. 3.2: value
+ * centroid = mean of the member values; Sec. 3.3: blockwise; Sec. 3.4: second level by k-means
+ * on the fine centroids).
+ *
+ *   k, v        device bf16 [B, Hkv, n_tokens, 128], read-only; not referenced after the enqueued
+ *               work has run (the context keeps its own cluster-contiguous copy).
+ *   n_fine      fine clusters per unit (total over blocks), 1 <= n_fine <= max_fine,
+ *               each block must get at least one and at most as many as it has tokens.
+ *   n_coarse    coarse clusters per unit (levels == 2; each block needs 1 <= count <= its fine
+ *               count); ignored when levels == 1.
+ *   iters       Lloyd iterations (>= 1) at each level, no early stop (Sec. 5.1 uses 10).
+ *   init_fine   host int32 [B*Hkv, n_fine]: seeds, block after block, each the index of a token
+ *               inside its block (distinct per block).  NULL: drawn from `seed`.
+ *   init_coarse host int32 [B*Hkv, n_coarse]: seeds of the coarse level, each the index of a fine
+ *               cluster inside its block, numbered as produced by the fine k-means (= position of
+ *               its seed in init_fine).  NULL: drawn from `seed`.
+ *
+ * Per block: centroids start at the seed keys; each iteration assigns every key to the nearest
+ * centroid (squared Euclidean distance in fp64, equal distances -> lowest index) and replaces each
+ * non-empty cluster's centroid by the bf16-rounded (nearest-even) fp64 mean of its members; empty
+ * clusters keep their centroid.  The coarse level repeats this with the fine centroids as points.
+ * Fine clusters are then renumbered so that the children of a coarse cluster are contiguous
+ * (stable in the old number), tokens are stored cluster after cluster (sequence order inside a
+ * cluster), and the stored tables hold, per cluster, N, bf16(mean key), bf16(mean value) (an empty
+ * cluster keeps its k-means centroid as key centroid and a zero value centroid).
+ *
+ * Errors: MP_EINVAL, MP_ECAPACITY (n_tokens > max_tokens, n_fine > max_fine, ...), MP_EHIP.
+ * Replaces any previous index of the context.
+ * ------------------------------------------------------------------------------------------- */
+mp_status mp_cluster_kv(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, int32_t n_fine,
+                        int32_t n_coarse, int32_t iters, uint64_t seed, const int32_t* init_fine,
+                        const int32_t* init_coarse, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * mp_set_clustering -- install an index from a given assignment instead of running k-means
+ * (same stored tables and layout as mp_cluster_kv; one block).
+ *
+ *   fine_of_token   device int32 [B*Hkv, n_tokens], values in [0, n_fine)
+ *   coarse_of_fine  device int32 [B*Hkv, n_fine], values in [0, n_coarse), NON-DECREASING in the
+ *                   fine id (children contiguous); NULL when levels == 1.
+ * Empty clusters get zero centroids and N = 0.  Out-of-range ids are undefined behaviour on the
+ * device side (they are not read back to be checked).
+ * ------------------------------------------------------------------------------------------- */
+mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens,
+                            const int32_t* fine_of_token, int32_t n_fine,
+                            const int32_t* coarse_of_fine, int32_t n_coarse, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * mp_update_clusters -- append n_new tokens per unit to the last block and refresh its clusters
+ * (Sec. 3.3: extra centroids sampled from the appended tokens, one-shot nearest-centroid
+ * assignment of the appended tokens with a running-mean update of the touched centroids, then a
+ * few full Lloyd iterations over the last block; when the last block reaches W+alpha tokens its
+ * first W tokens are split off and clustered as a block of their own).
+ *
+ *   k_new, v_new   device bf16 [B, Hkv, n_new, 128]
+ *   n_new_fine     fine clusters added to the last block, 0 <= n_new_fine <= n_new
+ *   n_new_coarse   coarse clusters added (levels == 2), 0 <= n_new_coarse <= n_new_fine
+ *   refine_iters   Lloyd iterations over the last block after the one-shot update (Sec. 5.1: 3)
+ *   split_iters    Lloyd iterations used for the two fresh clusterings at a split (Sec. 5.1: 10)
+ *   seeds          host int32, layout documented in DESIGN notes of mp_update_seed_count();
+ *                  NULL: drawn from `seed`.
+ * Errors: MP_ESTATE (no index yet), MP_ECAPACITY, MP_EINVAL, MP_EHIP.
+ * ------------------------------------------------------------------------------------------- */
+mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* v_new, int32_t n_new,
+                             int32_t n_new_fine, int32_t n_new_coarse, int32_t refine_iters,
+                             int32_t split_iters, uint64_t seed, const int32_t* seeds, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * mp_decode_attention -- one decode step for every unit (Eq. 1, Eq. 2, Sec. 3.4, Sec. 4).
+ *
+ *   q               device bf16 [B, Hq, 128]
+ *   k_tail, v_tail  device bf16 [B, Hkv, n_tail, 128]: newest tokens that are not clustered yet
+ *                   (the local buffer of Sec. 4); always attended exactly; NULL with n_tail == 0.
+ *   key_budget      keys of selected fine clusters per unit (>= 0; >= n_tokens => full attention;
+ *                   0 => every cluster enters through its centroid).  Tail tokens do not count.
+ *   coarse_budget   keys covered by the "promising" coarse clusters whose children are scored at
+ *                   the fine level (levels == 2; ignored otherwise).
+ *   flags           MP_DECODE_NO_MULTIPOLE drops the centroid terms of Eq. 2 (sparse attention
+ *                   over the retrieved keys only).
+ *   out             device bf16 [B, Hq, 128]
+ *   lse             device fp32 [B, Hq], natural log of the softmax denominator; may be NULL.
+ *
+ * Per unit: coarse logits l = scale*q.Kc for clusters with N > 0, Eq. 1 per head with the
+ * N-weighted denominator, averaged over the G heads of the group (ranked through its logarithm);
+ * clusters ordered by that key (ties: lower id first) are taken while the running token count
+ * stays <= the budget, stopping at the first that does not fit; the fine level repeats this over
+ * the children of the promising coarse clusters, with the Eq. 1 denominator running over those
+ * children and the unpromising coarse clusters.  The output is one softmax over the exact keys of
+ * the selected clusters, the tail, and N*exp(l) terms carrying the value centroids of all other
+ * clusters (unselected candidates at the fine level, unpromising clusters at the coarse level).
+ * Centroid logits and rank keys are evaluated in fp64; exact attention uses bf16 inputs with
+ * fp32 accumulation.
+ *
+ * Allocates nothing, never waits for the GPU, reads nothing back.
+ * Errors: MP_ESTATE (no index), MP_EINVAL (null, negative sizes), MP_ECAPACITY (n_tail > max_tail).
+ * ------------------------------------------------------------------------------------------- */
+#define MP_DECODE_NO_MULTIPOLE 1u
+mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, const void* v_tail,
+                              int32_t n_tail, int32_t key_budget, int32_t coarse_budget,
+                              uint32_t flags, void* out, float* lse, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Introspection (for parity tests and accounting).  Outputs are device buffers of the stated
+ * shape; NULL outputs are skipped.  Work is enqueued on `stream`.
+ * ------------------------------------------------------------------------------------------- */
+
+/* Sizes of the current index (host values, no GPU work). */
+mp_status mp_get_sizes(const mp_ctx* ctx, int32_t* n_tokens, int32_t* n_fine, int32_t* n_coarse,
+                       int32_t* n_blocks);
+
+/* fine_of_token int32 [U, n_tokens] in sequence order; coarse_of_fine int32 [U, n_fine]. */
+mp_status mp_get_assignments(mp_ctx* ctx, int32_t* fine_of_token, int32_t* coarse_of_fine, void* stream);
+
+/* level 0 = fine, 1 = coarse.  kc, vc: bf16 [U, n, 128]; n_members: int32 [U, n]. */
+mp_status mp_get_centroids(mp_ctx* ctx, int32_t level, void* kc, void* vc, int32_t* n_members, void* stream);
+
+/* Selection of the last decode call: fine_selected uint8 [U, n_fine], coarse_promising uint8
+ * [U, n_coarse]; rank keys of the last call (fp64, NaN where a cluster took no part):
+ * r_fine [U, n_fine], r_coarse [U, n_coarse]. */
+mp_status mp_get_selection(mp_ctx* ctx, uint8_t* fine_selected, uint8_t* coarse_promising,
+                           double* r_fine, double* r_coarse, void* stream);
+
+/* Per-unit counters of the last decode call, int32 [U, 4]:
+ * {keys attended exactly (selected + tail), fine centroids scored, coarse centroids scored,
+ *  centroid terms entering the softmax}. */
+mp_status mp_get_counters(mp_ctx* ctx, int32_t* counters, void* stream);
+
+/* Cluster-contiguous cache as stored: k_perm, v_perm bf16 [U, n_tokens, 128]; perm int32
+ * [U, n_tokens] (sequence index of each stored row); fine_start int32 [U, n_fine+1] (first stored
+ * row of each fine cluster). */
+mp_status mp_get_layout(mp_ctx* ctx, void* k_perm, void* v_perm, int32_t* perm, int32_t* fine_start,
+                        void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Dense bf16 decode attention over all n keys (the comparison point: split-KV streaming pass and
+ * an online-softmax merge, Sec. 4 / FlashDecoding), using the same inner loop as the exact pass
+ * of mp_decode_attention.
+ *
+ *   q bf16 [B, Hq, 128]; k, v bf16 [B, Hkv, n, 128]; out bf16 [B, Hq, 128]; lse fp32 [B, Hq] or NULL
+ *   workspace   device buffer of at least mp_dense_workspace_bytes(B, Hq, Hkv, n) bytes
+ * Context-free; errors are reported through mp_last_error(NULL).
+ * ------------------------------------------------------------------------------------------- */
+size_t mp_dense_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t n);
+mp_status mp_dense_attention(const void* q, const void* k, const void* v, int32_t batch,
+                             int32_t n_q_heads, int32_t n_kv_heads, int32_t n, float softmax_scale,
+                             void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Library version string. */
+const char* mp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MP_H_ */

@@ -1,0 +1,553 @@
+// C-ABI layer: argument checks, error strings, memory ownership, launch sequencing.
+#include "../../include/mp.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "mp_ctx.h"
+#include "mp_internal.h"
+
+using namespace mp;
+
+namespace mp {
+// implemented in mp_cluster.hip
+mp_status cluster_kv_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, int32_t n_fine,
+                          int32_t n_coarse, int32_t iters, uint64_t seed, const int32_t* init_fine,
+                          const int32_t* init_coarse, hipStream_t s);
+mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* v_new, int32_t n_new, int32_t n_new_fine,
+                               int32_t n_new_coarse, int32_t refine_iters, int32_t split_iters, uint64_t seed,
+                               const int32_t* seeds, hipStream_t s);
+
+thread_local std::string g_err;   // errors of context-free calls
+
+mp_status fail(mp_ctx* ctx, mp_status st, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf;
+    else g_err = buf;
+    return st;
+}
+
+// Rows per workgroup of the value pass for a stream of n rows per unit: large enough that the
+// partials stay a small fraction of the traffic, small enough that there are many workgroups.
+int pick_chunk_rows(long long n_rows_per_unit, int n_units)
+{
+    int cr = kChunkRowsMin;
+    while (cr < 4096 && n_units * ((n_rows_per_unit + cr - 1) / cr) > 8192) cr *= 2;
+    return cr;
+}
+
+// Build the stored layout and tables from ctx->fot (fine id of each token) and ctx->cof (coarse id
+// of each fine cluster, non-decreasing), reading the caller's K / V in sequence order.
+// key_fallback: Kc already holds the key centroids to keep for empty clusters (else zeros).
+mp_status finalize_index(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, int32_t n_fine,
+                         int32_t n_coarse, const std::vector<BlockPlan>& blocks, bool key_fallback, hipStream_t s)
+{
+#define MP_HIPX(expr)                                                                              \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) return fail(ctx, MP_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+    const int U = ctx->U;
+    const long long Ncap = ctx->Ncap, tab = ctx->tab_rows;
+    const int nb = (int)blocks.size();
+    std::vector<int32_t> bd(4 * (size_t)nb);
+    int max_kf = 0;
+    for (int b = 0; b < nb; ++b) {
+        bd[4 * b + 0] = blocks[b].t0; bd[4 * b + 1] = blocks[b].t1;
+        bd[4 * b + 2] = blocks[b].f0; bd[4 * b + 3] = blocks[b].f1;
+        max_kf = std::max(max_kf, blocks[b].f1 - blocks[b].f0);
+    }
+    MP_HIPX(hipMemcpyAsync(ctx->blocks_dev, bd.data(), bd.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
+    // fine member lists = stored order
+    MP_HIPX(launch_fill_i32(ctx->km_cnt, (long long)U * tab, 0, s));
+    MP_HIPX(launch_histogram(ctx->fot, Ncap, n_tokens, U, ctx->km_cnt, tab, s));
+    MP_HIPX(launch_exclusive_scan(ctx->km_cnt, tab, n_fine, U, ctx->fstart, ctx->Fcap + 1, s));
+    MP_HIPX(launch_member_lists(ctx->fot, Ncap, ctx->blocks_dev, nb, max_kf, U, ctx->fstart, ctx->Fcap + 1,
+                                ctx->perm, Ncap, s));
+    MP_HIPX(launch_gather_rows(k, v, n_tokens, ctx->perm, Ncap, n_tokens, U, ctx->Kp, ctx->Vp, Ncap, 0, s));
+    // fine tables
+    MP_HIPX(launch_cluster_means((const uint16_t*)k, n_tokens, ctx->perm, Ncap, ctx->fstart, ctx->Fcap + 1, n_fine, U,
+                                 ctx->Kc, tab, 0, key_fallback ? ctx->Kc : nullptr, tab, nullptr, 0, 0, s));
+    MP_HIPX(launch_cluster_means((const uint16_t*)v, n_tokens, ctx->perm, Ncap, ctx->fstart, ctx->Fcap + 1, n_fine, U,
+                                 ctx->Vc, tab, 0, nullptr, 0, ctx->Ncl, tab, 0, s));
+    if (ctx->cfg.levels == 2) {
+        MP_HIPX(launch_coarse_start(ctx->cof, ctx->Fcap, n_fine, n_coarse, U, ctx->cstart, ctx->Ccap + 1, s));
+        MP_HIPX(launch_coarse_row_start(ctx->cstart, ctx->Ccap + 1, ctx->fstart, ctx->Fcap + 1, n_coarse, U,
+                                        ctx->crow, ctx->Ccap + 1, s));
+        MP_HIPX(launch_cluster_means(ctx->Kp, Ncap, nullptr, 0, ctx->crow, ctx->Ccap + 1, n_coarse, U, ctx->Kc, tab,
+                                     ctx->Fcap, key_fallback ? ctx->Kc + (long long)ctx->Fcap * kHeadDimHost : nullptr,
+                                     tab, nullptr, 0, 0, s));
+        MP_HIPX(launch_cluster_means(ctx->Vp, Ncap, nullptr, 0, ctx->crow, ctx->Ccap + 1, n_coarse, U, ctx->Vc, tab,
+                                     ctx->Fcap, nullptr, 0, ctx->Ncl, tab, ctx->Fcap, s));
+    }
+    // keep the last block in sequence order for the online update
+    const BlockPlan& lb = blocks.back();
+    const int nlast = lb.t1 - lb.t0;
+    if (nlast <= ctx->FBcap) {
+        const size_t row = kHeadDimHost * sizeof(uint16_t);
+        MP_HIPX(hipMemcpy2DAsync(ctx->Kfb, (size_t)ctx->FBcap * row, (const char*)k + (size_t)lb.t0 * row,
+                                 (size_t)n_tokens * row, (size_t)nlast * row, U, hipMemcpyDeviceToDevice, s));
+        MP_HIPX(hipMemcpy2DAsync(ctx->Vfb, (size_t)ctx->FBcap * row, (const char*)v + (size_t)lb.t0 * row,
+                                 (size_t)n_tokens * row, (size_t)nlast * row, U, hipMemcpyDeviceToDevice, s));
+    }
+    ctx->n_tokens = n_tokens;
+    ctx->n_fine = n_fine;
+    ctx->n_coarse = ctx->cfg.levels == 2 ? n_coarse : 0;
+    ctx->blocks = blocks;
+    ctx->has_index = true;
+    ctx->decoded = false;
+    return MP_OK;
+#undef MP_HIPX
+}
+
+}  // namespace mp
+
+namespace {
+
+#define MP_HIP(ctx, expr)                                                                           \
+    do {                                                                                            \
+        hipError_t e_ = (expr);                                                                     \
+        if (e_ != hipSuccess) return fail((ctx), MP_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+template <typename T>
+hipError_t dev_alloc(mp_ctx* ctx, T** p, size_t count)
+{
+    const size_t bytes = std::max<size_t>(count, 1) * sizeof(T);
+    void* q = nullptr;
+    hipError_t e = hipMalloc(&q, bytes);
+    if (e != hipSuccess) return e;
+    ctx->allocs.push_back(q);
+    ctx->device_bytes += bytes;
+    *p = (T*)q;
+    return hipSuccess;
+}
+
+void free_all(mp_ctx* ctx)
+{
+    for (void* p : ctx->allocs) (void)hipFree(p);
+    ctx->allocs.clear();
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mp_version(void) { return "mp-gfx950 0.1"; }
+
+const char* mp_last_error(const mp_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+size_t mp_device_bytes(const mp_ctx* ctx) { return ctx ? ctx->device_bytes : 0; }
+
+int32_t mp_plan_blocks(int32_t n_tokens, int32_t block_w, int32_t block_alpha, int32_t n_fine, int32_t n_coarse,
+                       int32_t* out, int32_t max_blocks)
+{
+    if (n_tokens <= 0 || block_w < 0 || block_alpha < 0 || n_fine < 0 || n_coarse < 0) return -1;
+    std::vector<BlockPlan> b = plan_blocks(n_tokens, block_w, block_alpha, n_fine, n_coarse);
+    if (out) {
+        for (int i = 0; i < (int)b.size() && i < max_blocks; ++i) {
+            out[6 * i + 0] = b[i].t0; out[6 * i + 1] = b[i].t1;
+            out[6 * i + 2] = b[i].f0; out[6 * i + 3] = b[i].f1;
+            out[6 * i + 4] = b[i].c0; out[6 * i + 5] = b[i].c1;
+        }
+    }
+    return (int32_t)b.size();
+}
+
+mp_status mp_create(const mp_config* cfg, mp_ctx** out)
+{
+    if (!cfg || !out) return fail(nullptr, MP_EINVAL, "mp_create: null pointer");
+    *out = nullptr;
+    const mp_config& c = *cfg;
+    if (c.batch < 1 || c.n_kv_heads < 1 || c.n_q_heads < 1 || c.n_q_heads % c.n_kv_heads)
+        return fail(nullptr, MP_EINVAL, "mp_create: bad head counts B=%d Hq=%d Hkv=%d", c.batch, c.n_q_heads,
+                    c.n_kv_heads);
+    if (c.head_dim != kHeadDimHost) return fail(nullptr, MP_EINVAL, "mp_create: head_dim must be 128, got %d", c.head_dim);
+    const int G = c.n_q_heads / c.n_kv_heads;
+    if (G > 8) return fail(nullptr, MP_EINVAL, "mp_create: group size %d > 8 is not supported", G);
+    if (c.levels != 1 && c.levels != 2) return fail(nullptr, MP_EINVAL, "mp_create: levels must be 1 or 2");
+    if (c.max_tokens < 1) return fail(nullptr, MP_EINVAL, "mp_create: max_tokens must be >= 1");
+    if (c.max_fine < 1 || c.max_fine > kMaxClustersPerLevel)
+        return fail(nullptr, MP_EINVAL, "mp_create: max_fine must be in [1, %d]", kMaxClustersPerLevel);
+    if (c.levels == 2 && (c.max_coarse < 1 || c.max_coarse > c.max_fine))
+        return fail(nullptr, MP_EINVAL, "mp_create: max_coarse must be in [1, max_fine] when levels == 2");
+    if (c.levels == 1 && c.max_coarse < 0) return fail(nullptr, MP_EINVAL, "mp_create: max_coarse < 0");
+    if (c.block_w < 0 || c.block_alpha < 0 || (c.block_w > 0 && c.block_alpha > c.block_w))
+        return fail(nullptr, MP_EINVAL, "mp_create: need block_w >= 0 and 0 <= block_alpha <= block_w");
+    if (c.max_tail < 0) return fail(nullptr, MP_EINVAL, "mp_create: max_tail < 0");
+    if (!(c.softmax_scale >= 0.f)) return fail(nullptr, MP_EINVAL, "mp_create: softmax_scale must be >= 0");
+    if ((long long)c.batch * c.n_kv_heads > 65535) return fail(nullptr, MP_EINVAL, "mp_create: more than 65535 units");
+
+    mp_ctx* ctx = new (std::nothrow) mp_ctx();
+    if (!ctx) return fail(nullptr, MP_ENOMEM, "mp_create: host allocation failed");
+    ctx->cfg = c;
+    ctx->U = c.batch * c.n_kv_heads;
+    ctx->G = G;
+    ctx->scale_d = c.softmax_scale > 0.f ? (double)c.softmax_scale : 1.0 / std::sqrt((double)kHeadDimHost);
+    ctx->scale = (float)ctx->scale_d;
+    ctx->Ncap = c.max_tokens;
+    ctx->Fcap = c.max_fine;
+    ctx->Ccap = c.levels == 2 ? c.max_coarse : 0;
+    ctx->Tcap = c.max_tail;
+    ctx->tab_rows = (long long)ctx->Fcap + ctx->Ccap;
+    ctx->FBcap = c.block_w > 0 ? std::min<long long>(c.max_tokens, (long long)c.block_w + c.block_alpha) : c.max_tokens;
+    ctx->max_blocks = c.block_w > 0 ? c.max_tokens / c.block_w + 2 : 2;
+    ctx->Pcap = ceil_div(ctx->Ncap, kChunkRowsMin) + ceil_div(ctx->Tcap, kChunkRowsMin) +
+                ceil_div(ctx->tab_rows, kChunkRowsMin) + 1;
+
+    hipError_t e = hipGetDevice(&ctx->device);
+    const size_t U = ctx->U, N = ctx->Ncap, F = ctx->Fcap, Cc = std::max(ctx->Ccap, 1), T = ctx->tab_rows, D = kHeadDimHost;
+#define A(ptr, count) if (e == hipSuccess) e = dev_alloc(ctx, &ctx->ptr, (count))
+    A(Kp, U * N * D); A(Vp, U * N * D); A(perm, U * N); A(fot, U * N);
+    A(fstart, U * (F + 1)); A(cof, U * F); A(cstart, U * (Cc + 1)); A(crow, U * (Cc + 1));
+    A(Kc, U * T * D); A(Vc, U * T * D); A(Ncl, U * T);
+    A(Kfb, U * (size_t)ctx->FBcap * D); A(Vfb, U * (size_t)ctx->FBcap * D);
+    A(km_assign, U * N); A(km_list, U * N); A(km_cnt, U * T); A(km_start, U * (T + 2));
+    A(km_Cf, U * F * D); A(km_Cc, U * Cc * D); A(km_parent, U * F); A(km_plist, U * F); A(km_newid, U * F);
+    A(km_seed_f, U * F); A(km_seed_c, U * Cc); A(blocks_dev, 3 * (size_t)ctx->max_blocks * 4);
+    A(lg_c, U * G * Cc); A(lg_f, U * G * F); A(r_c, U * Cc); A(r_f, U * F); A(flag_c, U * Cc); A(flag_f, U * F);
+    A(cand, U * F); A(n_cand, U); A(unprom_lse, U * G); A(rows, U * N); A(n_rows, U);
+    A(mp_rows, U * T); A(mp_scores, U * T * G); A(n_mp, U); A(counters, U * 4);
+    A(partials, U * (size_t)ctx->Pcap * G * kPartStride);
+#undef A
+    if (e == hipSuccess) e = hipMemset(ctx->counters, 0, U * 4 * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMemset(ctx->n_mp, 0, U * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMemset(ctx->n_rows, 0, U * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMemset(ctx->n_cand, 0, U * sizeof(int32_t));
+    if (e != hipSuccess) {
+        const mp_status st = (e == hipErrorOutOfMemory) ? MP_ENOMEM : MP_EHIP;
+        fail(nullptr, st, "mp_create: %s (after %zu bytes)", hipGetErrorString(e), ctx->device_bytes);
+        free_all(ctx);
+        delete ctx;
+        return st;
+    }
+    *out = ctx;
+    return MP_OK;
+}
+
+void mp_destroy(mp_ctx* ctx)
+{
+    if (!ctx) return;
+    (void)hipDeviceSynchronize();
+    free_all(ctx);
+    delete ctx;
+}
+
+mp_status mp_cluster_kv(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, int32_t n_fine, int32_t n_coarse,
+                        int32_t iters, uint64_t seed, const int32_t* init_fine, const int32_t* init_coarse,
+                        void* stream)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_cluster_kv: null context");
+    if (!k || !v) return fail(ctx, MP_EINVAL, "mp_cluster_kv: null k/v");
+    if (n_tokens < 1 || n_fine < 1 || iters < 1) return fail(ctx, MP_EINVAL, "mp_cluster_kv: n_tokens, n_fine, iters must be >= 1");
+    if (n_tokens > ctx->Ncap) return fail(ctx, MP_ECAPACITY, "mp_cluster_kv: n_tokens %d > max_tokens %d", n_tokens, ctx->Ncap);
+    if (n_fine > ctx->Fcap) return fail(ctx, MP_ECAPACITY, "mp_cluster_kv: n_fine %d > max_fine %d", n_fine, ctx->Fcap);
+    if (ctx->cfg.levels == 2) {
+        if (n_coarse < 1) return fail(ctx, MP_EINVAL, "mp_cluster_kv: n_coarse must be >= 1 with two levels");
+        if (n_coarse > ctx->Ccap) return fail(ctx, MP_ECAPACITY, "mp_cluster_kv: n_coarse %d > max_coarse %d", n_coarse, ctx->Ccap);
+    } else {
+        n_coarse = 0;
+    }
+    const std::vector<BlockPlan> blocks = plan_blocks(n_tokens, ctx->cfg.block_w, ctx->cfg.block_alpha, n_fine, n_coarse);
+    if ((int)blocks.size() > ctx->max_blocks) return fail(ctx, MP_ECAPACITY, "mp_cluster_kv: too many blocks");
+    for (const BlockPlan& b : blocks) {
+        const int kf = b.f1 - b.f0, kc = b.c1 - b.c0, nt = b.t1 - b.t0;
+        if (kf < 1 || kf > nt) return fail(ctx, MP_EINVAL, "mp_cluster_kv: block [%d,%d) gets %d fine clusters", b.t0, b.t1, kf);
+        if (ctx->cfg.levels == 2 && (kc < 1 || kc > kf))
+            return fail(ctx, MP_EINVAL, "mp_cluster_kv: block [%d,%d) gets %d coarse clusters for %d fine", b.t0, b.t1, kc, kf);
+    }
+    const int U = ctx->U;
+    if (init_fine)
+        for (int u = 0; u < U; ++u)
+            for (const BlockPlan& b : blocks)
+                for (int f = b.f0; f < b.f1; ++f) {
+                    const int32_t t = init_fine[(size_t)u * n_fine + f];
+                    if (t < 0 || t >= b.t1 - b.t0) return fail(ctx, MP_EINVAL, "mp_cluster_kv: init_fine[%d][%d] = %d out of its block", u, f, t);
+                }
+    if (init_coarse && ctx->cfg.levels == 2)
+        for (int u = 0; u < U; ++u)
+            for (const BlockPlan& b : blocks)
+                for (int c = b.c0; c < b.c1; ++c) {
+                    const int32_t f = init_coarse[(size_t)u * n_coarse + c];
+                    if (f < 0 || f >= b.f1 - b.f0) return fail(ctx, MP_EINVAL, "mp_cluster_kv: init_coarse[%d][%d] = %d out of its block", u, c, f);
+                }
+    return cluster_kv_impl(ctx, k, v, n_tokens, n_fine, n_coarse, iters, seed, init_fine, init_coarse, (hipStream_t)stream);
+}
+
+mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, const int32_t* fine_of_token,
+                            int32_t n_fine, const int32_t* coarse_of_fine, int32_t n_coarse, void* stream)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_set_clustering: null context");
+    if (!k || !v || !fine_of_token) return fail(ctx, MP_EINVAL, "mp_set_clustering: null pointer");
+    if (n_tokens < 1 || n_fine < 1) return fail(ctx, MP_EINVAL, "mp_set_clustering: n_tokens and n_fine must be >= 1");
+    if (n_tokens > ctx->Ncap) return fail(ctx, MP_ECAPACITY, "mp_set_clustering: n_tokens %d > max_tokens %d", n_tokens, ctx->Ncap);
+    if (n_fine > ctx->Fcap) return fail(ctx, MP_ECAPACITY, "mp_set_clustering: n_fine %d > max_fine %d", n_fine, ctx->Fcap);
+    if (ctx->cfg.levels == 2) {
+        if (!coarse_of_fine || n_coarse < 1) return fail(ctx, MP_EINVAL, "mp_set_clustering: two levels need coarse_of_fine and n_coarse >= 1");
+        if (n_coarse > ctx->Ccap) return fail(ctx, MP_ECAPACITY, "mp_set_clustering: n_coarse %d > max_coarse %d", n_coarse, ctx->Ccap);
+    } else {
+        n_coarse = 0;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const int U = ctx->U;
+    MP_HIP(ctx, hipMemcpy2DAsync(ctx->fot, (size_t)ctx->Ncap * 4, fine_of_token, (size_t)n_tokens * 4, (size_t)n_tokens * 4, U,
+                                 hipMemcpyDeviceToDevice, s));
+    if (ctx->cfg.levels == 2)
+        MP_HIP(ctx, hipMemcpy2DAsync(ctx->cof, (size_t)ctx->Fcap * 4, coarse_of_fine, (size_t)n_fine * 4, (size_t)n_fine * 4, U,
+                                     hipMemcpyDeviceToDevice, s));
+    std::vector<BlockPlan> blocks(1);
+    blocks[0] = BlockPlan{0, n_tokens, 0, n_fine, 0, n_coarse};
+    return finalize_index(ctx, k, v, n_tokens, n_fine, n_coarse, blocks, false, s);
+}
+
+mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* v_new, int32_t n_new, int32_t n_new_fine,
+                             int32_t n_new_coarse, int32_t refine_iters, int32_t split_iters, uint64_t seed,
+                             const int32_t* seeds, void* stream)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_update_clusters: null context");
+    if (!ctx->has_index) return fail(ctx, MP_ESTATE, "mp_update_clusters: no index yet (call mp_cluster_kv first)");
+    if (!k_new || !v_new) return fail(ctx, MP_EINVAL, "mp_update_clusters: null k_new/v_new");
+    if (n_new < 1 || n_new_fine < 0 || n_new_fine > n_new || refine_iters < 0 || split_iters < 1)
+        return fail(ctx, MP_EINVAL, "mp_update_clusters: bad counts n_new=%d n_new_fine=%d refine=%d split=%d", n_new, n_new_fine,
+                    refine_iters, split_iters);
+    if (ctx->cfg.levels == 2 && (n_new_coarse < 0 || n_new_coarse > n_new_fine))
+        return fail(ctx, MP_EINVAL, "mp_update_clusters: n_new_coarse must be in [0, n_new_fine]");
+    return update_clusters_impl(ctx, k_new, v_new, n_new, n_new_fine, ctx->cfg.levels == 2 ? n_new_coarse : 0, refine_iters,
+                                split_iters, seed, seeds, (hipStream_t)stream);
+}
+
+mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, const void* v_tail, int32_t n_tail,
+                              int32_t key_budget, int32_t coarse_budget, uint32_t flags, void* out, float* lse, void* stream)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_decode_attention: null context");
+    if (!ctx->has_index) return fail(ctx, MP_ESTATE, "mp_decode_attention: no index yet (call mp_cluster_kv first)");
+    if (!q || !out) return fail(ctx, MP_EINVAL, "mp_decode_attention: null q/out");
+    if (n_tail < 0 || key_budget < 0 || coarse_budget < 0) return fail(ctx, MP_EINVAL, "mp_decode_attention: negative size or budget");
+    if (n_tail > 0 && (!k_tail || !v_tail)) return fail(ctx, MP_EINVAL, "mp_decode_attention: null tail with n_tail > 0");
+    if (n_tail > ctx->Tcap) return fail(ctx, MP_ECAPACITY, "mp_decode_attention: n_tail %d > max_tail %d", n_tail, ctx->Tcap);
+    if (flags & ~MP_DECODE_NO_MULTIPOLE) return fail(ctx, MP_EINVAL, "mp_decode_attention: unknown flags 0x%x", flags);
+    hipStream_t s = (hipStream_t)stream;
+    const int U = ctx->U, G = ctx->G;
+    const bool two = ctx->cfg.levels == 2;
+    const int use_mp = (flags & MP_DECODE_NO_MULTIPOLE) ? 0 : 1;
+
+    ScoreParams sp{};
+    sp.q = (const uint16_t*)q; sp.Kc = ctx->Kc; sp.N = ctx->Ncl; sp.tab_rows = ctx->tab_rows;
+    sp.scale = ctx->scale_d; sp.G = G; sp.U = U;
+    sp.mp_rows = ctx->mp_rows; sp.mp_scores = ctx->mp_scores; sp.mp_stride = ctx->tab_rows; sp.n_mp = ctx->n_mp;
+    sp.use_mp = use_mp; sp.counters = ctx->counters; sp.n_tail = n_tail;
+    if (two) {
+        ScoreParams c = sp;
+        c.coarse = 1; c.row_off = ctx->Fcap; c.cand = nullptr; c.n_cand_dev = nullptr; c.n_cand_fixed = ctx->n_coarse;
+        c.budget = coarse_budget; c.extra_lse = nullptr;
+        c.lg = ctx->lg_c; c.lg_stride = std::max(ctx->Ccap, 1); c.r_out = ctx->r_c; c.r_stride = std::max(ctx->Ccap, 1);
+        c.flag_out = ctx->flag_c;
+        c.cstart = ctx->cstart; c.cstart_stride = ctx->Ccap + 1; c.cand_out = ctx->cand; c.cand_out_stride = ctx->Fcap;
+        c.n_cand_out = ctx->n_cand; c.unprom_lse_out = ctx->unprom_lse; c.mp_append = 0;
+        c.smem_cap = ctx->n_coarse;
+        MP_HIP(ctx, launch_score_select(c, s));
+    }
+    {
+        ScoreParams f = sp;
+        f.coarse = 0; f.row_off = 0;
+        f.cand = two ? ctx->cand : nullptr; f.cand_stride = ctx->Fcap;
+        f.n_cand_dev = two ? ctx->n_cand : nullptr; f.n_cand_fixed = ctx->n_fine;
+        f.budget = key_budget; f.extra_lse = two ? ctx->unprom_lse : nullptr;
+        f.lg = ctx->lg_f; f.lg_stride = ctx->Fcap; f.r_out = ctx->r_f; f.r_stride = ctx->Fcap; f.flag_out = ctx->flag_f;
+        f.fstart = ctx->fstart; f.fstart_stride = ctx->Fcap + 1; f.rows_out = ctx->rows; f.rows_stride = ctx->Ncap;
+        f.n_rows_out = ctx->n_rows; f.mp_append = two ? 1 : 0;
+        f.smem_cap = ctx->n_fine;
+        MP_HIP(ctx, launch_score_select(f, s));
+    }
+
+    ValuePassParams vp{};
+    vp.q = (const uint16_t*)q;
+    vp.partials = ctx->partials;
+    vp.n_units = U;
+    vp.scale_log2e = (float)(ctx->scale_d * 1.4426950408889634);
+    const int main_max = std::min(key_budget, ctx->n_tokens);
+    vp.chunk_rows = pick_chunk_rows(std::max(main_max, 1), U);
+    int ns = 0, chunk0 = 0;
+    if (main_max > 0) {
+        RowSource& r = vp.src[ns++];
+        r.K = ctx->Kp; r.V = ctx->Vp; r.unit_rows = ctx->Ncap; r.rows = ctx->rows; r.rows_stride = ctx->Ncap;
+        r.count_dev = ctx->n_rows; r.count_max = main_max; r.scores = nullptr; r.chunk0 = chunk0;
+        r.n_chunks = ceil_div(main_max, vp.chunk_rows); chunk0 += r.n_chunks;
+    }
+    if (n_tail > 0) {
+        RowSource& r = vp.src[ns++];
+        r.K = (const uint16_t*)k_tail; r.V = (const uint16_t*)v_tail; r.unit_rows = n_tail; r.rows = nullptr; r.rows_stride = 0;
+        r.count_dev = nullptr; r.count_max = n_tail; r.scores = nullptr; r.chunk0 = chunk0;
+        r.n_chunks = ceil_div(n_tail, vp.chunk_rows); chunk0 += r.n_chunks;
+    }
+    if (use_mp) {
+        const int mp_max = ctx->n_fine + ctx->n_coarse;
+        RowSource& r = vp.src[ns++];
+        r.K = nullptr; r.V = ctx->Vc; r.unit_rows = ctx->tab_rows; r.rows = ctx->mp_rows; r.rows_stride = ctx->tab_rows;
+        r.count_dev = ctx->n_mp; r.count_max = mp_max; r.scores = ctx->mp_scores; r.chunk0 = chunk0;
+        r.n_chunks = ceil_div(mp_max, vp.chunk_rows); chunk0 += r.n_chunks;
+    }
+    vp.n_sources = ns;
+    vp.chunks_per_unit = chunk0;
+    if (chunk0 > ctx->Pcap) return fail(ctx, MP_ECAPACITY, "mp_decode_attention: %d chunks > workspace %d", chunk0, ctx->Pcap);
+    if (chunk0 > 0) MP_HIP(ctx, launch_value_pass(vp, G, s));
+    MP_HIP(ctx, launch_merge(ctx->partials, U, chunk0, G, (uint16_t*)out, lse, s));
+    ctx->decoded = true;
+    return MP_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Introspection
+// ------------------------------------------------------------------------------------------------
+mp_status mp_get_sizes(const mp_ctx* ctx, int32_t* n_tokens, int32_t* n_fine, int32_t* n_coarse, int32_t* n_blocks)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_get_sizes: null context");
+    if (!ctx->has_index) return fail(const_cast<mp_ctx*>(ctx), MP_ESTATE, "mp_get_sizes: no index yet");
+    if (n_tokens) *n_tokens = ctx->n_tokens;
+    if (n_fine) *n_fine = ctx->n_fine;
+    if (n_coarse) *n_coarse = ctx->n_coarse;
+    if (n_blocks) *n_blocks = (int32_t)ctx->blocks.size();
+    return MP_OK;
+}
+
+mp_status mp_get_assignments(mp_ctx* ctx, int32_t* fine_of_token, int32_t* coarse_of_fine, void* stream)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_get_assignments: null context");
+    if (!ctx->has_index) return fail(ctx, MP_ESTATE, "mp_get_assignments: no index yet");
+    hipStream_t s = (hipStream_t)stream;
+    if (fine_of_token)
+        MP_HIP(ctx, hipMemcpy2DAsync(fine_of_token, (size_t)ctx->n_tokens * 4, ctx->fot, (size_t)ctx->Ncap * 4,
+                                     (size_t)ctx->n_tokens * 4, ctx->U, hipMemcpyDeviceToDevice, s));
+    if (coarse_of_fine && ctx->cfg.levels == 2)
+        MP_HIP(ctx, hipMemcpy2DAsync(coarse_of_fine, (size_t)ctx->n_fine * 4, ctx->cof, (size_t)ctx->Fcap * 4,
+                                     (size_t)ctx->n_fine * 4, ctx->U, hipMemcpyDeviceToDevice, s));
+    return MP_OK;
+}
+
+mp_status mp_get_centroids(mp_ctx* ctx, int32_t level, void* kc, void* vc, int32_t* n_members, void* stream)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_get_centroids: null context");
+    if (!ctx->has_index) return fail(ctx, MP_ESTATE, "mp_get_centroids: no index yet");
+    if (level != 0 && !(level == 1 && ctx->cfg.levels == 2)) return fail(ctx, MP_EINVAL, "mp_get_centroids: no level %d", level);
+    hipStream_t s = (hipStream_t)stream;
+    const int n = level == 0 ? ctx->n_fine : ctx->n_coarse;
+    const size_t off = level == 0 ? 0 : (size_t)ctx->Fcap;
+    const size_t row = kHeadDimHost * 2;
+    if (kc)
+        MP_HIP(ctx, hipMemcpy2DAsync(kc, n * row, (const char*)ctx->Kc + off * row, (size_t)ctx->tab_rows * row, n * row, ctx->U,
+                                     hipMemcpyDeviceToDevice, s));
+    if (vc)
+        MP_HIP(ctx, hipMemcpy2DAsync(vc, n * row, (const char*)ctx->Vc + off * row, (size_t)ctx->tab_rows * row, n * row, ctx->U,
+                                     hipMemcpyDeviceToDevice, s));
+    if (n_members)
+        MP_HIP(ctx, hipMemcpy2DAsync(n_members, (size_t)n * 4, ctx->Ncl + off, (size_t)ctx->tab_rows * 4, (size_t)n * 4, ctx->U,
+                                     hipMemcpyDeviceToDevice, s));
+    return MP_OK;
+}
+
+mp_status mp_get_selection(mp_ctx* ctx, uint8_t* fine_selected, uint8_t* coarse_promising, double* r_fine, double* r_coarse,
+                           void* stream)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_get_selection: null context");
+    if (!ctx->has_index || !ctx->decoded) return fail(ctx, MP_ESTATE, "mp_get_selection: no decode call on this index yet");
+    hipStream_t s = (hipStream_t)stream;
+    const bool two = ctx->cfg.levels == 2;
+    if (fine_selected || r_fine)
+        MP_HIP(ctx, launch_scatter_selection(two ? ctx->cand : nullptr, ctx->Fcap, two ? ctx->n_cand : nullptr, ctx->n_fine,
+                                             ctx->flag_f, ctx->r_f, ctx->Fcap, ctx->n_fine, ctx->U, fine_selected, r_fine, s));
+    if (two && (coarse_promising || r_coarse))
+        MP_HIP(ctx, launch_scatter_selection(nullptr, 0, nullptr, ctx->n_coarse, ctx->flag_c, ctx->r_c, ctx->Ccap, ctx->n_coarse,
+                                             ctx->U, coarse_promising, r_coarse, s));
+    return MP_OK;
+}
+
+mp_status mp_get_counters(mp_ctx* ctx, int32_t* counters, void* stream)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_get_counters: null context");
+    if (!counters) return fail(ctx, MP_EINVAL, "mp_get_counters: null pointer");
+    if (!ctx->has_index || !ctx->decoded) return fail(ctx, MP_ESTATE, "mp_get_counters: no decode call on this index yet");
+    MP_HIP(ctx, hipMemcpyAsync(counters, ctx->counters, (size_t)ctx->U * 4 * sizeof(int32_t), hipMemcpyDeviceToDevice,
+                               (hipStream_t)stream));
+    return MP_OK;
+}
+
+mp_status mp_get_layout(mp_ctx* ctx, void* k_perm, void* v_perm, int32_t* perm, int32_t* fine_start, void* stream)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_get_layout: null context");
+    if (!ctx->has_index) return fail(ctx, MP_ESTATE, "mp_get_layout: no index yet");
+    hipStream_t s = (hipStream_t)stream;
+    const size_t row = kHeadDimHost * 2, n = ctx->n_tokens;
+    if (k_perm)
+        MP_HIP(ctx, hipMemcpy2DAsync(k_perm, n * row, ctx->Kp, (size_t)ctx->Ncap * row, n * row, ctx->U, hipMemcpyDeviceToDevice, s));
+    if (v_perm)
+        MP_HIP(ctx, hipMemcpy2DAsync(v_perm, n * row, ctx->Vp, (size_t)ctx->Ncap * row, n * row, ctx->U, hipMemcpyDeviceToDevice, s));
+    if (perm)
+        MP_HIP(ctx, hipMemcpy2DAsync(perm, n * 4, ctx->perm, (size_t)ctx->Ncap * 4, n * 4, ctx->U, hipMemcpyDeviceToDevice, s));
+    if (fine_start)
+        MP_HIP(ctx, hipMemcpy2DAsync(fine_start, (size_t)(ctx->n_fine + 1) * 4, ctx->fstart, (size_t)(ctx->Fcap + 1) * 4,
+                                     (size_t)(ctx->n_fine + 1) * 4, ctx->U, hipMemcpyDeviceToDevice, s));
+    return MP_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Dense comparison kernel
+// ------------------------------------------------------------------------------------------------
+size_t mp_dense_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t n)
+{
+    if (batch <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || n < 0 || n_q_heads % n_kv_heads) return 0;
+    const int U = batch * n_kv_heads, G = n_q_heads / n_kv_heads;
+    const int cr = pick_chunk_rows(n, U);
+    const int chunks = ceil_div(n > 0 ? n : 1, cr);
+    return sizeof(float) * (size_t)U * chunks * G * kPartStride;
+}
+
+mp_status mp_dense_attention(const void* q, const void* k, const void* v, int32_t batch, int32_t n_q_heads,
+                             int32_t n_kv_heads, int32_t n, float softmax_scale, void* out, float* lse, void* workspace,
+                             size_t workspace_bytes, void* stream)
+{
+    if (!q || !out || !workspace) return fail(nullptr, MP_EINVAL, "mp_dense_attention: null pointer");
+    if (batch <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || n < 0 || n_q_heads % n_kv_heads)
+        return fail(nullptr, MP_EINVAL, "mp_dense_attention: bad shape B=%d Hq=%d Hkv=%d n=%d", batch, n_q_heads, n_kv_heads, n);
+    if (n > 0 && (!k || !v)) return fail(nullptr, MP_EINVAL, "mp_dense_attention: null k/v with n > 0");
+    const int U = batch * n_kv_heads, G = n_q_heads / n_kv_heads;
+    if (G > 8) return fail(nullptr, MP_EINVAL, "mp_dense_attention: group size %d > 8 is not supported", G);
+    const size_t need = mp_dense_workspace_bytes(batch, n_q_heads, n_kv_heads, n);
+    if (workspace_bytes < need) return fail(nullptr, MP_EINVAL, "mp_dense_attention: workspace %zu < %zu bytes", workspace_bytes, need);
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)kHeadDimHost);
+
+    ValuePassParams p{};
+    p.q = (const uint16_t*)q;
+    p.partials = (float*)workspace;
+    p.n_units = U;
+    p.chunk_rows = pick_chunk_rows(n, U);
+    p.chunks_per_unit = ceil_div(n > 0 ? n : 1, p.chunk_rows);
+    p.n_sources = 1;
+    p.scale_log2e = scale * 1.4426950408889634f;
+    p.src[0].K = (const uint16_t*)k;
+    p.src[0].V = (const uint16_t*)v;
+    p.src[0].unit_rows = n;
+    p.src[0].count_max = n;
+    p.src[0].chunk0 = 0;
+    p.src[0].n_chunks = p.chunks_per_unit;
+    hipStream_t s = (hipStream_t)stream;
+    MP_HIP(nullptr, launch_value_pass(p, G, s));
+    MP_HIP(nullptr, launch_merge(p.partials, U, p.chunks_per_unit, G, (uint16_t*)out, lse, s));
+    return MP_OK;
+}
+
+}  // extern "C"

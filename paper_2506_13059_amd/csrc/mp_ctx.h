@@ -1,0 +1,131 @@
+// The context object behind the opaque mp_ctx handle, and small host-side helpers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/mp.h"
+
+namespace mp {
+
+constexpr int kHeadDimHost = 128;
+constexpr int kMaxClustersPerLevel = 8192;   // candidates of one level must fit the scoring kernel's LDS
+
+// Token / cluster ranges of one clustering block (Sec. 3.3).
+struct BlockPlan {
+    int32_t t0, t1;   // tokens
+    int32_t f0, f1;   // fine cluster ids
+    int32_t c0, c1;   // coarse cluster ids
+};
+
+// Blocks of block_w tokens; the last one takes the remaining block_alpha .. block_w+block_alpha-1
+// tokens.  Cluster totals are split by cumulative integer division.
+inline std::vector<BlockPlan> plan_blocks(int32_t n_tokens, int32_t block_w, int32_t block_alpha, int32_t n_fine,
+                                          int32_t n_coarse)
+{
+    std::vector<int32_t> bounds;
+    bounds.push_back(0);
+    if (block_w > 0 && n_tokens >= block_w + block_alpha) {
+        const int32_t m = (n_tokens - block_alpha) / block_w;
+        for (int32_t i = 1; i <= m; ++i) bounds.push_back(i * block_w);
+    }
+    if (bounds.back() != n_tokens) bounds.push_back(n_tokens);
+    std::vector<BlockPlan> out;
+    for (size_t b = 0; b + 1 < bounds.size(); ++b) {
+        const long long t0 = bounds[b], t1 = bounds[b + 1];
+        BlockPlan p;
+        p.t0 = (int32_t)t0;
+        p.t1 = (int32_t)t1;
+        p.f0 = (int32_t)((long long)n_fine * t0 / n_tokens);
+        p.f1 = (int32_t)((long long)n_fine * t1 / n_tokens);
+        p.c0 = (int32_t)((long long)n_coarse * t0 / n_tokens);
+        p.c1 = (int32_t)((long long)n_coarse * t1 / n_tokens);
+        out.push_back(p);
+    }
+    return out;
+}
+
+}  // namespace mp
+
+// The handle of the C ABI.  All device arrays have a leading unit axis; "cap" sizes come from cfg.
+struct mp_ctx {
+    mp_config cfg{};
+    std::string err;
+    int device = 0;
+    int U = 0, G = 0;
+    float scale = 0.f;
+    double scale_d = 0.0;          // softmax scale in double (0 in cfg => exactly 1/sqrt(128) in fp64)
+    size_t device_bytes = 0;
+    std::vector<void*> allocs;     // everything to hipFree at destroy
+
+    int32_t Ncap = 0, Fcap = 0, Ccap = 0, Tcap = 0, FBcap = 0;
+    long long tab_rows = 0;        // Fcap + Ccap: rows per unit of the centroid tables
+
+    // ---- clustered cache and index tables ----
+    uint16_t* Kp = nullptr;        // bf16 [U, Ncap, 128] keys, cluster after cluster
+    uint16_t* Vp = nullptr;        // bf16 [U, Ncap, 128]
+    int32_t* perm = nullptr;       // [U, Ncap] sequence index of each stored row
+    int32_t* fot = nullptr;        // [U, Ncap] fine cluster of each token (sequence order)
+    int32_t* fstart = nullptr;     // [U, Fcap+1] first stored row of each fine cluster
+    int32_t* cof = nullptr;        // [U, Fcap] coarse cluster of each fine cluster
+    int32_t* cstart = nullptr;     // [U, Ccap+1] first fine cluster of each coarse cluster
+    int32_t* crow = nullptr;       // [U, Ccap+1] first stored row of each coarse cluster
+    uint16_t* Kc = nullptr;        // bf16 [U, tab_rows, 128] key centroids: fine rows, coarse rows from Fcap
+    uint16_t* Vc = nullptr;        // bf16 [U, tab_rows, 128] value centroids
+    int32_t* Ncl = nullptr;        // [U, tab_rows] member counts
+
+    // ---- last block in sequence order (working set of the online update) ----
+    uint16_t* Kfb = nullptr;       // bf16 [U, FBcap, 128]
+    uint16_t* Vfb = nullptr;
+
+    // ---- k-means workspace ----
+    int32_t* km_assign = nullptr;  // [U, Ncap] block-local cluster of each point
+    int32_t* km_list = nullptr;    // [U, Ncap] member lists
+    int32_t* km_cnt = nullptr;     // [U, tab_rows]
+    int32_t* km_start = nullptr;   // [U, tab_rows + 2]
+    uint16_t* km_Cf = nullptr;     // bf16 [U, Fcap, 128] fine k-means centroids
+    uint16_t* km_Cc = nullptr;     // bf16 [U, Ccap, 128] coarse k-means centroids
+    int32_t* km_parent = nullptr;  // [U, Fcap] coarse assignment of the fine centroids
+    int32_t* km_plist = nullptr;   // [U, Fcap] fine ids ordered by parent
+    int32_t* km_newid = nullptr;   // [U, Fcap]
+    int32_t* km_seed_f = nullptr;  // [U, Fcap]
+    int32_t* km_seed_c = nullptr;  // [U, Ccap]
+    int32_t* blocks_dev = nullptr; // [3][max_blocks][4] block descriptors (fine level, coarse level, scratch)
+    int32_t max_blocks = 0;
+
+    // ---- decode workspace ----
+    double* lg_c = nullptr;        // [U, G, Ccap] coarse logits
+    double* lg_f = nullptr;        // [U, G, Fcap] fine logits by candidate position
+    double* r_c = nullptr;         // [U, Ccap]
+    double* r_f = nullptr;         // [U, Fcap] by candidate position
+    uint8_t* flag_c = nullptr;     // [U, Ccap] promising
+    uint8_t* flag_f = nullptr;     // [U, Fcap] selected, by candidate position
+    int32_t* cand = nullptr;       // [U, Fcap]
+    int32_t* n_cand = nullptr;     // [U]
+    double* unprom_lse = nullptr;  // [U, G]
+    int32_t* rows = nullptr;       // [U, Ncap] stored rows of the selected keys
+    int32_t* n_rows = nullptr;     // [U]
+    int32_t* mp_rows = nullptr;    // [U, tab_rows]
+    float* mp_scores = nullptr;    // [U, tab_rows, G]
+    int32_t* n_mp = nullptr;       // [U]
+    int32_t* counters = nullptr;   // [U, 4]
+    float* partials = nullptr;     // [U, Pcap, G, 132]
+    int32_t Pcap = 0;
+
+    // ---- current index (host copies of sizes) ----
+    bool has_index = false;
+    bool decoded = false;
+    int32_t n_tokens = 0, n_fine = 0, n_coarse = 0;
+    std::vector<mp::BlockPlan> blocks;
+};
+
+namespace mp {
+// Record an error message on the context (or, with ctx == nullptr, for the calling thread) and
+// return the status.
+mp_status fail(mp_ctx* ctx, mp_status st, const char* fmt, ...) __attribute__((format(printf, 3, 4)));
+int pick_chunk_rows(long long n_rows_per_unit, int n_units);
+mp_status finalize_index(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, int32_t n_fine, int32_t n_coarse,
+                         const std::vector<BlockPlan>& blocks, bool key_fallback, hipStream_t s);
+}  // namespace mp

@@ -1,0 +1,127 @@
+// Device-side helpers shared by the gfx950 kernels: wave64 cross-lane primitives and bf16 bit tricks.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mp {
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+constexpr int kHeadDim = 128;
+constexpr int kWave = 64;
+
+// ---- bf16 <-> fp32 (bit level; a bf16 is the upper half of an fp32) ---------------------------
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// fp32 -> bf16, round to nearest even (NaN kept quiet).
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t x = __float_as_uint(f);
+    if ((x & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((x >> 16) | 0x40u);
+    uint32_t lsb = (x >> 16) & 1u;
+    x += 0x7fffu + lsb;
+    return (uint16_t)(x >> 16);
+}
+
+// fp64 -> bf16 with ONE rounding (nearest even).  The double is first truncated to fp32 with a
+// sticky bit in the last place (round to odd), which makes the second rounding exact.  Values
+// whose magnitude is below 2^-126 go to signed zero; overflow goes to infinity.
+__device__ __forceinline__ uint16_t f64_to_bf16_rne(double v)
+{
+    uint64_t b = (uint64_t)__double_as_longlong(v);
+    uint32_t sign = (uint32_t)(b >> 63) << 31;
+    int32_t e = (int32_t)((b >> 52) & 0x7ff);
+    uint64_t man = b & 0xfffffffffffffull;
+    if (e == 0x7ff) {                                   // inf / nan
+        uint32_t x = sign | 0x7f800000u | (man ? 0x400000u : 0u);
+        return (uint16_t)(x >> 16);
+    }
+    int32_t fe = e - 1023 + 127;
+    if (fe <= 0) return (uint16_t)(sign >> 16);         // below the fp32 normal range (incl. zero)
+    if (fe >= 255) return (uint16_t)((sign | 0x7f800000u) >> 16);
+    uint32_t m23 = (uint32_t)(man >> 29);
+    uint32_t sticky = (man & ((1ull << 29) - 1)) ? 1u : 0u;
+    uint32_t x = sign | ((uint32_t)fe << 23) | m23 | sticky;
+    uint32_t lsb = (x >> 16) & 1u;
+    uint32_t mag = (x & 0x7fffffffu) + 0x7fffu + lsb;   // may carry into the exponent: correct
+    if (mag >= 0x7f800000u) mag = 0x7f800000u;
+    return (uint16_t)((sign | mag) >> 16);
+}
+
+// a.x*b.x + a.y*b.y + c on packed bf16 pairs (v_dot2c_f32_bf16)
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
+// ---- DPP cross-lane moves inside a row of 16 lanes ----------------------------------------------
+template <int kCtrl>
+__device__ __forceinline__ float dpp_f32(float v)
+{
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), kCtrl, 0xf, 0xf, true));
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each half row
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each row
+
+// Sum over aligned groups of 8 lanes; every lane of the group receives the total.
+__device__ __forceinline__ float sum8(float v)
+{
+    v += dpp_f32<kDppXor1>(v);
+    v += dpp_f32<kDppXor2>(v);
+    v += dpp_f32<kDppHalfMirror>(v);
+    return v;
+}
+// Sum over aligned groups of 4 lanes.
+__device__ __forceinline__ float sum4(float v)
+{
+    v += dpp_f32<kDppXor1>(v);
+    v += dpp_f32<kDppXor2>(v);
+    return v;
+}
+
+template <int kCtrl>
+__device__ __forceinline__ double dpp_f64(double v)
+{
+    long long b = __double_as_longlong(v);
+    int lo = __builtin_amdgcn_mov_dpp((int)(b & 0xffffffffll), kCtrl, 0xf, 0xf, true);
+    int hi = __builtin_amdgcn_mov_dpp((int)(b >> 32), kCtrl, 0xf, 0xf, true);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+__device__ __forceinline__ double sum4_f64(double v)
+{
+    v += dpp_f64<kDppXor1>(v);
+    v += dpp_f64<kDppXor2>(v);
+    return v;
+}
+
+// ---- whole-wave helpers (wave64) ---------------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v)
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        uint32_t t = __shfl_up(v, off, 64);
+        if (lane >= off) v += t;
+    }
+    return v;
+}
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_max_f64(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmax(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+}  // namespace mp

@@ -1,0 +1,348 @@
+// Index construction kernels for gfx950: member lists (stable counting sort by cluster id),
+// cluster-contiguous gather of the KV rows, and the per-cluster tables (N, key centroid, value
+// centroid = bf16-rounded fp64 means of the member keys / values, Sec. 3.1 and 3.2).
+//
+// Member sums run over the members in sequence order, one wave per cluster, in fp64: the result
+// does not depend on the launch shape and repeats bit for bit.
+#include "mp_device.h"
+#include "mp_internal.h"
+
+namespace mp {
+
+namespace {
+
+__global__ void fill_i32_kernel(int32_t* __restrict__ p, long long n, int32_t v)
+{
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long step = (long long)gridDim.x * blockDim.x;
+    for (; i < n; i += step) p[i] = v;
+}
+
+// cnt[u][id[u][t]] += 1
+__global__ void histogram_kernel(const int32_t* __restrict__ ids, long long ids_stride, int n,
+                                 int32_t* __restrict__ cnt, long long cnt_stride)
+{
+    const int u = blockIdx.y;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) atomicAdd(cnt + u * cnt_stride + ids[u * ids_stride + t], 1);
+}
+
+// start[u][0..k] = exclusive prefix sum of cnt[u][0..k), one workgroup of 1024 threads per unit.
+__global__ __launch_bounds__(1024) void exclusive_scan_kernel(const int32_t* __restrict__ cnt, long long cnt_stride,
+                                                              int k, int32_t* __restrict__ start,
+                                                              long long start_stride)
+{
+    __shared__ uint32_t wsum[16];
+    __shared__ uint32_t carry_s;
+    const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    for (int base = 0; base < k; base += 1024) {
+        const int i = base + tid;
+        const uint32_t v = (i < k) ? (uint32_t)cnt[u * cnt_stride + i] : 0u;
+        const uint32_t incl = wave_incl_scan_u32(v);
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        uint32_t woff = 0;
+        for (int w = 0; w < wave; ++w) woff += wsum[w];
+        const uint32_t carry = carry_s;
+        if (i < k) start[u * start_stride + i] = (int32_t)(carry + woff + incl - v);
+        __syncthreads();
+        if (tid == 1023) carry_s = carry + woff + incl;
+        __syncthreads();
+    }
+    if (tid == 0) start[u * start_stride + k] = (int32_t)carry_s;
+}
+
+// Member lists: list[u][start[id] + rank] = point index, points of a cluster in ascending order.
+// One thread per cluster walks the ids of its block (staged through LDS, every lane reads the same
+// word, which LDS serves as a broadcast) and appends its own members.
+// grid = (ceil(max clusters per block / 256), n_blocks, U)
+constexpr int kListTile = 4096;
+__global__ __launch_bounds__(256) void member_list_kernel(const int32_t* __restrict__ ids, long long ids_stride,
+                                                          const int32_t* __restrict__ blocks /*[nb][4]: x0,x1,k0,k1*/,
+                                                          const int32_t* __restrict__ start, long long start_stride,
+                                                          int32_t* __restrict__ list, long long list_stride)
+{
+    __shared__ int32_t tile[kListTile];
+    const int u = blockIdx.z, b = blockIdx.y;
+    const int x0 = blocks[4 * b + 0], x1 = blocks[4 * b + 1], k0 = blocks[4 * b + 2], k1 = blocks[4 * b + 3];
+    const int kbase = k0 + blockIdx.x * 256;
+    if (kbase >= k1) return;
+    const int my = kbase + threadIdx.x;
+    const bool live = my < k1;
+    int wr = live ? start[u * start_stride + my] : 0;
+    const int32_t* idp = ids + u * ids_stride;
+    int32_t* lp = list + u * list_stride;
+    for (int t0 = x0; t0 < x1; t0 += kListTile) {
+        const int nt = (x1 - t0 < kListTile) ? x1 - t0 : kListTile;
+        __syncthreads();
+        for (int i = threadIdx.x; i < nt; i += 256) tile[i] = idp[t0 + i];
+        __syncthreads();
+        if (live) {
+            int i = 0;
+            for (; i + 4 <= nt; i += 4) {
+                const int4 v = *reinterpret_cast<const int4*>(&tile[i]);
+                if (v.x == my) lp[wr++] = t0 + i;
+                if (v.y == my) lp[wr++] = t0 + i + 1;
+                if (v.z == my) lp[wr++] = t0 + i + 2;
+                if (v.w == my) lp[wr++] = t0 + i + 3;
+            }
+            for (; i < nt; ++i)
+                if (tile[i] == my) lp[wr++] = t0 + i;
+        }
+    }
+}
+
+// dst[u][p] = src[u][list[u][p]] for 256-byte rows; one thread moves 16 bytes.
+__global__ void gather_rows_kernel(const uint4* __restrict__ srcK, const uint4* __restrict__ srcV,
+                                   long long src_unit_rows, const int32_t* __restrict__ list, long long list_stride,
+                                   int n, uint4* __restrict__ dstK, uint4* __restrict__ dstV, long long dst_unit_rows,
+                                   int dst_row0)
+{
+    const int u = blockIdx.y;
+    const long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long p = g >> 4;
+    const int c = (int)(g & 15);
+    if (p >= n) return;
+    const long long s = list[u * list_stride + p];
+    dstK[((long long)u * dst_unit_rows + dst_row0 + p) * 16 + c] = srcK[((long long)u * src_unit_rows + s) * 16 + c];
+    dstV[((long long)u * dst_unit_rows + dst_row0 + p) * 16 + c] = srcV[((long long)u * src_unit_rows + s) * 16 + c];
+}
+
+// One wave per cluster: fp64 sum of the member rows in list order, mean rounded once to bf16.
+// Lane l owns dims 2l and 2l+1.  Empty cluster: `fallback` row if given (else zeros).
+// mean_out row index = out_row0 + cluster id.  count_out optional.
+__global__ __launch_bounds__(256) void cluster_mean_kernel(const uint16_t* __restrict__ X, long long x_unit_rows,
+                                                           const int32_t* __restrict__ list, long long list_stride,
+                                                           const int32_t* __restrict__ start, long long start_stride,
+                                                           int k, uint16_t* __restrict__ mean_out,
+                                                           long long out_unit_rows, int out_row0,
+                                                           const uint16_t* __restrict__ fallback,
+                                                           long long fb_unit_rows, int32_t* __restrict__ count_out,
+                                                           long long count_stride, int count_off)
+{
+    const int u = blockIdx.y;
+    const int f = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (f >= k) return;
+    const int s0 = start[u * start_stride + f], s1 = start[u * start_stride + f + 1];
+    const uint32_t* Xu = reinterpret_cast<const uint32_t*>(X + (long long)u * x_unit_rows * kHeadDim);
+    const int32_t* lp = list ? list + u * list_stride : nullptr;
+    double a0 = 0.0, a1 = 0.0;
+    int p = s0;
+    for (; p + 4 <= s1; p += 4) {
+        const long long r0 = lp ? lp[p] : p, r1 = lp ? lp[p + 1] : p + 1, r2 = lp ? lp[p + 2] : p + 2,
+                        r3 = lp ? lp[p + 3] : p + 3;
+        const uint32_t w0 = Xu[r0 * 64 + lane], w1 = Xu[r1 * 64 + lane], w2 = Xu[r2 * 64 + lane],
+                       w3 = Xu[r3 * 64 + lane];
+        a0 += (double)bf16lo_to_f32(w0); a1 += (double)bf16hi_to_f32(w0);
+        a0 += (double)bf16lo_to_f32(w1); a1 += (double)bf16hi_to_f32(w1);
+        a0 += (double)bf16lo_to_f32(w2); a1 += (double)bf16hi_to_f32(w2);
+        a0 += (double)bf16lo_to_f32(w3); a1 += (double)bf16hi_to_f32(w3);
+    }
+    for (; p < s1; ++p) {
+        const long long r0 = lp ? lp[p] : p;
+        const uint32_t w0 = Xu[r0 * 64 + lane];
+        a0 += (double)bf16lo_to_f32(w0); a1 += (double)bf16hi_to_f32(w0);
+    }
+    const int n = s1 - s0;
+    uint32_t outw;
+    if (n > 0) {
+        const double inv = (double)n;
+        outw = (uint32_t)f64_to_bf16_rne(a0 / inv) | ((uint32_t)f64_to_bf16_rne(a1 / inv) << 16);
+    } else if (fallback) {
+        outw = reinterpret_cast<const uint32_t*>(fallback + ((long long)u * fb_unit_rows + f) * kHeadDim)[lane];
+    } else {
+        outw = 0u;
+    }
+    reinterpret_cast<uint32_t*>(mean_out + ((long long)u * out_unit_rows + out_row0 + f) * kHeadDim)[lane] = outw;
+    if (count_out && lane == 0) count_out[u * count_stride + count_off + f] = n;
+}
+
+// cstart[u][c] = first fine id whose coarse id is >= c (coarse ids are non-decreasing in the fine id);
+// cstart[u][n_coarse] = n_fine.
+__global__ void coarse_start_kernel(const int32_t* __restrict__ cof, long long cof_stride, int n_fine, int n_coarse,
+                                    int32_t* __restrict__ cstart, long long cstart_stride)
+{
+    const int u = blockIdx.y;
+    const int f = blockIdx.x * blockDim.x + threadIdx.x;
+    if (f > n_fine) return;
+    const int cur = (f < n_fine) ? cof[u * cof_stride + f] : n_coarse;
+    const int prev = (f > 0) ? cof[u * cof_stride + f - 1] : -1;
+    for (int c = prev + 1; c <= cur; ++c) cstart[u * cstart_stride + c] = f;
+}
+
+// Row ranges of the coarse clusters in the stored order: rstart[u][c] = fstart[u][cstart[u][c]].
+__global__ void coarse_row_start_kernel(const int32_t* __restrict__ cstart, long long cstart_stride,
+                                        const int32_t* __restrict__ fstart, long long fstart_stride, int n_coarse,
+                                        int32_t* __restrict__ rstart, long long rstart_stride)
+{
+    const int u = blockIdx.y;
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c > n_coarse) return;
+    rstart[u * rstart_stride + c] = fstart[u * fstart_stride + cstart[u * cstart_stride + c]];
+}
+
+// fot[u][list[p]] = f for p in [start[f], start[f+1])  (inverse of the member lists)
+__global__ void ids_from_lists_kernel(const int32_t* __restrict__ list, long long list_stride,
+                                      const int32_t* __restrict__ start, long long start_stride, int k,
+                                      int32_t* __restrict__ ids, long long ids_stride)
+{
+    const int u = blockIdx.y;
+    const int f = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (f >= k) return;
+    const int s0 = start[u * start_stride + f], s1 = start[u * start_stride + f + 1];
+    for (int p = s0 + lane; p < s1; p += 64) ids[u * ids_stride + list[u * list_stride + p]] = f;
+}
+
+// out[u][i] = map[u][in[u][i] + off(block of i)] ... renumbering helper:
+// ids[u][t] = base_of_block + newid[u][k0 + ids[u][t]] for t in block b.
+__global__ void renumber_kernel(int32_t* __restrict__ ids, long long ids_stride, const int32_t* __restrict__ blocks,
+                                int nb, const int32_t* __restrict__ newid, long long newid_stride)
+{
+    const int u = blockIdx.z, b = blockIdx.y;
+    const int x0 = blocks[4 * b + 0], x1 = blocks[4 * b + 1], k0 = blocks[4 * b + 2];
+    const int t = x0 + blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= x1) return;
+    const int old = ids[u * ids_stride + t];
+    ids[u * ids_stride + t] = k0 + newid[u * newid_stride + k0 + old];
+}
+
+// Dense per-cluster views of the last decode call's selection, from the per-candidate arrays:
+// sel[u][id] = flag of the candidate with that id (0 if it was no candidate), r[u][id] = its rank
+// key (NaN if it was no candidate).  One workgroup per unit.
+__global__ __launch_bounds__(256) void scatter_selection_kernel(const int32_t* __restrict__ cand,
+                                                                long long cand_stride,
+                                                                const int32_t* __restrict__ n_cand_dev,
+                                                                int n_cand_fixed, const uint8_t* __restrict__ flag,
+                                                                const double* __restrict__ r, long long pos_stride,
+                                                                int n_ids, uint8_t* __restrict__ sel_out,
+                                                                double* __restrict__ r_out)
+{
+    const int u = blockIdx.x;
+    const int n = n_cand_dev ? n_cand_dev[u] : n_cand_fixed;
+    const double nan = __longlong_as_double(0x7ff8000000000000ll);
+    for (int i = threadIdx.x; i < n_ids; i += 256) {
+        if (sel_out) sel_out[(long long)u * n_ids + i] = 0;
+        if (r_out) r_out[(long long)u * n_ids + i] = nan;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += 256) {
+        const int id = cand ? cand[u * cand_stride + i] : i;
+        if (sel_out) sel_out[(long long)u * n_ids + id] = flag[u * pos_stride + i];
+        if (r_out) r_out[(long long)u * n_ids + id] = r[u * pos_stride + i];
+    }
+}
+
+}  // namespace
+
+hipError_t launch_scatter_selection(const int32_t* cand, long long cand_stride, const int32_t* n_cand_dev,
+                                    int n_cand_fixed, const uint8_t* flag, const double* r, long long pos_stride,
+                                    int n_ids, int U, uint8_t* sel_out, double* r_out, hipStream_t s)
+{
+    if (n_ids <= 0) return hipSuccess;
+    hipLaunchKernelGGL(scatter_selection_kernel, dim3(U), dim3(256), 0, s, cand, cand_stride, n_cand_dev,
+                       n_cand_fixed, flag, r, pos_stride, n_ids, sel_out, r_out);
+    return hipGetLastError();
+}
+
+// ---- host launchers ----------------------------------------------------------------------------
+hipError_t launch_fill_i32(int32_t* p, long long n, int32_t v, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    long long blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_histogram(const int32_t* ids, long long ids_stride, int n, int U, int32_t* cnt,
+                            long long cnt_stride, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(histogram_kernel, dim3((n + 255) / 256, U), dim3(256), 0, s, ids, ids_stride, n, cnt,
+                       cnt_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_exclusive_scan(const int32_t* cnt, long long cnt_stride, int k, int U, int32_t* start,
+                                 long long start_stride, hipStream_t s)
+{
+    hipLaunchKernelGGL(exclusive_scan_kernel, dim3(U), dim3(1024), 0, s, cnt, cnt_stride, k, start, start_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_member_lists(const int32_t* ids, long long ids_stride, const int32_t* blocks_dev, int nb,
+                               int max_k_per_block, int U, const int32_t* start, long long start_stride,
+                               int32_t* list, long long list_stride, hipStream_t s)
+{
+    if (nb <= 0 || max_k_per_block <= 0) return hipSuccess;
+    hipLaunchKernelGGL(member_list_kernel, dim3((max_k_per_block + 255) / 256, nb, U), dim3(256), 0, s, ids,
+                       ids_stride, blocks_dev, start, start_stride, list, list_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const void* srcK, const void* srcV, long long src_unit_rows, const int32_t* list,
+                              long long list_stride, int n, int U, void* dstK, void* dstV, long long dst_unit_rows,
+                              int dst_row0, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    const long long threads = (long long)n * 16;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((threads + 255) / 256), U), dim3(256), 0, s,
+                       (const uint4*)srcK, (const uint4*)srcV, src_unit_rows, list, list_stride, n, (uint4*)dstK,
+                       (uint4*)dstV, dst_unit_rows, dst_row0);
+    return hipGetLastError();
+}
+
+hipError_t launch_cluster_means(const uint16_t* X, long long x_unit_rows, const int32_t* list, long long list_stride,
+                                const int32_t* start, long long start_stride, int k, int U, uint16_t* mean_out,
+                                long long out_unit_rows, int out_row0, const uint16_t* fallback,
+                                long long fb_unit_rows, int32_t* count_out, long long count_stride, int count_off,
+                                hipStream_t s)
+{
+    if (k <= 0) return hipSuccess;
+    hipLaunchKernelGGL(cluster_mean_kernel, dim3((k + 3) / 4, U), dim3(256), 0, s, X, x_unit_rows, list, list_stride,
+                       start, start_stride, k, mean_out, out_unit_rows, out_row0, fallback, fb_unit_rows, count_out,
+                       count_stride, count_off);
+    return hipGetLastError();
+}
+
+hipError_t launch_coarse_start(const int32_t* cof, long long cof_stride, int n_fine, int n_coarse, int U,
+                               int32_t* cstart, long long cstart_stride, hipStream_t s)
+{
+    hipLaunchKernelGGL(coarse_start_kernel, dim3((n_fine + 1 + 255) / 256, U), dim3(256), 0, s, cof, cof_stride,
+                       n_fine, n_coarse, cstart, cstart_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_coarse_row_start(const int32_t* cstart, long long cstart_stride, const int32_t* fstart,
+                                   long long fstart_stride, int n_coarse, int U, int32_t* rstart,
+                                   long long rstart_stride, hipStream_t s)
+{
+    hipLaunchKernelGGL(coarse_row_start_kernel, dim3((n_coarse + 1 + 255) / 256, U), dim3(256), 0, s, cstart,
+                       cstart_stride, fstart, fstart_stride, n_coarse, rstart, rstart_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_ids_from_lists(const int32_t* list, long long list_stride, const int32_t* start,
+                                 long long start_stride, int k, int U, int32_t* ids, long long ids_stride,
+                                 hipStream_t s)
+{
+    if (k <= 0) return hipSuccess;
+    hipLaunchKernelGGL(ids_from_lists_kernel, dim3((k + 3) / 4, U), dim3(256), 0, s, list, list_stride, start,
+                       start_stride, k, ids, ids_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_renumber(int32_t* ids, long long ids_stride, const int32_t* blocks_dev, int nb,
+                           int max_pts_per_block, int U, const int32_t* newid, long long newid_stride, hipStream_t s)
+{
+    if (nb <= 0 || max_pts_per_block <= 0) return hipSuccess;
+    hipLaunchKernelGGL(renumber_kernel, dim3((max_pts_per_block + 255) / 256, nb, U), dim3(256), 0, s, ids,
+                       ids_stride, blocks_dev, nb, newid, newid_stride);
+    return hipGetLastError();
+}
+
+}  // namespace mp

@@ -1,0 +1,133 @@
+// Host-side declarations shared by the kernel translation units and the C-ABI layer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mp {
+
+// ------------------------------------------------------------------------------------------------
+// Value pass: streams rows (keys + values, or value centroids with ready-made scores) and produces
+// one online-softmax partial (m, l, acc[128]) per (unit, chunk, head).
+// ------------------------------------------------------------------------------------------------
+constexpr int kChunkRowsMin = 512;     // a workgroup is 4 waves, each taking strips of 128 rows
+constexpr int kPartStride = 132;       // floats per (unit, chunk, head): m, l, pad, pad, acc[128]
+constexpr int kMaxSources = 4;
+
+// One stream of rows.  Row j of unit u lives at K + (u*unit_rows + idx)*128 where idx = rows ?
+// rows[u*rows_stride + j] : j.  The number of rows is *count_dev (clamped to count_max) or count_max.
+struct RowSource {
+    const uint16_t* K;         // bf16 keys; unused when scores != nullptr
+    const uint16_t* V;         // bf16 values (or value centroids)
+    long long unit_rows;       // rows per unit in K / V
+    const int32_t* rows;       // optional gather list
+    long long rows_stride;     // entries per unit in rows / scores
+    const int32_t* count_dev;  // optional per-unit row count on the device
+    int32_t count_max;         // upper bound of the row count (fixes the chunk count)
+    const float* scores;       // optional [U, rows_stride, G] ready-made logits in log2 units
+    int32_t chunk0;            // first chunk id of this source inside a unit
+    int32_t n_chunks;          // ceil(count_max / chunk_rows)
+};
+
+struct ValuePassParams {
+    const uint16_t* q;         // bf16 [U*G, 128]
+    float* partials;           // [U, chunks_per_unit, G, kPartStride]
+    int32_t n_units;
+    int32_t chunks_per_unit;
+    int32_t n_sources;
+    int32_t chunk_rows;        // rows per workgroup, a multiple of kChunkRowsMin
+    float scale_log2e;         // softmax scale * log2(e)
+    RowSource src[kMaxSources];
+};
+
+hipError_t launch_value_pass(const ValuePassParams& p, int G, hipStream_t stream);
+
+// Merge of the partials of a unit into the output: out bf16 [U*G, 128], lse fp32 [U*G] (optional).
+hipError_t launch_merge(const float* partials, int n_units, int chunks_per_unit, int G, uint16_t* out,
+                        float* lse, hipStream_t stream);
+
+// ------------------------------------------------------------------------------------------------
+// Centroid scoring + budgeted selection (one launch per level)
+// ------------------------------------------------------------------------------------------------
+struct ScoreParams {
+    const uint16_t* q;          // bf16 [U*G, 128]
+    const uint16_t* Kc;         // bf16 [U, tab_rows, 128]: fine rows, then coarse rows at row_off
+    const int32_t* N;           // [U, tab_rows]
+    long long tab_rows;
+    int row_off;                // row of candidate id 0 at this level
+    const int32_t* cand;        // [U, cand_stride] candidate ids, or nullptr = identity
+    long long cand_stride;
+    const int32_t* n_cand_dev;  // [U] or nullptr
+    int n_cand_fixed;
+    long long budget;
+    double scale;
+    const double* extra_lse;    // [U, G] log-sum of terms that join the Eq. 1 denominator, or nullptr
+    double* lg;                 // [U, G, lg_stride] logits by candidate position
+    long long lg_stride;
+    double* r_out;              // [U, r_stride] rank key by candidate position (NaN if N == 0)
+    long long r_stride;
+    uint8_t* flag_out;          // [U, r_stride] 1 = promising / selected, by candidate position
+    // coarse level only
+    const int32_t* cstart;      // [U, cstart_stride] first child of each coarse cluster
+    long long cstart_stride;
+    int32_t* cand_out;          // [U, cand_out_stride]
+    long long cand_out_stride;
+    int32_t* n_cand_out;        // [U]
+    double* unprom_lse_out;     // [U, G]
+    // fine level only
+    const int32_t* fstart;      // [U, fstart_stride] first stored row of each fine cluster
+    long long fstart_stride;
+    int32_t* rows_out;          // [U, rows_stride]
+    long long rows_stride;
+    int32_t* n_rows_out;        // [U]
+    // centroid-term list (both levels)
+    int32_t* mp_rows;           // [U, mp_stride] row in the centroid table
+    float* mp_scores;           // [U, mp_stride, G] (l + ln N) * log2(e)
+    long long mp_stride;
+    int32_t* n_mp;              // [U]: coarse writes, fine appends (fine starts at 0 if mp_append == 0)
+    int mp_append;
+    int use_mp;
+    int32_t* counters;          // [U, 4]
+    int n_tail;
+    int smem_cap;               // candidate capacity of the LDS arrays
+    int G, U;                   // group size, units
+    int coarse;                 // 1 = coarse level launch
+};
+
+hipError_t launch_score_select(const ScoreParams& p, hipStream_t stream);
+size_t score_smem_bytes(int G, int cap);
+
+// ------------------------------------------------------------------------------------------------
+// Index construction helpers (member lists, gathers, per-cluster means)
+// ------------------------------------------------------------------------------------------------
+hipError_t launch_fill_i32(int32_t* p, long long n, int32_t v, hipStream_t s);
+hipError_t launch_histogram(const int32_t* ids, long long ids_stride, int n, int U, int32_t* cnt,
+                            long long cnt_stride, hipStream_t s);
+hipError_t launch_exclusive_scan(const int32_t* cnt, long long cnt_stride, int k, int U, int32_t* start,
+                                 long long start_stride, hipStream_t s);
+// blocks_dev: int32 [nb][4] = {first point, end point, first cluster, end cluster}
+hipError_t launch_member_lists(const int32_t* ids, long long ids_stride, const int32_t* blocks_dev, int nb,
+                               int max_k_per_block, int U, const int32_t* start, long long start_stride,
+                               int32_t* list, long long list_stride, hipStream_t s);
+hipError_t launch_gather_rows(const void* srcK, const void* srcV, long long src_unit_rows, const int32_t* list,
+                              long long list_stride, int n, int U, void* dstK, void* dstV, long long dst_unit_rows,
+                              int dst_row0, hipStream_t s);
+hipError_t launch_cluster_means(const uint16_t* X, long long x_unit_rows, const int32_t* list, long long list_stride,
+                                const int32_t* start, long long start_stride, int k, int U, uint16_t* mean_out,
+                                long long out_unit_rows, int out_row0, const uint16_t* fallback,
+                                long long fb_unit_rows, int32_t* count_out, long long count_stride, int count_off,
+                                hipStream_t s);
+hipError_t launch_coarse_start(const int32_t* cof, long long cof_stride, int n_fine, int n_coarse, int U,
+                               int32_t* cstart, long long cstart_stride, hipStream_t s);
+hipError_t launch_coarse_row_start(const int32_t* cstart, long long cstart_stride, const int32_t* fstart,
+                                   long long fstart_stride, int n_coarse, int U, int32_t* rstart,
+                                   long long rstart_stride, hipStream_t s);
+hipError_t launch_ids_from_lists(const int32_t* list, long long list_stride, const int32_t* start,
+                                 long long start_stride, int k, int U, int32_t* ids, long long ids_stride,
+                                 hipStream_t s);
+hipError_t launch_scatter_selection(const int32_t* cand, long long cand_stride, const int32_t* n_cand_dev,
+                                    int n_cand_fixed, const uint8_t* flag, const double* r, long long pos_stride,
+                                    int n_ids, int U, uint8_t* sel_out, double* r_out, hipStream_t s);
+hipError_t launch_renumber(int32_t* ids, long long ids_stride, const int32_t* blocks_dev, int nb,
+                           int max_pts_per_block, int U, const int32_t* newid, long long newid_stride, hipStream_t s);
+
+}  // namespace mp

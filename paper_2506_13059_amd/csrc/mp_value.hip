@@ -1,0 +1,370 @@
+// Value pass and merge for gfx950.
+//
+// The value pass is the byte mover of the decode step: it streams 256-byte key rows and value rows
+// (the keys of the selected clusters, the unclustered tail, or all keys for the dense comparison)
+// and, in the same launch, the value-centroid rows of the clusters that enter the softmax through
+// their centroid term N*exp(q.Kc) (Eq. 2).  Every workgroup writes one online-softmax partial
+// (m, l, acc[128]) per query head of the group; the merge kernel combines them (Sec. 4: split over
+// the KV dimension followed by a reduction of the intermediate results).
+//
+// Lane layout inside a wave: lane = 8*r + c.  A group of 8 lanes (fixed r) owns one row at a
+// time; lane c holds dims [8c, 8c+8) and [64+8c, 64+8c+8) of that row, so that each 16-byte load
+// instruction of the wave covers eight full 128-byte lines.  A query-key product is 8 packed bf16
+// dot instructions per head followed by a 3-step DPP sum over the 8 lanes; the value update keeps
+// 16 fp32 accumulators per head and lane.  All G heads of the group share every loaded row.
+#include "mp_device.h"
+#include "mp_internal.h"
+
+namespace mp {
+
+namespace {
+
+struct RowRegs {
+    uint4 klo, khi, vlo, vhi;
+};
+
+__device__ __forceinline__ void load_row(RowRegs& t, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+                                         long long row, int c)
+{
+    const uint4* kp = reinterpret_cast<const uint4*>(K + row * kHeadDim) + c;
+    const uint4* vp = reinterpret_cast<const uint4*>(V + row * kHeadDim) + c;
+    t.klo = kp[0];
+    t.khi = kp[8];
+    t.vlo = vp[0];
+    t.vhi = vp[8];
+}
+
+__device__ __forceinline__ void load_vrow(RowRegs& t, const uint16_t* __restrict__ V, long long row, int c)
+{
+    const uint4* vp = reinterpret_cast<const uint4*>(V + row * kHeadDim) + c;
+    t.vlo = vp[0];
+    t.vhi = vp[8];
+}
+
+template <int G>
+struct HeadState {
+    float m[G];
+    float l[G];
+    float acc[G][16];
+};
+
+template <int G>
+__device__ __forceinline__ void qk_scores(const RowRegs& t, const uint4 (&qlo)[G], const uint4 (&qhi)[G], float scale,
+                                          bool valid, float (&s)[G])
+{
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        float a = 0.f;
+        a = dot2_bf16(t.klo.x, qlo[h].x, a);
+        a = dot2_bf16(t.klo.y, qlo[h].y, a);
+        a = dot2_bf16(t.klo.z, qlo[h].z, a);
+        a = dot2_bf16(t.klo.w, qlo[h].w, a);
+        a = dot2_bf16(t.khi.x, qhi[h].x, a);
+        a = dot2_bf16(t.khi.y, qhi[h].y, a);
+        a = dot2_bf16(t.khi.z, qhi[h].z, a);
+        a = dot2_bf16(t.khi.w, qhi[h].w, a);
+        a = sum8(a);
+        s[h] = valid ? a * scale : -INFINITY;
+    }
+}
+
+template <int G>
+__device__ __forceinline__ void accumulate_v(HeadState<G>& st, const RowRegs& t, const float (&p)[G])
+{
+    const uint32_t w[8] = {t.vlo.x, t.vlo.y, t.vlo.z, t.vlo.w, t.vhi.x, t.vhi.y, t.vhi.z, t.vhi.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float va = bf16lo_to_f32(w[i]);
+        const float vb = bf16hi_to_f32(w[i]);
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            st.acc[h][2 * i] = fmaf(p[h], va, st.acc[h][2 * i]);
+            st.acc[h][2 * i + 1] = fmaf(p[h], vb, st.acc[h][2 * i + 1]);
+        }
+    }
+}
+
+// Online-softmax update with the scores of two rows (s0, s1) and their value rows.
+template <int G>
+__device__ __forceinline__ void softmax_step(HeadState<G>& st, const float (&s0)[G], const float (&s1)[G],
+                                             const RowRegs& t0, const RowRegs& t1)
+{
+    float mn[G];
+    bool grow = false;
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        mn[h] = fmaxf(st.m[h], fmaxf(s0[h], s1[h]));
+        grow |= (mn[h] > st.m[h]);
+    }
+    if (__any(grow)) {   // rescale lazily: the running maximum settles after a few rows
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            const float ms = (mn[h] == -INFINITY) ? 0.f : mn[h];
+            const float a = __builtin_amdgcn_exp2f(st.m[h] - ms);
+            st.l[h] *= a;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) st.acc[h][e] *= a;
+            st.m[h] = mn[h];
+        }
+    }
+    float p0[G], p1[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        const float ms = (st.m[h] == -INFINITY) ? 0.f : st.m[h];
+        p0[h] = __builtin_amdgcn_exp2f(s0[h] - ms);
+        p1[h] = __builtin_amdgcn_exp2f(s1[h] - ms);
+        st.l[h] += p0[h] + p1[h];
+    }
+    accumulate_v<G>(st, t0, p0);
+    accumulate_v<G>(st, t1, p1);
+}
+
+constexpr int kStrip = 128;   // rows a wave handles between two refills of its index registers
+
+template <int G>
+__global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p)
+{
+    constexpr int HB = G < 4 ? G : 4;   // heads combined per round of the epilogue
+    extern __shared__ float smem[];
+
+    const int u = blockIdx.x / p.chunks_per_unit;
+    const int cidx = blockIdx.x - u * p.chunks_per_unit;
+    int si = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxSources; ++i)
+        if (i < p.n_sources && cidx >= p.src[i].chunk0) si = i;
+    const RowSource& S = p.src[si];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int r = lane >> 3, c = lane & 7;
+
+    int count = S.count_max;
+    if (S.count_dev) {
+        const int cd = S.count_dev[u];
+        count = cd < count ? cd : count;
+    }
+    const int chunk_rows = p.chunk_rows;
+    const int begin = (cidx - S.chunk0) * chunk_rows;
+    const int end = (begin + chunk_rows < count) ? begin + chunk_rows : count;
+    float* part = p.partials + ((long long)u * p.chunks_per_unit + cidx) * G * kPartStride;
+    if (begin >= end) {   // nothing to do for this chunk: an empty partial
+        if (tid < G) {
+            part[tid * kPartStride + 0] = -INFINITY;
+            part[tid * kPartStride + 1] = 0.f;
+        }
+        return;
+    }
+
+    HeadState<G> st;
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        st.m[h] = -INFINITY;
+        st.l[h] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) st.acc[h][e] = 0.f;
+    }
+
+    const int wave_rows = chunk_rows >> 2;
+    const int w0 = begin + wave * wave_rows;
+    const int w1 = (w0 + wave_rows < end) ? w0 + wave_rows : end;
+    const uint16_t* __restrict__ Vb = S.V + (long long)u * S.unit_rows * kHeadDim;
+    const int32_t* __restrict__ rows = S.rows ? S.rows + (long long)u * S.rows_stride : nullptr;
+
+    if (S.scores == nullptr) {
+        // -------- exact rows: scores from q.k --------
+        const uint16_t* __restrict__ Kb = S.K + (long long)u * S.unit_rows * kHeadDim;
+        uint4 qlo[G], qhi[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            const uint4* qp = reinterpret_cast<const uint4*>(p.q + ((long long)u * G + h) * kHeadDim) + c;
+            qlo[h] = qp[0];
+            qhi[h] = qp[8];
+        }
+        const float scale = p.scale_log2e;
+        for (int j0 = w0; j0 < w1; j0 += kStrip) {
+            // positions of this strip's rows, two per lane, fetched with coalesced loads
+            int pa = j0 + lane, pb = j0 + 64 + lane;
+            pa = pa < end ? pa : end - 1;
+            pb = pb < end ? pb : end - 1;
+            int ia = pa, ib = pb;
+            if (rows) {
+                ia = rows[pa];
+                ib = rows[pb];
+            }
+            RowRegs cur0, cur1, nx0, nx1;
+            {
+                const int i0 = __shfl(ia, r, 64), i1 = __shfl(ia, 8 + r, 64);
+                load_row(cur0, Kb, Vb, i0, c);
+                load_row(cur1, Kb, Vb, i1, c);
+            }
+#pragma unroll
+            for (int it = 0; it < kStrip / 16; ++it) {
+                const int jj = j0 + it * 16;
+                if (jj >= w1) break;
+                const bool more = (it + 1 < kStrip / 16) && (jj + 16 < w1);
+                if (more) {
+                    const int slot = (it + 1) * 16 + r;
+                    const int src_reg = (slot < 64) ? ia : ib;
+                    const int i0 = __shfl(src_reg, slot & 63, 64);
+                    const int i1 = __shfl(src_reg, (slot + 8) & 63, 64);
+                    load_row(nx0, Kb, Vb, i0, c);
+                    load_row(nx1, Kb, Vb, i1, c);
+                }
+                float s0[G], s1[G];
+                qk_scores<G>(cur0, qlo, qhi, scale, jj + r < w1, s0);
+                qk_scores<G>(cur1, qlo, qhi, scale, jj + 8 + r < w1, s1);
+                softmax_step<G>(st, s0, s1, cur0, cur1);
+                if (more) {
+                    cur0 = nx0;
+                    cur1 = nx1;
+                }
+            }
+        }
+    } else {
+        // -------- centroid terms: ready-made logits (already in log2 units, ln N included) --------
+        const float* __restrict__ sc = S.scores + (long long)u * S.rows_stride * G;
+        for (int j0 = w0; j0 < w1; j0 += 16) {
+            const int ja = j0 + r, jb = j0 + 8 + r;
+            const bool va = ja < w1, vb = jb < w1;
+            const int pa = va ? ja : w1 - 1, pb = vb ? jb : w1 - 1;
+            const int ia = rows ? rows[pa] : pa, ib = rows ? rows[pb] : pb;
+            RowRegs t0, t1;
+            load_vrow(t0, Vb, ia, c);
+            load_vrow(t1, Vb, ib, c);
+            float s0[G], s1[G];
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                s0[h] = va ? sc[(long long)pa * G + h] : -INFINITY;
+                s1[h] = vb ? sc[(long long)pb * G + h] : -INFINITY;
+            }
+            softmax_step<G>(st, s0, s1, t0, t1);
+        }
+    }
+
+    // -------- combine the 32 row groups of the workgroup (4 waves x 8 groups), HB heads per round ----
+    float* sm_m = smem;             // [32][HB]
+    float* sm_l = smem + 128;       // [32][HB]
+    float* sm_w = smem + 256;       // [32][HB]
+    float* sm_ml = smem + 384;      // [HB][2] : merged m and l
+    float* sm_acc = smem + 400;     // [32][HB][128]
+    const int sid = wave * 8 + r;
+#pragma unroll
+    for (int hb = 0; hb < G; hb += HB) {
+        if (hb) __syncthreads();
+#pragma unroll
+        for (int hh = 0; hh < HB; ++hh) {
+            const int h = hb + hh;
+            if (h < G) {
+                if (c == 0) {
+                    sm_m[sid * HB + hh] = st.m[h];
+                    sm_l[sid * HB + hh] = st.l[h];
+                }
+                float4* dst = reinterpret_cast<float4*>(sm_acc + ((sid * HB + hh) * kHeadDim));
+                dst[2 * c] = make_float4(st.acc[h][0], st.acc[h][1], st.acc[h][2], st.acc[h][3]);
+                dst[2 * c + 1] = make_float4(st.acc[h][4], st.acc[h][5], st.acc[h][6], st.acc[h][7]);
+                dst[16 + 2 * c] = make_float4(st.acc[h][8], st.acc[h][9], st.acc[h][10], st.acc[h][11]);
+                dst[16 + 2 * c + 1] = make_float4(st.acc[h][12], st.acc[h][13], st.acc[h][14], st.acc[h][15]);
+            }
+        }
+        __syncthreads();
+        if (tid < HB && hb + tid < G) {
+            float M = -INFINITY;
+            for (int s = 0; s < 32; ++s) M = fmaxf(M, sm_m[s * HB + tid]);
+            const float Ms = (M == -INFINITY) ? 0.f : M;
+            float L = 0.f;
+            for (int s = 0; s < 32; ++s) {
+                const float w = __builtin_amdgcn_exp2f(sm_m[s * HB + tid] - Ms);
+                sm_w[s * HB + tid] = w;
+                L += sm_l[s * HB + tid] * w;
+            }
+            sm_ml[2 * tid] = M;
+            sm_ml[2 * tid + 1] = L;
+        }
+        __syncthreads();
+        for (int o = tid; o < HB * 64; o += 256) {
+            const int hh = o >> 6, dp = o & 63;
+            if (hb + hh < G) {
+                float a0 = 0.f, a1 = 0.f;
+#pragma unroll 8
+                for (int s = 0; s < 32; ++s) {
+                    const float w = sm_w[s * HB + hh];
+                    const float2 v = *reinterpret_cast<const float2*>(sm_acc + ((s * HB + hh) * kHeadDim) + 2 * dp);
+                    a0 = fmaf(w, v.x, a0);
+                    a1 = fmaf(w, v.y, a1);
+                }
+                float* ph = part + (hb + hh) * kPartStride;
+                *reinterpret_cast<float2*>(ph + 4 + 2 * dp) = make_float2(a0, a1);
+                if (dp == 0) {
+                    ph[0] = sm_ml[2 * hh];
+                    ph[1] = sm_ml[2 * hh + 1];
+                }
+            }
+        }
+    }
+}
+
+// One workgroup of 128 threads per (unit, head): thread d combines dimension d over the chunks.
+__global__ __launch_bounds__(128) void merge_kernel(const float* __restrict__ partials, int chunks_per_unit, int G,
+                                                    uint16_t* __restrict__ out, float* __restrict__ lse)
+{
+    const int uh = blockIdx.x;
+    const int u = uh / G, h = uh - u * G;
+    const int d = threadIdx.x;
+    const float* base = partials + ((long long)u * chunks_per_unit * G + h) * kPartStride;
+    const long long cs = (long long)G * kPartStride;
+    float M = -INFINITY;
+    for (int i = 0; i < chunks_per_unit; ++i) M = fmaxf(M, base[i * cs]);
+    const float Ms = (M == -INFINITY) ? 0.f : M;
+    float L = 0.f, a = 0.f;
+    for (int i = 0; i < chunks_per_unit; ++i) {
+        const float mi = base[i * cs];
+        if (mi == -INFINITY) continue;
+        const float w = __builtin_amdgcn_exp2f(mi - Ms);
+        L = fmaf(base[i * cs + 1], w, L);
+        a = fmaf(base[i * cs + 4 + d], w, a);
+    }
+    const float o = (L > 0.f) ? a / L : 0.f;
+    out[(long long)uh * kHeadDim + d] = f32_to_bf16_rne(o);
+    if (lse && d == 0) lse[uh] = (L > 0.f) ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
+}
+
+template <int G>
+hipError_t launch_vp(const ValuePassParams& p, hipStream_t stream)
+{
+    constexpr int HB = G < 4 ? G : 4;
+    const size_t smem = sizeof(float) * (size_t)(400 + 32 * HB * kHeadDim);
+    const long long blocks = (long long)p.n_units * p.chunks_per_unit;
+    if (blocks <= 0) return hipSuccess;
+    hipLaunchKernelGGL(value_pass_kernel<G>, dim3((unsigned)blocks), dim3(256), smem, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_value_pass(const ValuePassParams& p, int G, hipStream_t stream)
+{
+    switch (G) {
+        case 1: return launch_vp<1>(p, stream);
+        case 2: return launch_vp<2>(p, stream);
+        case 3: return launch_vp<3>(p, stream);
+        case 4: return launch_vp<4>(p, stream);
+        case 5: return launch_vp<5>(p, stream);
+        case 6: return launch_vp<6>(p, stream);
+        case 7: return launch_vp<7>(p, stream);
+        case 8: return launch_vp<8>(p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_merge(const float* partials, int n_units, int chunks_per_unit, int G, uint16_t* out, float* lse,
+                        hipStream_t stream)
+{
+    const long long blocks = (long long)n_units * G;
+    if (blocks <= 0) return hipSuccess;
+    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)blocks), dim3(128), 0, stream, partials, chunks_per_unit, G, out,
+                       lse);
+    return hipGetLastError();
+}
+
+}  // namespace mp
