@@ -110,7 +110,7 @@ __device__ __forceinline__ uint32_t chunk_excl_scan(uint32_t v, Scratch& s)
 // first entry (in (key, index) order) at which the running weight exceeds `budget`, and the
 // weight `acc` of all entries with key < K*.  Returns false if everything fits.
 __device__ __forceinline__ bool radix_select(const uint64_t* keys, const uint32_t* wts, int n, long long budget,
-                                             Scratch& s, uint64_t& kstar, uint64_t& acc_out)
+                                             Scratch& s, uint64_t& kstar, uint64_t& acc_out, uint32_t& ties_out)
 {
     const int tid = threadIdx.x;
     uint64_t prefix = 0;      // digits fixed so far (high bits)
@@ -174,12 +174,14 @@ __device__ __forceinline__ bool radix_select(const uint64_t* keys, const uint32_
             __syncthreads();
             kstar = s.sel_key;
             acc_out = acc;
+            ties_out = 1;
             __syncthreads();
             return true;
         }
     }
     kstar = prefix;
     acc_out = acc;
+    ties_out = s.sel_cnt;   // entries whose key equals K* exactly
     return true;
 }
 
@@ -307,7 +309,8 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(const ScoreParam
 
     // ---- budgeted selection ----
     uint64_t kstar = 0, acc = 0;
-    const bool bounded = radix_select(keys, wts, n, p.budget, S, kstar, acc);
+    uint32_t ties = 0;
+    const bool bounded = radix_select(keys, wts, n, p.budget, S, kstar, acc, ties);
     for (int i = tid; i < n; i += kThreads) {
         uint8_t f = 0;
         if (wts[i]) {
@@ -315,7 +318,7 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(const ScoreParam
             else {
                 const uint64_t k = keys[i];
                 if (k < kstar) f = 1;
-                else if (k == kstar) {
+                else if (k == kstar && ties > 1) {
                     // equal keys: lower position first; keep while the running count still fits
                     uint64_t run = acc;
                     for (int j = 0; j <= i; ++j)

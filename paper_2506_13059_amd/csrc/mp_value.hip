@@ -304,25 +304,49 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
     }
 }
 
-// One workgroup of 128 threads per (unit, head): thread d combines dimension d over the chunks.
+// One workgroup of 128 threads per (unit, head).  The chunk weights 2^(m_i - M) are computed
+// once (one chunk per thread, loads in flight together) and kept in LDS; thread d then combines
+// dimension d over the chunks with independent loads, in chunk order (bit-reproducible).
 __global__ __launch_bounds__(128) void merge_kernel(const float* __restrict__ partials, int chunks_per_unit, int G,
                                                     uint16_t* __restrict__ out, float* __restrict__ lse)
 {
+    extern __shared__ float sw[];            // [chunks_per_unit] weights
+    __shared__ float red[4];
     const int uh = blockIdx.x;
     const int u = uh / G, h = uh - u * G;
-    const int d = threadIdx.x;
+    const int d = threadIdx.x, lane = d & 63, wave = d >> 6;
     const float* base = partials + ((long long)u * chunks_per_unit * G + h) * kPartStride;
     const long long cs = (long long)G * kPartStride;
     float M = -INFINITY;
-    for (int i = 0; i < chunks_per_unit; ++i) M = fmaxf(M, base[i * cs]);
-    const float Ms = (M == -INFINITY) ? 0.f : M;
-    float L = 0.f, a = 0.f;
-    for (int i = 0; i < chunks_per_unit; ++i) {
+    for (int i = d; i < chunks_per_unit; i += 128) {
         const float mi = base[i * cs];
-        if (mi == -INFINITY) continue;
-        const float w = __builtin_amdgcn_exp2f(mi - Ms);
-        L = fmaf(base[i * cs + 1], w, L);
-        a = fmaf(base[i * cs + 4 + d], w, a);
+        sw[i] = mi;
+        M = fmaxf(M, mi);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+    if (lane == 0) red[wave] = M;
+    __syncthreads();
+    M = fmaxf(red[0], red[1]);
+    const float Ms = (M == -INFINITY) ? 0.f : M;
+    float L = 0.f;
+    for (int i = d; i < chunks_per_unit; i += 128) {
+        const float mi = sw[i];
+        const float w = (mi == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mi - Ms);
+        sw[i] = w;
+        if (w > 0.f) L = fmaf(base[i * cs + 1], w, L);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off, 64);
+    if (lane == 0) red[2 + wave] = L;
+    __syncthreads();
+    L = red[2] + red[3];
+    float a = 0.f;
+#pragma unroll 8
+    for (int i = 0; i < chunks_per_unit; ++i) {
+        const float w = sw[i];
+        const float v = base[i * cs + 4 + d];      // always a valid address; ignored when w == 0
+        a = fmaf(w > 0.f ? v : 0.f, w, a);
     }
     const float o = (L > 0.f) ? a / L : 0.f;
     out[(long long)uh * kHeadDim + d] = f32_to_bf16_rne(o);
@@ -362,8 +386,8 @@ hipError_t launch_merge(const float* partials, int n_units, int chunks_per_unit,
 {
     const long long blocks = (long long)n_units * G;
     if (blocks <= 0) return hipSuccess;
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)blocks), dim3(128), 0, stream, partials, chunks_per_unit, G, out,
-                       lse);
+    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)blocks), dim3(128), sizeof(float) * (size_t)(chunks_per_unit + 1),
+                       stream, partials, chunks_per_unit, G, out, lse);
     return hipGetLastError();
 }
 
