@@ -63,7 +63,8 @@ mp_status finalize_index(mp_ctx* ctx, const void* k, const void* v, int32_t n_to
     const int U = ctx->U;
     const long long Ncap = ctx->Ncap, tab = ctx->tab_rows;
     const int nb = (int)blocks.size();
-    std::vector<int32_t> bd(4 * (size_t)nb);
+    std::vector<int32_t>& bd = ctx->stage_blocks;
+    bd.assign(4 * (size_t)nb, 0);
     int max_kf = 0;
     for (int b = 0; b < nb; ++b) {
         bd[4 * b + 0] = blocks[b].t0; bd[4 * b + 1] = blocks[b].t1;

@@ -119,6 +119,9 @@ struct mp_ctx {
     bool decoded = false;
     int32_t n_tokens = 0, n_fine = 0, n_coarse = 0;
     std::vector<mp::BlockPlan> blocks;
+
+    // host staging for small uploads (kept alive until the next call that uploads)
+    std::vector<int32_t> stage_blocks, stage_blocks2, stage_seed_f, stage_seed_c;
 };
 
 namespace mp {

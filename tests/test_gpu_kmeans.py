@@ -1,0 +1,115 @@
+"""GPU parity: mp_cluster_kv (Lloyd k-means, blockwise, two levels, renumbering, stored tables)
+against the oracle, free-running from the same seeds.  Assignments must be bit-exact (ties to the
+lowest index); fine centroids bit-exact; coarse stored means equal up to the order of an fp64 sum."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_case(B, Hq, Hkv, n, modes, levels, nf, nc, W, alpha, iters, seed, noise=0.3):
+    from paper_2506_13059_amd import binding as mp, inputs
+    from oracle import mp_oracle as O
+    from tests.gpu_util import f64, i32
+    U = B * Hkv
+    centers = inputs.make_modes(U, modes, "cuda", seed)
+    K, V = inputs.draw_tokens(centers, n, seed + 1, noise=noise)
+    K4, V4 = K.view(B, Hkv, n, 128), V.view(B, Hkv, n, 128)
+    blocks = mp.mp_plan_blocks(n, W, alpha, nf, nc if levels == 2 else 0)
+    assert blocks == O.plan_blocks(n, W, alpha, nf, nc if levels == 2 else 0)
+    init_f, init_c = inputs.draw_seeds(U, blocks, levels, seed + 3)
+    ctx = mp.MpContext(B, Hq, Hkv, max_tokens=n, levels=levels, max_fine=nf, max_coarse=nc, block_w=W,
+                       block_alpha=alpha, max_tail=0)
+    ctx.mp_cluster_kv(K4, V4, nf, nc, iters=iters, init_fine=init_f, init_coarse=init_c if levels == 2 else None)
+    fot, cof = ctx.mp_get_assignments()
+    kc, vc, nm = ctx.mp_get_centroids(0)
+    torch.cuda.synchronize()
+    fot, kc, vc, nm = i32(fot), f64(kc), f64(vc), i32(nm)
+    K64, V64 = f64(K), f64(V)
+    if levels == 2:
+        kcc, vcc, nmc = ctx.mp_get_centroids(1)
+        torch.cuda.synchronize()
+        cof, kcc, vcc, nmc = i32(cof), f64(kcc), f64(vcc), i32(nmc)
+    for u in range(U):
+        cl = O.cluster_unit(K64[u], V64[u], blocks, init_f[u].numpy(), init_c[u].numpy() if levels == 2 else None,
+                            iters, levels)
+        np.testing.assert_array_equal(fot[u], cl["fine_of_token"], err_msg=f"unit {u} fine assignment")
+        np.testing.assert_array_equal(nm[u], cl["N_f"])
+        np.testing.assert_array_equal(kc[u], cl["Kc_f"])
+        np.testing.assert_array_equal(vc[u], cl["Vc_f"])
+        if levels == 2:
+            np.testing.assert_array_equal(cof[u], cl["coarse_of_fine"], err_msg=f"unit {u} coarse assignment")
+            np.testing.assert_array_equal(nmc[u], cl["N_c"])
+            live = cl["N_c"] > 0
+            assert (kcc[u][live] != cl["Kc_c"][live]).mean() < 1e-3
+            assert (vcc[u][live] != cl["Vc_c"][live]).mean() < 1e-3
+            np.testing.assert_allclose(kcc[u][live], cl["Kc_c"][live], rtol=2.0 ** -7, atol=1e-30)
+            np.testing.assert_array_equal(kcc[u][~live], cl["Kc_c"][~live])
+    return ctx, K4, V4
+
+
+def test_cluster_cfg0_one_level():
+    ctx, K, V = _run_case(1, 4, 1, 4096, 64, 1, 64, 0, 0, 0, iters=10, seed=11)
+    ctx.close()
+
+
+def test_cluster_two_level_blockwise_ragged():
+    # three blocks (1024, 1024, 952 tokens), 96 fine / 12 coarse in total
+    ctx, K, V = _run_case(1, 8, 2, 3000, 96, 2, 96, 12, 1024, 512, iters=4, seed=12)
+    assert ctx.mp_get_sizes()["n_blocks"] == 3
+    ctx.close()
+
+
+def test_cluster_more_centroids_than_modes_gives_near_ties_and_empties():
+    # few, tight modes and many centroids: duplicated seeds inside a mode, empty clusters, near ties
+    ctx, K, V = _run_case(2, 2, 1, 1500, 5, 2, 40, 6, 0, 0, iters=5, seed=13, noise=0.05)
+    ctx.close()
+
+
+def test_cluster_then_decode_end_to_end():
+    from tests.gpu_util import compare_decode
+    from paper_2506_13059_amd import inputs
+    ctx, K, V = _run_case(1, 4, 1, 2500, 40, 2, 80, 10, 1024, 512, iters=3, seed=14)
+    centers = inputs.make_modes(1, 40, "cuda", 14)
+    q = inputs.draw_queries(centers, 4, 1, 99, softness=0.3).view(1, 1, 4, 128)[0]
+    compare_decode(ctx, q.contiguous(), K, V, 300, 900, label="after cluster_kv")
+    ctx.close()
+
+
+def test_cluster_seeded_without_explicit_seeds_is_deterministic():
+    from paper_2506_13059_amd import binding as mp, inputs
+    centers = inputs.make_modes(2, 16, "cuda", 5)
+    K, V = inputs.draw_tokens(centers, 1200, 6)
+    K4, V4 = K.view(1, 2, 1200, 128), V.view(1, 2, 1200, 128)
+    res = []
+    for _ in range(2):
+        ctx = mp.MpContext(1, 2, 2, max_tokens=1200, levels=2, max_fine=32, max_coarse=4, max_tail=0)
+        ctx.mp_cluster_kv(K4, V4, 32, 4, iters=3, seed=77)
+        fot, cof = ctx.mp_get_assignments()
+        torch.cuda.synchronize()
+        res.append((fot.cpu(), cof.cpu()))
+        assert int(ctx.mp_get_centroids(0)[2].sum()) == 2 * 1200
+        ctx.close()
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+
+
+def test_cluster_argument_errors():
+    from paper_2506_13059_amd import binding as mp
+    ctx = mp.MpContext(1, 2, 1, max_tokens=256, levels=2, max_fine=16, max_coarse=4, max_tail=0)
+    K = torch.randn(1, 1, 256, 128, device="cuda").to(torch.bfloat16)
+    for kwargs, status in [(dict(n_fine=17, n_coarse=4), mp.MP_ECAPACITY), (dict(n_fine=16, n_coarse=5), mp.MP_ECAPACITY),
+                           (dict(n_fine=16, n_coarse=0), mp.MP_EINVAL), (dict(n_fine=16, n_coarse=4, iters=0), mp.MP_EINVAL),
+                           (dict(n_fine=2, n_coarse=4), mp.MP_EINVAL)]:
+        with pytest.raises(mp.MpError) as e:
+            ctx.mp_cluster_kv(K, K, **kwargs)
+        assert e.value.status == status, kwargs
+    bad = torch.full((1, 16), 300, dtype=torch.int32)
+    with pytest.raises(mp.MpError) as e:
+        ctx.mp_cluster_kv(K, K, 16, 4, init_fine=bad)
+    assert e.value.status == mp.MP_EINVAL
+    big = torch.randn(1, 1, 300, 128, device="cuda").to(torch.bfloat16)
+    with pytest.raises(mp.MpError) as e:
+        ctx.mp_cluster_kv(big, big, 16, 4)
+    assert e.value.status == mp.MP_ECAPACITY
+    ctx.close()
