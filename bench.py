@@ -1,0 +1,261 @@
+#!/usr/bin/env python3
+"""Benchmark of the Multipole Attention decode path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3_128k_b16]
+
+One "step" = one decode step of the whole batch: coarse scoring + selection, fine scoring +
+selection, the value pass over the selected keys and the centroid terms, and the merge, with the
+clustered KV cache already resident in HBM (built once, before the timed region, by mp_cluster_kv;
+its time is reported next to the decode numbers).  Queries rotate over 16 sets so that successive
+steps select different clusters.  Prints ONE JSON line.
+
+`value` is the decode latency (us per step) at the first key budget of the workload; the other
+budgets, the dense bf16 attention kernel of the same library on the same tensors, the per-stage
+split, the achieved HBM rate, the roofline of the dominant kernel (the value pass) and the CPU
+oracle timed on this machine's host cores are reported in the same line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(counters, G):
+    """Bytes a decode step must read, from the device counters (summed over units).
+
+    per unit: 512 B per exactly attended key (key row + value row) + 4 B of row index,
+              256 B per scored centroid (fine and coarse key centroids),
+              256 B + 4*G B + 4 B per centroid term (value centroid row, its logits, its row index).
+    Returns (whole step, value pass only)."""
+    keys = int(counters[:, 0].sum())
+    scored = int(counters[:, 1].sum() + counters[:, 2].sum())
+    terms = int(counters[:, 3].sum())
+    value_pass = keys * (512 + 4) + terms * (256 + 4 * G + 4)
+    return value_pass + scored * 256, value_pass
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="cfg3_128k_b16")
+    ap.add_argument("--coarse-mult", type=int, default=2, help="coarse budget = mult * key budget")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one process, one device); --gpus must be 1. "
+              "Units (sequence x KV head) shard over GPUs without any exchange; see DESIGN.md.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2506_13059_amd import binding as mp, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    w = inputs.WORKLOADS[args.workload]
+    dev = "cuda"
+    n_sets = 16
+    t0 = time.time()
+    data = inputs.make_workload(w, dev, seed=1000 * list(inputs.WORKLOADS).index(args.workload), n_query_sets=n_sets)
+    K, V, Q = data["K"], data["V"], data["q"]
+    torch.cuda.synchronize()
+    t_gen = time.time() - t0
+
+    ctx = mp.MpContext(w.batch, w.n_q_heads, w.n_kv_heads, max_tokens=w.context, levels=w.levels, max_fine=w.n_fine,
+                       max_coarse=w.n_coarse, block_w=w.block_w, block_alpha=w.block_alpha, max_tail=256)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    ctx.mp_cluster_kv(K, V, w.n_fine, w.n_coarse, iters=w.kmeans_iters, init_fine=data["init_fine"],
+                      init_coarse=data["init_coarse"] if w.levels == 2 else None)
+    e1.record()
+    torch.cuda.synchronize()
+    cluster_ms = e0.elapsed_time(e1)
+
+    out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.bfloat16, device=dev)
+    G = w.group
+    results = {}
+    for kb in w.key_budgets:
+        cb = args.coarse_mult * kb
+        for i in range(args.warmup):
+            ctx.mp_decode_attention(Q[i % n_sets], kb, cb, out=out)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            ctx.mp_decode_attention(Q[i % n_sets], kb, cb, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / args.steps * 1e3
+        # per-stage durations (HIP events recorded by the library on the launch stream) and byte counters
+        ctx.mp_enable_stage_timing(True)
+        stage = dict(coarse_ms=0.0, fine_ms=0.0, value_ms=0.0, merge_ms=0.0)
+        step_bytes = vp_bytes = 0
+        n_t = min(args.steps, 64)
+        for i in range(n_t):
+            ctx.mp_decode_attention(Q[i % n_sets], kb, cb, out=out)
+            t = ctx.mp_get_stage_timing()
+            for k_ in stage:
+                stage[k_] += t[k_] / n_t
+            if i < n_sets:
+                c = ctx.mp_get_counters().cpu()
+                sb, vb = algorithmic_bytes(c, G)
+                step_bytes += sb / min(n_t, n_sets)
+                vp_bytes += vb / min(n_t, n_sets)
+        ctx.mp_enable_stage_timing(False)
+        results[kb] = dict(us=us, stage_us={k_[:-3]: v * 1e3 for k_, v in stage.items()}, step_bytes=step_bytes,
+                           vp_bytes=vp_bytes, gbps=step_bytes / us / 1e3,
+                           vp_gbps=vp_bytes / (stage["value_ms"] * 1e3) / 1e3 if stage["value_ms"] > 0 else 0.0)
+
+    # dense comparison kernel, same tensors
+    ws = torch.empty(max(mp.mp_dense_workspace_bytes(w.batch, w.n_q_heads, w.n_kv_heads, w.context), 16),
+                     dtype=torch.uint8, device=dev)
+    n_dense = max(5, min(args.steps, 30))
+    for i in range(3):
+        mp.mp_dense_attention(Q[i % n_sets], K, V, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(n_dense):
+        mp.mp_dense_attention(Q[i % n_sets], K, V, out=out, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    dense_us = e0.elapsed_time(e1) / n_dense * 1e3
+    dense_bytes = 2 * K.numel() * 2
+    dense_gbps = dense_bytes / dense_us / 1e3
+
+    kb0 = w.key_budgets[0]
+    r0 = results[kb0]
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(ctx, w, K, V, Q, kb0, args.coarse_mult * kb0)
+
+    line = {
+        "metric": "decode-attention us/step + achieved HBM GB/s (% peak) vs dense attn, 128K ctx",
+        "value": round(r0["us"], 2),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(r0["us"] / 1e3, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "context": w.context, "levels": w.levels, "n_fine": w.n_fine, "n_coarse": w.n_coarse,
+                   "key_budget": kb0, "coarse_budget": args.coarse_mult * kb0, "block_w": w.block_w,
+                   "kmeans_iters": w.kmeans_iters, "query_sets": n_sets},
+        "achieved_hbm_gbps": round(r0["gbps"], 1),
+        "achieved_hbm_frac_of_peak": round(r0["gbps"] / HBM_PEAK_GBPS, 4),
+        "algorithmic_bytes_per_step": int(r0["step_bytes"]),
+        "stage_us": {k_: round(v, 2) for k_, v in r0["stage_us"].items()},
+        "dense_us_per_step": round(dense_us, 2),
+        "dense_hbm_gbps": round(dense_gbps, 1),
+        "speedup_vs_dense": round(dense_us / r0["us"], 3),
+        "other_budgets": {str(kb): {"us_per_step": round(r["us"], 2), "achieved_hbm_gbps": round(r["gbps"], 1),
+                                    "stage_us": {k_: round(v, 2) for k_, v in r["stage_us"].items()},
+                                    "speedup_vs_dense": round(dense_us / r["us"], 3)}
+                          for kb, r in results.items() if kb != kb0},
+        "cluster_build_ms": round(cluster_ms, 2),
+        "input_generation_s": round(t_gen, 2),
+        "paper_context": "paper reports up to 4.5x attention speedup vs FlashDecoding on an NVIDIA A6000 "
+                         "(2.8x on A100), batch 16, 128K context",
+        "roofline": {"bound": "hbm", "kernel": "value_pass_kernel", "achieved": round(r0["vp_gbps"], 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(r0["vp_gbps"] / HBM_PEAK_GBPS, 4),
+                     "traffic": measured_traffic(w.name, kb0),
+                     "bytes_per_launch": int(r0["vp_bytes"]), "avg_launch_us": round(r0["stage_us"]["value"], 2)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+def measured_traffic(workload, key_budget):
+    """HBM bytes per value-pass launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), taken
+    from profiles/traffic.json when the measurement has been recorded for this workload; else None."""
+    p = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(p):
+        return None
+    try:
+        with open(p) as f:
+            t = json.load(f)
+        return t.get(f"{workload}:{key_budget}")
+    except Exception:
+        return None
+
+
+def cpu_baseline(ctx, w, K, V, Q, kb, cb):
+    """The fp64 oracle as it stands, on a bounded sample of units of the same workload and step."""
+    import numpy as np
+    import torch
+    from oracle import mp_oracle as O
+
+    sample = min(8, ctx.U)
+    units = list(range(sample))
+    fot, cof = ctx.mp_get_assignments()
+    kc_f, vc_f, n_f = ctx.mp_get_centroids(0)
+    torch.cuda.synchronize()
+    f64 = lambda t: t.to(torch.float64).cpu().numpy()
+    n, d, G = w.context, 128, w.group
+    Ku = K.reshape(ctx.U, n, d)[:sample]
+    Vu = V.reshape(ctx.U, n, d)[:sample]
+    args = dict(
+        q=np.ascontiguousarray(f64(Q[0].reshape(ctx.U, G, d)[:sample])),
+        K=np.ascontiguousarray(f64(Ku)), V=np.ascontiguousarray(f64(Vu)),
+        fot=np.ascontiguousarray(fot[:sample].cpu().numpy().astype(np.int32)),
+        Kc_f=np.ascontiguousarray(f64(kc_f[:sample])), Vc_f=np.ascontiguousarray(f64(vc_f[:sample])),
+        N_f=np.ascontiguousarray(n_f[:sample].cpu().numpy().astype(np.int32)))
+    Cf = args["N_f"].shape[1]
+    if w.levels == 2:
+        kc_c, vc_c, n_c = ctx.mp_get_centroids(1)
+        torch.cuda.synchronize()
+        args.update(cof=np.ascontiguousarray(cof[:sample].cpu().numpy().astype(np.int32)),
+                    Kc_c=np.ascontiguousarray(f64(kc_c[:sample])), Vc_c=np.ascontiguousarray(f64(vc_c[:sample])),
+                    N_c=np.ascontiguousarray(n_c[:sample].cpu().numpy().astype(np.int32)))
+        Cc = args["N_c"].shape[1]
+    else:
+        Cc = 0
+    import ctypes as C
+    L = O.lib()
+    out = np.zeros((sample, G, d))
+    lse = np.zeros((sample, G))
+    prom = np.zeros((sample, max(Cc, 1)), dtype=np.uint8)
+    sel = np.zeros((sample, Cf), dtype=np.uint8)
+    dp = lambda a: None if a is None else a.ctypes.data_as(C.POINTER(C.c_double))
+    ip = lambda a: None if a is None else a.ctypes.data_as(C.POINTER(C.c_int32))
+    bp = lambda a: a.ctypes.data_as(C.POINTER(C.c_uint8))
+
+    def run():
+        return L.mpo_decode_batch(
+            C.c_int(sample), dp(args["q"]), C.c_int(G), C.c_int(d), C.c_double(1 / math.sqrt(d)), dp(args["K"]),
+            dp(args["V"]), C.c_int(n), ip(args["fot"]), C.c_int(Cf), dp(args["Kc_f"]), dp(args["Vc_f"]),
+            ip(args["N_f"]), C.c_int(w.levels), C.c_int(Cc), ip(args.get("cof")), dp(args.get("Kc_c")),
+            dp(args.get("Vc_c")), ip(args.get("N_c")), None, None, C.c_int(0), C.c_int64(kb), C.c_int64(cb),
+            C.c_int(1), dp(out), dp(lse), bp(prom), bp(sel))
+
+    assert run() == 0
+    reps, t0 = 0, time.time()
+    while True:
+        run()
+        reps += 1
+        el = time.time() - t0
+        if el >= 10.0 or reps >= 200:
+            break
+    per_unit_us = el / reps / sample * 1e6
+    return {"value": round(per_unit_us * ctx.U, 1), "unit": "us/step", "cores": O.num_threads(), "kind": "oracle",
+            "sample": f"{sample} of {ctx.U} units of {w.name} (same clustering, query set 0, key budget {kb}), "
+                      f"{reps} repetitions in {el:.1f} s, scaled to {ctx.U} units"}
+
+
+if __name__ == "__main__":
+    main()

@@ -146,7 +146,7 @@ mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* v, int32_t n
  *   n_new_coarse   coarse clusters added (levels == 2), 0 <= n_new_coarse <= n_new_fine
  *   refine_iters   Lloyd iterations over the last block after the one-shot update (Sec. 5.1: 3)
  *   split_iters    Lloyd iterations used for the two fresh clusterings at a split (Sec. 5.1: 10)
- *   seeds          host int32, layout documented in DESIGN notes of mp_update_seed_count();
+ *   seeds          host int32 [B*Hkv, n_new_fine + n_new_coarse (+ split seeds)], see below;
  *                  NULL: drawn from `seed`.
  * Errors: MP_ESTATE (no index yet), MP_ECAPACITY, MP_EINVAL, MP_EHIP.
  * ------------------------------------------------------------------------------------------- */
@@ -187,6 +187,17 @@ mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* v_new, 
 mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, const void* v_tail,
                               int32_t n_tail, int32_t key_budget, int32_t coarse_budget,
                               uint32_t flags, void* out, float* lse, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage timing (for benchmarks).  While enabled, mp_decode_attention records HIP events on the
+ * call's own stream before and after each of its launches.  mp_get_stage_timing waits for the last
+ * timed call and writes its four durations in milliseconds:
+ * ms[0] coarse scoring + selection (0 with one level), ms[1] fine scoring + selection,
+ * ms[2] value pass (the kernel that streams the selected keys / values and the centroid terms),
+ * ms[3] merge.  Errors: MP_ESTATE if no timed call has been made.
+ * ------------------------------------------------------------------------------------------- */
+mp_status mp_enable_stage_timing(mp_ctx* ctx, int32_t enable);
+mp_status mp_get_stage_timing(mp_ctx* ctx, float* ms);
 
 /* ---------------------------------------------------------------------------------------------
  * Introspection (for parity tests and accounting).  Outputs are device buffers of the stated

@@ -21,7 +21,7 @@ EXPORTS = [
     "mp_create", "mp_destroy", "mp_last_error", "mp_device_bytes", "mp_plan_blocks", "mp_cluster_kv",
     "mp_set_clustering", "mp_update_clusters", "mp_decode_attention", "mp_get_sizes", "mp_get_assignments",
     "mp_get_centroids", "mp_get_selection", "mp_get_counters", "mp_get_layout", "mp_dense_workspace_bytes",
-    "mp_dense_attention", "mp_version",
+    "mp_dense_attention", "mp_version", "mp_enable_stage_timing", "mp_get_stage_timing",
 ]
 
 
@@ -63,6 +63,8 @@ def lib():
         L.mp_set_clustering.argtypes = [vp, vp, vp, i32, vp, i32, vp, i32, vp]
         L.mp_update_clusters.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, u64, vp, vp]
         L.mp_decode_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, u32, vp, vp, vp]
+        L.mp_enable_stage_timing.argtypes = [vp, i32]
+        L.mp_get_stage_timing.argtypes = [vp, vp]
         L.mp_get_sizes.argtypes = [vp, vp, vp, vp, vp]
         L.mp_get_assignments.argtypes = [vp, vp, vp, vp]
         L.mp_get_centroids.argtypes = [vp, i32, vp, vp, vp, vp]
@@ -188,6 +190,14 @@ class MpContext:
                                        coarse_budget, flags, _ptr(out), _ptr(lse), _stream())
         _check(st, self.h)
         return out
+
+    def mp_enable_stage_timing(self, enable=True):
+        _check(lib().mp_enable_stage_timing(self.h, 1 if enable else 0), self.h)
+
+    def mp_get_stage_timing(self):
+        buf = (C.c_float * 4)()
+        _check(lib().mp_get_stage_timing(self.h, C.cast(buf, C.c_void_p)), self.h)
+        return dict(coarse_ms=buf[0], fine_ms=buf[1], value_ms=buf[2], merge_ms=buf[3])
 
     def mp_get_sizes(self):
         v = [C.c_int32() for _ in range(4)]

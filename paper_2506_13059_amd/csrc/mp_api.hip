@@ -245,6 +245,8 @@ void mp_destroy(mp_ctx* ctx)
 {
     if (!ctx) return;
     (void)hipDeviceSynchronize();
+    for (hipEvent_t e : ctx->ev)
+        if (e) (void)hipEventDestroy(e);
     free_all(ctx);
     delete ctx;
 }
@@ -361,6 +363,7 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
         c.cstart = ctx->cstart; c.cstart_stride = ctx->Ccap + 1; c.cand_out = ctx->cand; c.cand_out_stride = ctx->Fcap;
         c.n_cand_out = ctx->n_cand; c.unprom_lse_out = ctx->unprom_lse; c.mp_append = 0;
         c.smem_cap = ctx->n_coarse;
+        if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[0], s));
         MP_HIP(ctx, launch_score_select(c, s));
     }
     {
@@ -373,7 +376,9 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
         f.fstart = ctx->fstart; f.fstart_stride = ctx->Fcap + 1; f.rows_out = ctx->rows; f.rows_stride = ctx->Ncap;
         f.n_rows_out = ctx->n_rows; f.mp_append = two ? 1 : 0;
         f.smem_cap = ctx->n_fine;
+        if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[1], s));
         MP_HIP(ctx, launch_score_select(f, s));
+        if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[2], s));
     }
 
     ValuePassParams vp{};
@@ -407,8 +412,37 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
     vp.chunks_per_unit = chunk0;
     if (chunk0 > ctx->Pcap) return fail(ctx, MP_ECAPACITY, "mp_decode_attention: %d chunks > workspace %d", chunk0, ctx->Pcap);
     if (chunk0 > 0) MP_HIP(ctx, launch_value_pass(vp, G, s));
+    if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[3], s));
     MP_HIP(ctx, launch_merge(ctx->partials, U, chunk0, G, (uint16_t*)out, lse, s));
+    if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[4], s));
+    ctx->timed_levels = two ? 2 : 1;
     ctx->decoded = true;
+    return MP_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Stage timing
+// ------------------------------------------------------------------------------------------------
+mp_status mp_enable_stage_timing(mp_ctx* ctx, int32_t enable)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_enable_stage_timing: null context");
+    if (enable && !ctx->ev[0])
+        for (hipEvent_t& e : ctx->ev) MP_HIP(ctx, hipEventCreate(&e));
+    ctx->timing = enable != 0;
+    ctx->timed_levels = 0;
+    return MP_OK;
+}
+
+mp_status mp_get_stage_timing(mp_ctx* ctx, float* ms)
+{
+    if (!ctx || !ms) return fail(ctx, MP_EINVAL, "mp_get_stage_timing: null pointer");
+    if (!ctx->timing || !ctx->timed_levels) return fail(ctx, MP_ESTATE, "mp_get_stage_timing: no timed decode call yet");
+    MP_HIP(ctx, hipEventSynchronize(ctx->ev[4]));
+    ms[0] = 0.f;
+    if (ctx->timed_levels == 2) MP_HIP(ctx, hipEventElapsedTime(&ms[0], ctx->ev[0], ctx->ev[1]));
+    MP_HIP(ctx, hipEventElapsedTime(&ms[1], ctx->ev[1], ctx->ev[2]));
+    MP_HIP(ctx, hipEventElapsedTime(&ms[2], ctx->ev[2], ctx->ev[3]));
+    MP_HIP(ctx, hipEventElapsedTime(&ms[3], ctx->ev[3], ctx->ev[4]));
     return MP_OK;
 }
 

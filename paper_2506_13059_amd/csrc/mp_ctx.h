@@ -120,6 +120,11 @@ struct mp_ctx {
     int32_t n_tokens = 0, n_fine = 0, n_coarse = 0;
     std::vector<mp::BlockPlan> blocks;
 
+    // optional stage timing of mp_decode_attention: events before coarse, fine, value pass, merge, and after
+    bool timing = false;
+    int timed_levels = 0;
+    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+
     // host staging for small uploads (kept alive until the next call that uploads)
     std::vector<int32_t> stage_blocks, stage_blocks2, stage_seed_f, stage_seed_c;
 };
