@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--workload", default="cfg3_128k_b16")
     ap.add_argument("--coarse-mult", type=int, default=2, help="coarse budget = mult * key budget")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one process, one device); --gpus must be 1. "
@@ -81,6 +83,14 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     cluster_ms = e0.elapsed_time(e1)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.bfloat16, device=dev)
     G = w.group
@@ -249,7 +259,7 @@ def cpu_baseline(ctx, w, K, V, Q, kb, cb):
         run()
         reps += 1
         el = time.time() - t0
-        if el >= 10.0 or reps >= 200:
+        if el >= 10.0 or reps >= 5000:
             break
     per_unit_us = el / reps / sample * 1e6
     return {"value": round(per_unit_us * ctx.U, 1), "unit": "us/step", "cores": O.num_threads(), "kind": "oracle",
