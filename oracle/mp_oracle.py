@@ -303,3 +303,110 @@ def clustering_from_assignment(K, V, fine_of_token, n_fine, coarse_of_fine=None,
         Svc, _ = member_sums(V, ac, n_coarse)
         cl.update(coarse_of_fine=cof, Kc_c=_mean_bf16(Skc, N_c), Vc_c=_mean_bf16(Svc, N_c), N_c=N_c)
     return cl
+
+
+
+# --------------------------------------------------------------------------------------------
+# Online cluster update (Sec. 3.3): append tokens to the last block, seed extra centroids from the
+# appended tokens, assign the appended tokens once to their nearest centroid and move the touched
+# centroids by a running mean, then run a few full Lloyd iterations over the last block; the
+# coarse level is refreshed the same way on the block's fine centroids; when the last block reaches
+# W + alpha tokens its first W tokens are split off and both parts are clustered afresh.
+# --------------------------------------------------------------------------------------------
+
+def update_seed_counts(blocks, n_new, n_new_fine, n_new_coarse, block_w, block_alpha, levels):
+    """Sizes of the seed lists one update consumes, in order: new fine seeds (indices into the
+    appended tokens), new coarse seeds (indices into the new fine clusters), and -- only if the
+    update makes the last block reach W+alpha tokens -- fresh fine seeds for its first W tokens
+    (token indices inside that part), for the remaining tokens, then fresh coarse seeds for the two
+    parts (fine-cluster indices inside each part)."""
+    b = blocks[-1]
+    nb = b["t1"] - b["t0"] + n_new
+    kf = b["f1"] - b["f0"] + n_new_fine
+    kc = (b["c1"] - b["c0"] + n_new_coarse) if levels == 2 else 0
+    counts = [n_new_fine, n_new_coarse if levels == 2 else 0, 0, 0, 0, 0]
+    if block_w > 0 and nb >= block_w + block_alpha:
+        kf1 = kf * block_w // nb
+        kc1 = kc * block_w // nb
+        counts[2:] = [kf1, kf - kf1, kc1, kc - kc1]
+    return counts
+
+
+def _replace_last_block(cl, K, V, blocks, parts):
+    """New clustering dict: all blocks but the last as they are, the last one replaced by `parts`
+    (one or two finalized blocks whose ranges are blocks[-len(parts):])."""
+    levels = int(cl["levels"])
+    old_last = cl["blocks"][-1]
+    t0, f0, c0 = old_last["t0"], old_last["f0"], old_last["c0"]
+    out = dict(K=K, V=V, levels=levels, blocks=[dict(b) for b in blocks])
+    fot = np.concatenate([cl["fine_of_token"][:t0]] +
+                         [p["fine_of_token"] + b["f0"] for b, p in zip(blocks[-len(parts):], parts)]).astype(np.int32)
+    out["fine_of_token"] = fot
+    for key in ("Kc_f", "Vc_f", "N_f"):
+        out[key] = np.concatenate([cl[key][:f0]] + [p[key] for p in parts], axis=0)
+    if levels == 2:
+        out["coarse_of_fine"] = np.concatenate(
+            [cl["coarse_of_fine"][:f0]] + [p["coarse_of_fine"] + b["c0"] for b, p in zip(blocks[-len(parts):], parts)]
+        ).astype(np.int32)
+        for key in ("Kc_c", "Vc_c", "N_c"):
+            out[key] = np.concatenate([cl[key][:c0]] + [p[key] for p in parts], axis=0)
+    return out
+
+
+def update_unit(cl, K_new, V_new, n_new_fine, n_new_coarse, seeds, refine_iters, block_w, block_alpha,
+                split_iters=10):
+    """Apply one online update to the clustering dict `cl` of a unit; returns the new dict.
+    seeds: int32 list laid out as described by :func:`update_seed_counts`."""
+    K_new, V_new = _f64(K_new), _f64(V_new)
+    levels = int(cl["levels"])
+    blocks = [dict(b) for b in cl["blocks"]]
+    b = blocks[-1]
+    t0, t1, f0, f1, c0, c1 = b["t0"], b["t1"], b["f0"], b["f1"], b["c0"], b["c1"]
+    n_new = K_new.shape[0]
+    counts = update_seed_counts(blocks, n_new, n_new_fine, n_new_coarse, block_w, block_alpha, levels)
+    seeds = np.asarray(seeds, dtype=np.int64)
+    assert seeds.shape[0] == sum(counts)
+    cuts = np.cumsum([0] + counts)
+    sd = [seeds[cuts[i]:cuts[i + 1]] for i in range(6)]
+    K = np.concatenate([cl["K"], K_new])
+    V = np.concatenate([cl["V"], V_new])
+    Kb, Vb = K[t0:], V[t0:]
+    nb = Kb.shape[0]
+    kf_old, kf = f1 - f0, f1 - f0 + n_new_fine
+    kc_old, kc = c1 - c0, c1 - c0 + (n_new_coarse if levels == 2 else 0)
+
+    # working centroids of the block: the stored fine key centroids, plus the new seeds
+    Cw = np.concatenate([cl["Kc_f"][f0:f1], K_new[sd[0]]]) if n_new_fine else cl["Kc_f"][f0:f1].copy()
+    Nw = np.concatenate([cl["N_f"][f0:f1], np.zeros(n_new_fine, dtype=np.int32)]).astype(np.int64)
+    # one-shot assignment of the appended tokens against frozen centroids
+    a_new = assign(K_new, Cw)
+    # running mean of the touched centroids: c <- bf16((N c + sum of newly assigned keys) / (N + n))
+    Cw = Cw.copy()
+    for j in np.unique(a_new):
+        s = Nw[j] * Cw[j]
+        members = np.flatnonzero(a_new == j)
+        for t in members:
+            s = s + K_new[t]
+        Cw[j] = round_bf16(s / float(Nw[j] + members.size))
+    a = np.concatenate([cl["fine_of_token"][t0:t1] - f0, a_new]).astype(np.int32)
+    # refinement: full Lloyd iterations over the last block
+    if refine_iters > 0:
+        Cw, a, _ = lloyd_from(Kb, Cw, refine_iters)
+    parent = Ccw = None
+    if levels == 2:
+        Ccw = cl["Kc_c"][c0:c1]
+        if n_new_coarse:
+            Ccw = np.concatenate([Ccw, Cw[kf_old + sd[1]]])
+        Ccw, parent, _ = lloyd_from(Cw, Ccw, max(1, refine_iters))
+    part = finalize_block(Kb, Vb, a, Cw, parent, kc, Ccw)
+    b.update(t1=t0 + nb, f1=f0 + kf, c1=c0 + kc)
+    out = _replace_last_block(cl, K, V, blocks, [part])
+
+    if counts[2] > 0:   # the last block reached W + alpha tokens: split it
+        W = block_w
+        b1 = dict(t0=t0, t1=t0 + W, f0=f0, f1=f0 + counts[2], c0=c0, c1=c0 + counts[4])
+        b2 = dict(t0=t0 + W, t1=t0 + nb, f0=b1["f1"], f1=f0 + kf, c0=b1["c1"], c1=c0 + kc)
+        p1 = cluster_block(Kb[:W], Vb[:W], _i32(sd[2]), _i32(sd[4]) if levels == 2 else None, split_iters, levels)
+        p2 = cluster_block(Kb[W:], Vb[W:], _i32(sd[3]), _i32(sd[5]) if levels == 2 else None, split_iters, levels)
+        out = _replace_last_block(cl, K, V, blocks[:-1] + [b1, b2], [p1, p2])
+    return out
