@@ -136,20 +136,40 @@ mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* v, int32_t n
 
 /* ---------------------------------------------------------------------------------------------
  * mp_update_clusters -- append n_new tokens per unit to the last block and refresh its clusters
- * (Sec. 3.3: extra centroids sampled from the appended tokens, one-shot nearest-centroid
- * assignment of the appended tokens with a running-mean update of the touched centroids, then a
- * few full Lloyd iterations over the last block; when the last block reaches W+alpha tokens its
- * first W tokens are split off and clustered as a block of their own).
+ * (Sec. 3.3; the coarse level follows Sec. 3.4's remark that the blockwise update applies at every
+ * level).  Per unit, with the last block's fine clusters [f0,f1) and coarse clusters [c0,c1):
+ *
+ *   1. n_new_fine new fine clusters are appended (ids f1..), each seeded with one appended key.
+ *   2. one-shot step: every appended token is assigned to its nearest centroid among the block's
+ *      stored fine key centroids and the new seeds (centroids frozen); every touched centroid moves
+ *      to bf16((N c + sum of its newly assigned keys, sequence order) / (N + n)).
+ *   3. refine_iters full Lloyd iterations over all tokens of the last block, from those centroids
+ *      (refine_iters == 0: old tokens keep their cluster, appended ones keep the one-shot choice).
+ *   4. two levels: n_new_coarse new coarse clusters are appended, each seeded with the working
+ *      centroid of one NEW fine cluster; max(1, refine_iters) Lloyd iterations over the block's fine
+ *      working centroids, starting from the stored coarse key centroids and the seeds.
+ *   5. the last block is renumbered, re-stored and its tables recomputed exactly as in
+ *      mp_cluster_kv (stored centroids = bf16 means of the members; empty clusters keep their
+ *      working centroid).  Earlier blocks are untouched.
+ *   6. if the last block now holds >= block_w + block_alpha tokens (block_w > 0), its first block_w
+ *      tokens become a block of their own and the rest the new last block; both are clustered
+ *      afresh (split_iters Lloyd iterations per level, Sec. 5.1 uses 10) with the block's kf fine
+ *      and kc coarse clusters shared out as kf*block_w/nb (integer division) to the first part and
+ *      the remainder to the second, nb = tokens in the block.
  *
  *   k_new, v_new   device bf16 [B, Hkv, n_new, 128]
- *   n_new_fine     fine clusters added to the last block, 0 <= n_new_fine <= n_new
- *   n_new_coarse   coarse clusters added (levels == 2), 0 <= n_new_coarse <= n_new_fine
- *   refine_iters   Lloyd iterations over the last block after the one-shot update (Sec. 5.1: 3)
- *   split_iters    Lloyd iterations used for the two fresh clusterings at a split (Sec. 5.1: 10)
- *   seeds          host int32 [B*Hkv, n_new_fine + n_new_coarse (+ split seeds)], see below;
- *                  NULL: drawn from `seed`.
- * Errors: MP_ESTATE (no index yet), MP_ECAPACITY, MP_EINVAL, MP_EHIP.
+ *   n_new_fine     0 <= n_new_fine <= n_new;  n_new_coarse: 0 <= n_new_coarse <= n_new_fine
+ *   seeds          host int32 [B*Hkv, total], total and the six list lengths from
+ *                  mp_update_seed_counts(): {n_new_fine indices into the appended tokens,
+ *                  n_new_coarse indices into the new fine clusters, and -- only when step 6 applies --
+ *                  fine seeds of the first part (token index inside it), fine seeds of the second
+ *                  part, coarse seeds of the first part (fine-cluster index inside it), coarse seeds
+ *                  of the second part}; every list holds distinct indices.  NULL: drawn from `seed`.
+ * The last block may grow to at most 2*block_w tokens by one call (any size when block_w == 0, up
+ * to max_tokens).  Errors: MP_ESTATE (no index yet), MP_ECAPACITY, MP_EINVAL, MP_EHIP.
  * ------------------------------------------------------------------------------------------- */
+int32_t mp_update_seed_counts(const mp_ctx* ctx, int32_t n_new, int32_t n_new_fine, int32_t n_new_coarse,
+                              int32_t* counts /* host int32 [6] */);   /* returns total, -1 on bad arguments */
 mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* v_new, int32_t n_new,
                              int32_t n_new_fine, int32_t n_new_coarse, int32_t refine_iters,
                              int32_t split_iters, uint64_t seed, const int32_t* seeds, void* stream);

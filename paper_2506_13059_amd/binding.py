@@ -21,7 +21,7 @@ EXPORTS = [
     "mp_create", "mp_destroy", "mp_last_error", "mp_device_bytes", "mp_plan_blocks", "mp_cluster_kv",
     "mp_set_clustering", "mp_update_clusters", "mp_decode_attention", "mp_get_sizes", "mp_get_assignments",
     "mp_get_centroids", "mp_get_selection", "mp_get_counters", "mp_get_layout", "mp_dense_workspace_bytes",
-    "mp_dense_attention", "mp_version", "mp_enable_stage_timing", "mp_get_stage_timing",
+    "mp_dense_attention", "mp_version", "mp_enable_stage_timing", "mp_get_stage_timing", "mp_update_seed_counts",
 ]
 
 
@@ -63,6 +63,8 @@ def lib():
         L.mp_set_clustering.argtypes = [vp, vp, vp, i32, vp, i32, vp, i32, vp]
         L.mp_update_clusters.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, u64, vp, vp]
         L.mp_decode_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, u32, vp, vp, vp]
+        L.mp_update_seed_counts.argtypes = [vp, i32, i32, i32, vp]
+        L.mp_update_seed_counts.restype = i32
         L.mp_enable_stage_timing.argtypes = [vp, i32]
         L.mp_get_stage_timing.argtypes = [vp, vp]
         L.mp_get_sizes.argtypes = [vp, vp, vp, vp, vp]
@@ -180,6 +182,13 @@ class MpContext:
         st = lib().mp_update_clusters(self.h, _ptr(k_new), _ptr(v_new), n_new, n_new_fine, n_new_coarse,
                                       refine_iters, split_iters, seed, s_ptr, _stream())
         _check(st, self.h)
+
+    def mp_update_seed_counts(self, n_new, n_new_fine, n_new_coarse=0):
+        buf = (C.c_int32 * 6)()
+        t = lib().mp_update_seed_counts(self.h, n_new, n_new_fine, n_new_coarse, C.cast(buf, C.c_void_p))
+        if t < 0:
+            raise MpError(MP_EINVAL, "mp_update_seed_counts: invalid arguments or no index yet")
+        return list(buf)
 
     def mp_decode_attention(self, q, key_budget, coarse_budget=0, k_tail=None, v_tail=None, out=None, lse=None,
                             flags=0):

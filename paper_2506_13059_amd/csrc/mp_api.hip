@@ -25,6 +25,9 @@ mp_status cluster_kv_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_t
 mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* v_new, int32_t n_new, int32_t n_new_fine,
                                int32_t n_new_coarse, int32_t refine_iters, int32_t split_iters, uint64_t seed,
                                const int32_t* seeds, hipStream_t s);
+mp_status set_clustering_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, const int32_t* fine_of_token,
+                              int32_t n_fine, const int32_t* coarse_of_fine, int32_t n_coarse, hipStream_t s);
+void update_seed_counts(const mp_ctx* ctx, int n_new, int n_new_fine, int n_new_coarse, int32_t counts[6]);
 
 thread_local std::string g_err;   // errors of context-free calls
 
@@ -47,71 +50,6 @@ int pick_chunk_rows(long long n_rows_per_unit, int n_units)
     int cr = kChunkRowsMin;
     while (cr < 4096 && n_units * ((n_rows_per_unit + cr - 1) / cr) > 8192) cr *= 2;
     return cr;
-}
-
-// Build the stored layout and tables from ctx->fot (fine id of each token) and ctx->cof (coarse id
-// of each fine cluster, non-decreasing), reading the caller's K / V in sequence order.
-// key_fallback: Kc already holds the key centroids to keep for empty clusters (else zeros).
-mp_status finalize_index(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, int32_t n_fine,
-                         int32_t n_coarse, const std::vector<BlockPlan>& blocks, bool key_fallback, hipStream_t s)
-{
-#define MP_HIPX(expr)                                                                              \
-    do {                                                                                           \
-        hipError_t e_ = (expr);                                                                    \
-        if (e_ != hipSuccess) return fail(ctx, MP_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
-    } while (0)
-    const int U = ctx->U;
-    const long long Ncap = ctx->Ncap, tab = ctx->tab_rows;
-    const int nb = (int)blocks.size();
-    std::vector<int32_t>& bd = ctx->stage_blocks;
-    bd.assign(4 * (size_t)nb, 0);
-    int max_kf = 0;
-    for (int b = 0; b < nb; ++b) {
-        bd[4 * b + 0] = blocks[b].t0; bd[4 * b + 1] = blocks[b].t1;
-        bd[4 * b + 2] = blocks[b].f0; bd[4 * b + 3] = blocks[b].f1;
-        max_kf = std::max(max_kf, blocks[b].f1 - blocks[b].f0);
-    }
-    MP_HIPX(hipMemcpyAsync(ctx->blocks_dev, bd.data(), bd.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
-    // fine member lists = stored order
-    MP_HIPX(launch_fill_i32(ctx->km_cnt, (long long)U * tab, 0, s));
-    MP_HIPX(launch_histogram(ctx->fot, Ncap, n_tokens, U, ctx->km_cnt, tab, s));
-    MP_HIPX(launch_exclusive_scan(ctx->km_cnt, tab, n_fine, U, ctx->fstart, ctx->Fcap + 1, s));
-    MP_HIPX(launch_member_lists(ctx->fot, Ncap, ctx->blocks_dev, nb, max_kf, U, ctx->fstart, ctx->Fcap + 1,
-                                ctx->perm, Ncap, s));
-    MP_HIPX(launch_gather_rows(k, v, n_tokens, ctx->perm, Ncap, n_tokens, U, ctx->Kp, ctx->Vp, Ncap, 0, s));
-    // fine tables
-    MP_HIPX(launch_cluster_means((const uint16_t*)k, n_tokens, ctx->perm, Ncap, ctx->fstart, ctx->Fcap + 1, n_fine, U,
-                                 ctx->Kc, tab, 0, key_fallback ? ctx->Kc : nullptr, tab, nullptr, 0, 0, s));
-    MP_HIPX(launch_cluster_means((const uint16_t*)v, n_tokens, ctx->perm, Ncap, ctx->fstart, ctx->Fcap + 1, n_fine, U,
-                                 ctx->Vc, tab, 0, nullptr, 0, ctx->Ncl, tab, 0, s));
-    if (ctx->cfg.levels == 2) {
-        MP_HIPX(launch_coarse_start(ctx->cof, ctx->Fcap, n_fine, n_coarse, U, ctx->cstart, ctx->Ccap + 1, s));
-        MP_HIPX(launch_coarse_row_start(ctx->cstart, ctx->Ccap + 1, ctx->fstart, ctx->Fcap + 1, n_coarse, U,
-                                        ctx->crow, ctx->Ccap + 1, s));
-        MP_HIPX(launch_cluster_means(ctx->Kp, Ncap, nullptr, 0, ctx->crow, ctx->Ccap + 1, n_coarse, U, ctx->Kc, tab,
-                                     ctx->Fcap, key_fallback ? ctx->Kc + (long long)ctx->Fcap * kHeadDimHost : nullptr,
-                                     tab, nullptr, 0, 0, s));
-        MP_HIPX(launch_cluster_means(ctx->Vp, Ncap, nullptr, 0, ctx->crow, ctx->Ccap + 1, n_coarse, U, ctx->Vc, tab,
-                                     ctx->Fcap, nullptr, 0, ctx->Ncl, tab, ctx->Fcap, s));
-    }
-    // keep the last block in sequence order for the online update
-    const BlockPlan& lb = blocks.back();
-    const int nlast = lb.t1 - lb.t0;
-    if (nlast <= ctx->FBcap) {
-        const size_t row = kHeadDimHost * sizeof(uint16_t);
-        MP_HIPX(hipMemcpy2DAsync(ctx->Kfb, (size_t)ctx->FBcap * row, (const char*)k + (size_t)lb.t0 * row,
-                                 (size_t)n_tokens * row, (size_t)nlast * row, U, hipMemcpyDeviceToDevice, s));
-        MP_HIPX(hipMemcpy2DAsync(ctx->Vfb, (size_t)ctx->FBcap * row, (const char*)v + (size_t)lb.t0 * row,
-                                 (size_t)n_tokens * row, (size_t)nlast * row, U, hipMemcpyDeviceToDevice, s));
-    }
-    ctx->n_tokens = n_tokens;
-    ctx->n_fine = n_fine;
-    ctx->n_coarse = ctx->cfg.levels == 2 ? n_coarse : 0;
-    ctx->blocks = blocks;
-    ctx->has_index = true;
-    ctx->decoded = false;
-    return MP_OK;
-#undef MP_HIPX
 }
 
 }  // namespace mp
@@ -188,8 +126,8 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     if (c.levels == 2 && (c.max_coarse < 1 || c.max_coarse > c.max_fine))
         return fail(nullptr, MP_EINVAL, "mp_create: max_coarse must be in [1, max_fine] when levels == 2");
     if (c.levels == 1 && c.max_coarse < 0) return fail(nullptr, MP_EINVAL, "mp_create: max_coarse < 0");
-    if (c.block_w < 0 || c.block_alpha < 0 || (c.block_w > 0 && c.block_alpha > c.block_w))
-        return fail(nullptr, MP_EINVAL, "mp_create: need block_w >= 0 and 0 <= block_alpha <= block_w");
+    if (c.block_w < 0 || c.block_alpha < 0 || (c.block_w > 0 && (c.block_alpha < 1 || c.block_alpha > c.block_w)))
+        return fail(nullptr, MP_EINVAL, "mp_create: need block_w >= 0 and, with block_w > 0, 1 <= block_alpha <= block_w");
     if (c.max_tail < 0) return fail(nullptr, MP_EINVAL, "mp_create: max_tail < 0");
     if (!(c.softmax_scale >= 0.f)) return fail(nullptr, MP_EINVAL, "mp_create: softmax_scale must be >= 0");
     if ((long long)c.batch * c.n_kv_heads > 65535) return fail(nullptr, MP_EINVAL, "mp_create: more than 65535 units");
@@ -206,8 +144,8 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     ctx->Ccap = c.levels == 2 ? c.max_coarse : 0;
     ctx->Tcap = c.max_tail;
     ctx->tab_rows = (long long)ctx->Fcap + ctx->Ccap;
-    ctx->FBcap = c.block_w > 0 ? std::min<long long>(c.max_tokens, (long long)c.block_w + c.block_alpha) : c.max_tokens;
-    ctx->max_blocks = c.block_w > 0 ? c.max_tokens / c.block_w + 2 : 2;
+    ctx->FBcap = c.block_w > 0 ? (int32_t)std::min<long long>(c.max_tokens, 2ll * c.block_w) : c.max_tokens;
+    ctx->max_blocks = std::max(4, c.block_w > 0 ? c.max_tokens / c.block_w + 2 : 2);
     ctx->Pcap = ceil_div(ctx->Ncap, kChunkRowsMin) + ceil_div(ctx->Tcap, kChunkRowsMin) +
                 ceil_div(ctx->tab_rows, kChunkRowsMin) + 1;
 
@@ -306,16 +244,16 @@ mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* v, int32_t n
     } else {
         n_coarse = 0;
     }
-    hipStream_t s = (hipStream_t)stream;
-    const int U = ctx->U;
-    MP_HIP(ctx, hipMemcpy2DAsync(ctx->fot, (size_t)ctx->Ncap * 4, fine_of_token, (size_t)n_tokens * 4, (size_t)n_tokens * 4, U,
-                                 hipMemcpyDeviceToDevice, s));
-    if (ctx->cfg.levels == 2)
-        MP_HIP(ctx, hipMemcpy2DAsync(ctx->cof, (size_t)ctx->Fcap * 4, coarse_of_fine, (size_t)n_fine * 4, (size_t)n_fine * 4, U,
-                                     hipMemcpyDeviceToDevice, s));
-    std::vector<BlockPlan> blocks(1);
-    blocks[0] = BlockPlan{0, n_tokens, 0, n_fine, 0, n_coarse};
-    return finalize_index(ctx, k, v, n_tokens, n_fine, n_coarse, blocks, false, s);
+    return set_clustering_impl(ctx, k, v, n_tokens, fine_of_token, n_fine, coarse_of_fine, n_coarse, (hipStream_t)stream);
+}
+
+int32_t mp_update_seed_counts(const mp_ctx* ctx, int32_t n_new, int32_t n_new_fine, int32_t n_new_coarse, int32_t* counts)
+{
+    if (!ctx || !counts || !ctx->has_index || n_new < 1 || n_new_fine < 0 || n_new_coarse < 0) return -1;
+    update_seed_counts(ctx, n_new, n_new_fine, n_new_coarse, counts);
+    int32_t t = 0;
+    for (int i = 0; i < 6; ++i) t += counts[i];
+    return t;
 }
 
 mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* v_new, int32_t n_new, int32_t n_new_fine,

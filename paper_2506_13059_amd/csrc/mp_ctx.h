@@ -117,6 +117,7 @@ struct mp_ctx {
     // ---- current index (host copies of sizes) ----
     bool has_index = false;
     bool decoded = false;
+    bool updatable = false;        // the last block fits Kfb / Vfb
     int32_t n_tokens = 0, n_fine = 0, n_coarse = 0;
     std::vector<mp::BlockPlan> blocks;
 
@@ -134,6 +135,4 @@ namespace mp {
 // return the status.
 mp_status fail(mp_ctx* ctx, mp_status st, const char* fmt, ...) __attribute__((format(printf, 3, 4)));
 int pick_chunk_rows(long long n_rows_per_unit, int n_units);
-mp_status finalize_index(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, int32_t n_fine, int32_t n_coarse,
-                         const std::vector<BlockPlan>& blocks, bool key_fallback, hipStream_t s);
 }  // namespace mp

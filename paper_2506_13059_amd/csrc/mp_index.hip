@@ -110,20 +110,20 @@ __global__ void gather_rows_kernel(const uint4* __restrict__ srcK, const uint4* 
     dstV[((long long)u * dst_unit_rows + dst_row0 + p) * 16 + c] = srcV[((long long)u * src_unit_rows + s) * 16 + c];
 }
 
-// One wave per cluster: fp64 sum of the member rows in list order, mean rounded once to bf16.
+// One wave per cluster of [k0, k): fp64 sum of the member rows in list order, mean rounded once to bf16.
 // Lane l owns dims 2l and 2l+1.  Empty cluster: `fallback` row if given (else zeros).
 // mean_out row index = out_row0 + cluster id.  count_out optional.
 __global__ __launch_bounds__(256) void cluster_mean_kernel(const uint16_t* __restrict__ X, long long x_unit_rows,
                                                            const int32_t* __restrict__ list, long long list_stride,
                                                            const int32_t* __restrict__ start, long long start_stride,
-                                                           int k, uint16_t* __restrict__ mean_out,
+                                                           int k0, int k, uint16_t* __restrict__ mean_out,
                                                            long long out_unit_rows, int out_row0,
                                                            const uint16_t* __restrict__ fallback,
                                                            long long fb_unit_rows, int32_t* __restrict__ count_out,
                                                            long long count_stride, int count_off)
 {
     const int u = blockIdx.y;
-    const int f = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int f = k0 + blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     if (f >= k) return;
     const int s0 = start[u * start_stride + f], s1 = start[u * start_stride + f + 1];
@@ -160,28 +160,41 @@ __global__ __launch_bounds__(256) void cluster_mean_kernel(const uint16_t* __res
     if (count_out && lane == 0) count_out[u * count_stride + count_off + f] = n;
 }
 
-// cstart[u][c] = first fine id whose coarse id is >= c (coarse ids are non-decreasing in the fine id);
-// cstart[u][n_coarse] = n_fine.
-__global__ void coarse_start_kernel(const int32_t* __restrict__ cof, long long cof_stride, int n_fine, int n_coarse,
-                                    int32_t* __restrict__ cstart, long long cstart_stride)
+// For the fine range [f0, f1) whose coarse ids lie in [c0, c1) and are non-decreasing in the fine id:
+// cstart[u][c] = first fine id of the range whose coarse id is >= c, for c in [c0, c1]; cstart[c1] = f1.
+__global__ void coarse_start_kernel(const int32_t* __restrict__ cof, long long cof_stride, int f0, int f1, int c0,
+                                    int c1, int32_t* __restrict__ cstart, long long cstart_stride)
 {
     const int u = blockIdx.y;
-    const int f = blockIdx.x * blockDim.x + threadIdx.x;
-    if (f > n_fine) return;
-    const int cur = (f < n_fine) ? cof[u * cof_stride + f] : n_coarse;
-    const int prev = (f > 0) ? cof[u * cof_stride + f - 1] : -1;
+    const int f = f0 + blockIdx.x * blockDim.x + threadIdx.x;
+    if (f > f1) return;
+    const int cur = (f < f1) ? cof[u * cof_stride + f] : c1;
+    const int prev = (f > f0) ? cof[u * cof_stride + f - 1] : c0 - 1;
     for (int c = prev + 1; c <= cur; ++c) cstart[u * cstart_stride + c] = f;
 }
 
-// Row ranges of the coarse clusters in the stored order: rstart[u][c] = fstart[u][cstart[u][c]].
+// Row ranges of the coarse clusters [c0, c1] in the stored order: rstart[u][c] = fstart[u][cstart[u][c]].
 __global__ void coarse_row_start_kernel(const int32_t* __restrict__ cstart, long long cstart_stride,
-                                        const int32_t* __restrict__ fstart, long long fstart_stride, int n_coarse,
+                                        const int32_t* __restrict__ fstart, long long fstart_stride, int c0, int c1,
                                         int32_t* __restrict__ rstart, long long rstart_stride)
 {
     const int u = blockIdx.y;
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c > n_coarse) return;
+    const int c = c0 + blockIdx.x * blockDim.x + threadIdx.x;
+    if (c > c1) return;
     rstart[u * rstart_stride + c] = fstart[u * fstart_stride + cstart[u * cstart_stride + c]];
+}
+
+// Stored-order tables from member lists built on local point indices:
+// fstart[u][f] = pt0 + start[u][f] for f in [f0, f1];  perm[u][pt0 + p] = pt0 + list[u][p] for p < n_pts.
+__global__ void offset_lists_kernel(const int32_t* __restrict__ start, long long start_stride, int f0, int f1,
+                                    const int32_t* __restrict__ list, long long list_stride, int n_pts, int pt0,
+                                    int32_t* __restrict__ fstart, long long fstart_stride, int32_t* __restrict__ perm,
+                                    long long perm_stride)
+{
+    const int u = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_pts) perm[u * perm_stride + pt0 + i] = pt0 + list[u * list_stride + i];
+    if (i <= f1 - f0) fstart[u * fstart_stride + f0 + i] = pt0 + start[u * start_stride + f0 + i];
 }
 
 // fot[u][list[p]] = f for p in [start[f], start[f+1])  (inverse of the member lists)
@@ -195,19 +208,6 @@ __global__ void ids_from_lists_kernel(const int32_t* __restrict__ list, long lon
     if (f >= k) return;
     const int s0 = start[u * start_stride + f], s1 = start[u * start_stride + f + 1];
     for (int p = s0 + lane; p < s1; p += 64) ids[u * ids_stride + list[u * list_stride + p]] = f;
-}
-
-// out[u][i] = map[u][in[u][i] + off(block of i)] ... renumbering helper:
-// ids[u][t] = base_of_block + newid[u][k0 + ids[u][t]] for t in block b.
-__global__ void renumber_kernel(int32_t* __restrict__ ids, long long ids_stride, const int32_t* __restrict__ blocks,
-                                int nb, const int32_t* __restrict__ newid, long long newid_stride)
-{
-    const int u = blockIdx.z, b = blockIdx.y;
-    const int x0 = blocks[4 * b + 0], x1 = blocks[4 * b + 1], k0 = blocks[4 * b + 2];
-    const int t = x0 + blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= x1) return;
-    const int old = ids[u * ids_stride + t];
-    ids[u * ids_stride + t] = k0 + newid[u * newid_stride + k0 + old];
 }
 
 // Dense per-cluster views of the last decode call's selection, from the per-candidate arrays:
@@ -297,32 +297,42 @@ hipError_t launch_gather_rows(const void* srcK, const void* srcV, long long src_
 }
 
 hipError_t launch_cluster_means(const uint16_t* X, long long x_unit_rows, const int32_t* list, long long list_stride,
-                                const int32_t* start, long long start_stride, int k, int U, uint16_t* mean_out,
-                                long long out_unit_rows, int out_row0, const uint16_t* fallback,
+                                const int32_t* start, long long start_stride, int k0, int k, int U,
+                                uint16_t* mean_out, long long out_unit_rows, int out_row0, const uint16_t* fallback,
                                 long long fb_unit_rows, int32_t* count_out, long long count_stride, int count_off,
                                 hipStream_t s)
 {
-    if (k <= 0) return hipSuccess;
-    hipLaunchKernelGGL(cluster_mean_kernel, dim3((k + 3) / 4, U), dim3(256), 0, s, X, x_unit_rows, list, list_stride,
-                       start, start_stride, k, mean_out, out_unit_rows, out_row0, fallback, fb_unit_rows, count_out,
-                       count_stride, count_off);
+    if (k <= k0) return hipSuccess;
+    hipLaunchKernelGGL(cluster_mean_kernel, dim3((k - k0 + 3) / 4, U), dim3(256), 0, s, X, x_unit_rows, list,
+                       list_stride, start, start_stride, k0, k, mean_out, out_unit_rows, out_row0, fallback,
+                       fb_unit_rows, count_out, count_stride, count_off);
     return hipGetLastError();
 }
 
-hipError_t launch_coarse_start(const int32_t* cof, long long cof_stride, int n_fine, int n_coarse, int U,
+hipError_t launch_coarse_start(const int32_t* cof, long long cof_stride, int f0, int f1, int c0, int c1, int U,
                                int32_t* cstart, long long cstart_stride, hipStream_t s)
 {
-    hipLaunchKernelGGL(coarse_start_kernel, dim3((n_fine + 1 + 255) / 256, U), dim3(256), 0, s, cof, cof_stride,
-                       n_fine, n_coarse, cstart, cstart_stride);
+    hipLaunchKernelGGL(coarse_start_kernel, dim3((f1 - f0 + 1 + 255) / 256, U), dim3(256), 0, s, cof, cof_stride, f0,
+                       f1, c0, c1, cstart, cstart_stride);
     return hipGetLastError();
 }
 
 hipError_t launch_coarse_row_start(const int32_t* cstart, long long cstart_stride, const int32_t* fstart,
-                                   long long fstart_stride, int n_coarse, int U, int32_t* rstart,
+                                   long long fstart_stride, int c0, int c1, int U, int32_t* rstart,
                                    long long rstart_stride, hipStream_t s)
 {
-    hipLaunchKernelGGL(coarse_row_start_kernel, dim3((n_coarse + 1 + 255) / 256, U), dim3(256), 0, s, cstart,
-                       cstart_stride, fstart, fstart_stride, n_coarse, rstart, rstart_stride);
+    hipLaunchKernelGGL(coarse_row_start_kernel, dim3((c1 - c0 + 1 + 255) / 256, U), dim3(256), 0, s, cstart,
+                       cstart_stride, fstart, fstart_stride, c0, c1, rstart, rstart_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_offset_lists(const int32_t* start, long long start_stride, int f0, int f1, const int32_t* list,
+                               long long list_stride, int n_pts, int pt0, int U, int32_t* fstart,
+                               long long fstart_stride, int32_t* perm, long long perm_stride, hipStream_t s)
+{
+    const int n = n_pts > f1 - f0 + 1 ? n_pts : f1 - f0 + 1;
+    hipLaunchKernelGGL(offset_lists_kernel, dim3((n + 255) / 256, U), dim3(256), 0, s, start, start_stride, f0, f1,
+                       list, list_stride, n_pts, pt0, fstart, fstart_stride, perm, perm_stride);
     return hipGetLastError();
 }
 
@@ -333,15 +343,6 @@ hipError_t launch_ids_from_lists(const int32_t* list, long long list_stride, con
     if (k <= 0) return hipSuccess;
     hipLaunchKernelGGL(ids_from_lists_kernel, dim3((k + 3) / 4, U), dim3(256), 0, s, list, list_stride, start,
                        start_stride, k, ids, ids_stride);
-    return hipGetLastError();
-}
-
-hipError_t launch_renumber(int32_t* ids, long long ids_stride, const int32_t* blocks_dev, int nb,
-                           int max_pts_per_block, int U, const int32_t* newid, long long newid_stride, hipStream_t s)
-{
-    if (nb <= 0 || max_pts_per_block <= 0) return hipSuccess;
-    hipLaunchKernelGGL(renumber_kernel, dim3((max_pts_per_block + 255) / 256, nb, U), dim3(256), 0, s, ids,
-                       ids_stride, blocks_dev, nb, newid, newid_stride);
     return hipGetLastError();
 }
 

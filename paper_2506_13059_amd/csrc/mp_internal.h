@@ -112,22 +112,23 @@ hipError_t launch_gather_rows(const void* srcK, const void* srcV, long long src_
                               long long list_stride, int n, int U, void* dstK, void* dstV, long long dst_unit_rows,
                               int dst_row0, hipStream_t s);
 hipError_t launch_cluster_means(const uint16_t* X, long long x_unit_rows, const int32_t* list, long long list_stride,
-                                const int32_t* start, long long start_stride, int k, int U, uint16_t* mean_out,
-                                long long out_unit_rows, int out_row0, const uint16_t* fallback,
+                                const int32_t* start, long long start_stride, int k0, int k, int U,
+                                uint16_t* mean_out, long long out_unit_rows, int out_row0, const uint16_t* fallback,
                                 long long fb_unit_rows, int32_t* count_out, long long count_stride, int count_off,
                                 hipStream_t s);
-hipError_t launch_coarse_start(const int32_t* cof, long long cof_stride, int n_fine, int n_coarse, int U,
+hipError_t launch_coarse_start(const int32_t* cof, long long cof_stride, int f0, int f1, int c0, int c1, int U,
                                int32_t* cstart, long long cstart_stride, hipStream_t s);
 hipError_t launch_coarse_row_start(const int32_t* cstart, long long cstart_stride, const int32_t* fstart,
-                                   long long fstart_stride, int n_coarse, int U, int32_t* rstart,
+                                   long long fstart_stride, int c0, int c1, int U, int32_t* rstart,
                                    long long rstart_stride, hipStream_t s);
+hipError_t launch_offset_lists(const int32_t* start, long long start_stride, int f0, int f1, const int32_t* list,
+                               long long list_stride, int n_pts, int pt0, int U, int32_t* fstart,
+                               long long fstart_stride, int32_t* perm, long long perm_stride, hipStream_t s);
 hipError_t launch_ids_from_lists(const int32_t* list, long long list_stride, const int32_t* start,
                                  long long start_stride, int k, int U, int32_t* ids, long long ids_stride,
                                  hipStream_t s);
 hipError_t launch_scatter_selection(const int32_t* cand, long long cand_stride, const int32_t* n_cand_dev,
                                     int n_cand_fixed, const uint8_t* flag, const double* r, long long pos_stride,
                                     int n_ids, int U, uint8_t* sel_out, double* r_out, hipStream_t s);
-hipError_t launch_renumber(int32_t* ids, long long ids_stride, const int32_t* blocks_dev, int nb,
-                           int max_pts_per_block, int U, const int32_t* newid, long long newid_stride, hipStream_t s);
 
 }  // namespace mp
