@@ -212,7 +212,7 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
  * Stage timing (for benchmarks).  While enabled, mp_decode_attention records HIP events on the
  * call's own stream before and after each of its launches.  mp_get_stage_timing waits for the last
  * timed call and writes its four durations in milliseconds:
- * ms[0] coarse scoring + selection (0 with one level), ms[1] fine scoring + selection,
+ * ms[0] = 0 (reserved), ms[1] scoring + selection (both levels, one launch),
  * ms[2] value pass (the kernel that streams the selected keys / values and the centroid terms),
  * ms[3] merge.  Errors: MP_ESTATE if no timed call has been made.
  * ------------------------------------------------------------------------------------------- */

@@ -45,6 +45,8 @@ mp_status fail(mp_ctx* ctx, mp_status st, const char* fmt, ...)
 
 // Rows per workgroup of the value pass for a stream of n rows per unit: large enough that the
 // partials stay a small fraction of the traffic, small enough that there are many workgroups.
+constexpr int kFineChunkRows = 128;   // 4 waves x 32 rows
+
 int pick_chunk_rows(long long n_rows_per_unit, int n_units)
 {
     int cr = kChunkRowsMin;
@@ -146,7 +148,7 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     ctx->tab_rows = (long long)ctx->Fcap + ctx->Ccap;
     ctx->FBcap = c.block_w > 0 ? (int32_t)std::min<long long>(c.max_tokens, 2ll * c.block_w) : c.max_tokens;
     ctx->max_blocks = std::max(4, c.block_w > 0 ? c.max_tokens / c.block_w + 2 : 2);
-    ctx->Pcap = ceil_div(ctx->Ncap, kChunkRowsMin) + ceil_div(ctx->Tcap, kChunkRowsMin) +
+    ctx->Pcap = 2 * ceil_div(ctx->Ncap, kChunkRowsMin) + 2 + ceil_div(ctx->Tcap, kChunkRowsMin) +
                 ceil_div(ctx->tab_rows, kChunkRowsMin) + 1;
 
     hipError_t e = hipGetDevice(&ctx->device);
@@ -159,7 +161,10 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     A(km_assign, U * N); A(km_list, U * N); A(km_cnt, U * T); A(km_start, U * (T + 2));
     A(km_Cf, U * F * D); A(km_Cc, U * Cc * D); A(km_parent, U * F); A(km_plist, U * F); A(km_newid, U * F);
     A(km_seed_f, U * F); A(km_seed_c, U * Cc); A(blocks_dev, 3 * (size_t)ctx->max_blocks * 4);
-    A(lg_c, U * G * Cc); A(lg_f, U * G * F); A(r_c, U * Cc); A(r_f, U * F); A(flag_c, U * Cc); A(flag_f, U * F);
+    ctx->Lcap = (int32_t)std::max(F, Cc);
+    const size_t Lc = ctx->Lcap;
+    A(lg, U * G * Lc); A(sc_keys, U * Lc); A(sc_wts, U * Lc); A(sc_ids, U * Lc); A(sc_aux, U * Lc); A(sc_aux2, U * Lc);
+    A(sc_flags, U * Lc); A(r_c, U * Cc); A(r_f, U * F); A(flag_c, U * Cc); A(flag_f, U * F);
     A(cand, U * F); A(n_cand, U); A(unprom_lse, U * G); A(rows, U * N); A(n_rows, U);
     A(mp_rows, U * T); A(mp_scores, U * T * G); A(n_mp, U); A(counters, U * 4);
     A(partials, U * (size_t)ctx->Pcap * G * kPartStride);
@@ -288,36 +293,23 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
     const int use_mp = (flags & MP_DECODE_NO_MULTIPOLE) ? 0 : 1;
 
     ScoreParams sp{};
-    sp.q = (const uint16_t*)q; sp.Kc = ctx->Kc; sp.N = ctx->Ncl; sp.tab_rows = ctx->tab_rows;
-    sp.scale = ctx->scale_d; sp.G = G; sp.U = U;
+    sp.q = (const uint16_t*)q; sp.Kc = ctx->Kc; sp.N = ctx->Ncl; sp.tab_rows = ctx->tab_rows; sp.fcap = ctx->Fcap;
+    sp.levels = ctx->cfg.levels; sp.n_fine = ctx->n_fine; sp.n_coarse = ctx->n_coarse;
+    sp.key_budget = key_budget; sp.coarse_budget = coarse_budget; sp.scale = ctx->scale_d;
+    sp.cstart = ctx->cstart; sp.cstart_stride = ctx->Ccap + 1; sp.fstart = ctx->fstart; sp.fstart_stride = ctx->Fcap + 1;
+    sp.lg = ctx->lg; sp.lg_stride = ctx->Lcap; sp.g_keys = ctx->sc_keys; sp.g_wts = ctx->sc_wts; sp.g_ids = ctx->sc_ids;
+    sp.g_aux = ctx->sc_aux; sp.g_aux2 = ctx->sc_aux2; sp.g_flags = ctx->sc_flags; sp.g_stride = ctx->Lcap;
+    sp.r_c = ctx->r_c; sp.flag_c = ctx->flag_c; sp.c_stride = std::max(ctx->Ccap, 1);
+    sp.r_f = ctx->r_f; sp.flag_f = ctx->flag_f; sp.f_stride = ctx->Fcap; sp.cand = ctx->cand; sp.n_cand = ctx->n_cand;
+    sp.rows = ctx->rows; sp.rows_stride = ctx->Ncap; sp.n_rows = ctx->n_rows;
     sp.mp_rows = ctx->mp_rows; sp.mp_scores = ctx->mp_scores; sp.mp_stride = ctx->tab_rows; sp.n_mp = ctx->n_mp;
     sp.use_mp = use_mp; sp.counters = ctx->counters; sp.n_tail = n_tail;
-    if (two) {
-        ScoreParams c = sp;
-        c.coarse = 1; c.row_off = ctx->Fcap; c.cand = nullptr; c.n_cand_dev = nullptr; c.n_cand_fixed = ctx->n_coarse;
-        c.budget = coarse_budget; c.extra_lse = nullptr;
-        c.lg = ctx->lg_c; c.lg_stride = std::max(ctx->Ccap, 1); c.r_out = ctx->r_c; c.r_stride = std::max(ctx->Ccap, 1);
-        c.flag_out = ctx->flag_c;
-        c.cstart = ctx->cstart; c.cstart_stride = ctx->Ccap + 1; c.cand_out = ctx->cand; c.cand_out_stride = ctx->Fcap;
-        c.n_cand_out = ctx->n_cand; c.unprom_lse_out = ctx->unprom_lse; c.mp_append = 0;
-        c.smem_cap = ctx->n_coarse;
-        if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[0], s));
-        MP_HIP(ctx, launch_score_select(c, s));
-    }
-    {
-        ScoreParams f = sp;
-        f.coarse = 0; f.row_off = 0;
-        f.cand = two ? ctx->cand : nullptr; f.cand_stride = ctx->Fcap;
-        f.n_cand_dev = two ? ctx->n_cand : nullptr; f.n_cand_fixed = ctx->n_fine;
-        f.budget = key_budget; f.extra_lse = two ? ctx->unprom_lse : nullptr;
-        f.lg = ctx->lg_f; f.lg_stride = ctx->Fcap; f.r_out = ctx->r_f; f.r_stride = ctx->Fcap; f.flag_out = ctx->flag_f;
-        f.fstart = ctx->fstart; f.fstart_stride = ctx->Fcap + 1; f.rows_out = ctx->rows; f.rows_stride = ctx->Ncap;
-        f.n_rows_out = ctx->n_rows; f.mp_append = two ? 1 : 0;
-        f.smem_cap = ctx->n_fine;
-        if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[1], s));
-        MP_HIP(ctx, launch_score_select(f, s));
-        if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[2], s));
-    }
+    sp.lds_cap = std::min(1024, std::max(ctx->n_fine, std::max(ctx->n_coarse, 1)));
+    sp.G = G; sp.U = U;
+    if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[0], s));
+    if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[1], s));
+    MP_HIP(ctx, launch_score_select(sp, s));
+    if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[2], s));
 
     ValuePassParams vp{};
     vp.q = (const uint16_t*)q;
@@ -325,26 +317,38 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
     vp.n_units = U;
     vp.scale_log2e = (float)(ctx->scale_d * 1.4426950408889634);
     const int main_max = std::min(key_budget, ctx->n_tokens);
-    vp.chunk_rows = pick_chunk_rows(std::max(main_max, 1), U);
+    const int cr = pick_chunk_rows(std::max(main_max, 1), U);
     int ns = 0, chunk0 = 0;
-    if (main_max > 0) {
-        RowSource& r = vp.src[ns++];
-        r.K = ctx->Kp; r.V = ctx->Vp; r.unit_rows = ctx->Ncap; r.rows = ctx->rows; r.rows_stride = ctx->Ncap;
-        r.count_dev = ctx->n_rows; r.count_max = main_max; r.scores = nullptr; r.chunk0 = chunk0;
-        r.n_chunks = ceil_div(main_max, vp.chunk_rows); chunk0 += r.n_chunks;
-    }
-    if (n_tail > 0) {
-        RowSource& r = vp.src[ns++];
-        r.K = (const uint16_t*)k_tail; r.V = (const uint16_t*)v_tail; r.unit_rows = n_tail; r.rows = nullptr; r.rows_stride = 0;
-        r.count_dev = nullptr; r.count_max = n_tail; r.scores = nullptr; r.chunk0 = chunk0;
-        r.n_chunks = ceil_div(n_tail, vp.chunk_rows); chunk0 += r.n_chunks;
-    }
+    // order: centroid terms, tail, selected keys -- the longest stream goes last (see the kernel's block mapping)
     if (use_mp) {
         const int mp_max = ctx->n_fine + ctx->n_coarse;
         RowSource& r = vp.src[ns++];
         r.K = nullptr; r.V = ctx->Vc; r.unit_rows = ctx->tab_rows; r.rows = ctx->mp_rows; r.rows_stride = ctx->tab_rows;
         r.count_dev = ctx->n_mp; r.count_max = mp_max; r.scores = ctx->mp_scores; r.chunk0 = chunk0;
-        r.n_chunks = ceil_div(mp_max, vp.chunk_rows); chunk0 += r.n_chunks;
+        r.chunk_rows = cr; r.row0 = 0; r.n_chunks = ceil_div(mp_max, cr); chunk0 += r.n_chunks;
+    }
+    if (n_tail > 0) {
+        RowSource& r = vp.src[ns++];
+        r.K = (const uint16_t*)k_tail; r.V = (const uint16_t*)v_tail; r.unit_rows = n_tail; r.rows = nullptr; r.rows_stride = 0;
+        r.count_dev = nullptr; r.count_max = n_tail; r.scores = nullptr; r.chunk0 = chunk0;
+        r.chunk_rows = cr; r.row0 = 0; r.n_chunks = ceil_div(n_tail, cr); chunk0 += r.n_chunks;
+    }
+    if (main_max > 0) {
+        // the selected keys: large chunks first, and the last eighth of the stream in small chunks,
+        // so that the workgroups still running when the grid drains are short ones
+        int bulk = main_max;
+        if (main_max >= 4 * cr) bulk = ((main_max - main_max / 8) / cr) * cr;
+        const int fine = main_max - bulk;
+        RowSource& r = vp.src[ns++];
+        r.K = ctx->Kp; r.V = ctx->Vp; r.unit_rows = ctx->Ncap; r.rows = ctx->rows; r.rows_stride = ctx->Ncap;
+        r.count_dev = ctx->n_rows; r.count_max = bulk; r.scores = nullptr; r.chunk0 = chunk0;
+        r.chunk_rows = cr; r.row0 = 0; r.n_chunks = ceil_div(bulk, cr); chunk0 += r.n_chunks;
+        if (fine > 0) {
+            RowSource& f = vp.src[ns++];
+            f = r;
+            f.count_max = fine; f.chunk0 = chunk0; f.chunk_rows = kFineChunkRows; f.row0 = bulk;
+            f.n_chunks = ceil_div(fine, kFineChunkRows); chunk0 += f.n_chunks;
+        }
     }
     vp.n_sources = ns;
     vp.chunks_per_unit = chunk0;
@@ -377,7 +381,6 @@ mp_status mp_get_stage_timing(mp_ctx* ctx, float* ms)
     if (!ctx->timing || !ctx->timed_levels) return fail(ctx, MP_ESTATE, "mp_get_stage_timing: no timed decode call yet");
     MP_HIP(ctx, hipEventSynchronize(ctx->ev[4]));
     ms[0] = 0.f;
-    if (ctx->timed_levels == 2) MP_HIP(ctx, hipEventElapsedTime(&ms[0], ctx->ev[0], ctx->ev[1]));
     MP_HIP(ctx, hipEventElapsedTime(&ms[1], ctx->ev[1], ctx->ev[2]));
     MP_HIP(ctx, hipEventElapsedTime(&ms[2], ctx->ev[2], ctx->ev[3]));
     MP_HIP(ctx, hipEventElapsedTime(&ms[3], ctx->ev[3], ctx->ev[4]));
@@ -444,7 +447,7 @@ mp_status mp_get_selection(mp_ctx* ctx, uint8_t* fine_selected, uint8_t* coarse_
         MP_HIP(ctx, launch_scatter_selection(two ? ctx->cand : nullptr, ctx->Fcap, two ? ctx->n_cand : nullptr, ctx->n_fine,
                                              ctx->flag_f, ctx->r_f, ctx->Fcap, ctx->n_fine, ctx->U, fine_selected, r_fine, s));
     if (two && (coarse_promising || r_coarse))
-        MP_HIP(ctx, launch_scatter_selection(nullptr, 0, nullptr, ctx->n_coarse, ctx->flag_c, ctx->r_c, ctx->Ccap, ctx->n_coarse,
+        MP_HIP(ctx, launch_scatter_selection(nullptr, 0, nullptr, ctx->n_coarse, ctx->flag_c, ctx->r_c, std::max(ctx->Ccap, 1), ctx->n_coarse,
                                              ctx->U, coarse_promising, r_coarse, s));
     return MP_OK;
 }
@@ -507,8 +510,10 @@ mp_status mp_dense_attention(const void* q, const void* k, const void* v, int32_
     p.q = (const uint16_t*)q;
     p.partials = (float*)workspace;
     p.n_units = U;
-    p.chunk_rows = pick_chunk_rows(n, U);
-    p.chunks_per_unit = ceil_div(n > 0 ? n : 1, p.chunk_rows);
+    const int dcr = pick_chunk_rows(n, U);
+    p.chunks_per_unit = ceil_div(n > 0 ? n : 1, dcr);
+    p.src[0].chunk_rows = dcr;
+    p.src[0].row0 = 0;
     p.n_sources = 1;
     p.scale_log2e = scale * 1.4426950408889634f;
     p.src[0].K = (const uint16_t*)k;

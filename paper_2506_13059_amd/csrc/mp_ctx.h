@@ -96,8 +96,14 @@ struct mp_ctx {
     int32_t max_blocks = 0;
 
     // ---- decode workspace ----
-    double* lg_c = nullptr;        // [U, G, Ccap] coarse logits
-    double* lg_f = nullptr;        // [U, G, Fcap] fine logits by candidate position
+    double* lg = nullptr;          // [U, G, Lcap] logits of a level that does not fit LDS (Lcap = max(Fcap, Ccap))
+    unsigned long long* sc_keys = nullptr;   // [U, Lcap] and the other per-entry arrays of such a level
+    uint32_t* sc_wts = nullptr;
+    int32_t* sc_ids = nullptr;
+    int32_t* sc_aux = nullptr;
+    int32_t* sc_aux2 = nullptr;
+    uint8_t* sc_flags = nullptr;
+    int32_t Lcap = 0;
     double* r_c = nullptr;         // [U, Ccap]
     double* r_f = nullptr;         // [U, Fcap] by candidate position
     uint8_t* flag_c = nullptr;     // [U, Ccap] promising

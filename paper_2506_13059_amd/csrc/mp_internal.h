@@ -7,7 +7,8 @@ namespace mp {
 
 // ------------------------------------------------------------------------------------------------
 // Value pass: streams rows (keys + values, or value centroids with ready-made scores) and produces
-// one online-softmax partial (m, l, acc[128]) per (unit, chunk, head).
+// one online-softmax partial (m, l, acc[128]) per (unit, chunk, head).  A stream may be cut into two
+// sources with different chunk sizes (large chunks first, small ones last) to shorten the drain.
 // ------------------------------------------------------------------------------------------------
 constexpr int kChunkRowsMin = 512;     // a workgroup is 4 waves, each taking strips of 128 rows
 constexpr int kPartStride = 132;       // floats per (unit, chunk, head): m, l, pad, pad, acc[128]
@@ -26,6 +27,8 @@ struct RowSource {
     const float* scores;       // optional [U, rows_stride, G] ready-made logits in log2 units
     int32_t chunk0;            // first chunk id of this source inside a unit
     int32_t n_chunks;          // ceil(count_max / chunk_rows)
+    int32_t chunk_rows;        // rows per workgroup of this source, a multiple of 64
+    int32_t row0;              // first list position this source covers: [row0, row0 + count_max)
 };
 
 struct ValuePassParams {
@@ -34,7 +37,6 @@ struct ValuePassParams {
     int32_t n_units;
     int32_t chunks_per_unit;
     int32_t n_sources;
-    int32_t chunk_rows;        // rows per workgroup, a multiple of kChunkRowsMin
     float scale_log2e;         // softmax scale * log2(e)
     RowSource src[kMaxSources];
 };
@@ -50,47 +52,49 @@ hipError_t launch_merge(const float* partials, int n_units, int chunks_per_unit,
 // ------------------------------------------------------------------------------------------------
 struct ScoreParams {
     const uint16_t* q;          // bf16 [U*G, 128]
-    const uint16_t* Kc;         // bf16 [U, tab_rows, 128]: fine rows, then coarse rows at row_off
+    const uint16_t* Kc;         // bf16 [U, tab_rows, 128]: fine rows, then coarse rows from row fcap
     const int32_t* N;           // [U, tab_rows]
     long long tab_rows;
-    int row_off;                // row of candidate id 0 at this level
-    const int32_t* cand;        // [U, cand_stride] candidate ids, or nullptr = identity
-    long long cand_stride;
-    const int32_t* n_cand_dev;  // [U] or nullptr
-    int n_cand_fixed;
-    long long budget;
+    int fcap;
+    int levels, n_fine, n_coarse;
+    long long key_budget, coarse_budget;
     double scale;
-    const double* extra_lse;    // [U, G] log-sum of terms that join the Eq. 1 denominator, or nullptr
-    double* lg;                 // [U, G, lg_stride] logits by candidate position
-    long long lg_stride;
-    double* r_out;              // [U, r_stride] rank key by candidate position (NaN if N == 0)
-    long long r_stride;
-    uint8_t* flag_out;          // [U, r_stride] 1 = promising / selected, by candidate position
-    // coarse level only
     const int32_t* cstart;      // [U, cstart_stride] first child of each coarse cluster
     long long cstart_stride;
-    int32_t* cand_out;          // [U, cand_out_stride]
-    long long cand_out_stride;
-    int32_t* n_cand_out;        // [U]
-    double* unprom_lse_out;     // [U, G]
-    // fine level only
     const int32_t* fstart;      // [U, fstart_stride] first stored row of each fine cluster
     long long fstart_stride;
-    int32_t* rows_out;          // [U, rows_stride]
+    // working arrays in global memory, used by a level with more than lds_cap entries
+    double* lg;                 // [U, G, lg_stride]
+    long long lg_stride;
+    unsigned long long* g_keys; // [U, g_stride]
+    uint32_t* g_wts;
+    int32_t* g_ids;
+    int32_t* g_aux;
+    int32_t* g_aux2;
+    uint8_t* g_flags;
+    long long g_stride;
+    // per-position views of the last call (for the getters)
+    double* r_c;                // [U, c_stride] coarse rank keys (NaN if N == 0)
+    uint8_t* flag_c;            // [U, c_stride] promising
+    long long c_stride;
+    double* r_f;                // [U, f_stride] fine rank keys by candidate position
+    uint8_t* flag_f;            // [U, f_stride] selected, by candidate position
+    long long f_stride;
+    int32_t* cand;              // [U, f_stride] candidate fine ids (two levels)
+    int32_t* n_cand;            // [U]
+    // outputs for the value pass
+    int32_t* rows;              // [U, rows_stride] stored rows of the selected keys
     long long rows_stride;
-    int32_t* n_rows_out;        // [U]
-    // centroid-term list (both levels)
-    int32_t* mp_rows;           // [U, mp_stride] row in the centroid table
+    int32_t* n_rows;            // [U]
+    int32_t* mp_rows;           // [U, mp_stride] centroid-table row of each centroid term
     float* mp_scores;           // [U, mp_stride, G] (l + ln N) * log2(e)
     long long mp_stride;
-    int32_t* n_mp;              // [U]: coarse writes, fine appends (fine starts at 0 if mp_append == 0)
-    int mp_append;
+    int32_t* n_mp;              // [U]
     int use_mp;
     int32_t* counters;          // [U, 4]
     int n_tail;
-    int smem_cap;               // candidate capacity of the LDS arrays
-    int G, U;                   // group size, units
-    int coarse;                 // 1 = coarse level launch
+    int lds_cap;                // entries of a level that fit the LDS working arrays
+    int G, U;
 };
 
 hipError_t launch_score_select(const ScoreParams& p, hipStream_t stream);

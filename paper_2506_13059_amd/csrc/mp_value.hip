@@ -23,6 +23,32 @@ struct RowRegs {
     uint4 klo, khi, vlo, vhi;
 };
 
+// 16-byte global load issued through inline assembly: the compiler neither moves it towards its
+// use nor waits for it, so the software pipeline below stays as written.  Every use of the result
+// must be preceded by wait_rows<N>(), N = number of such loads issued after the ones needed
+// (vector memory loads return in order).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void issue_load16(u32x4& d, const void* p)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(d) : "v"(p) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_rows(u32x4 (&b)[8])
+{
+    asm volatile("s_waitcnt vmcnt(%8)"
+                 : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7])
+                 : "n"(N));
+}
+__device__ __forceinline__ RowRegs as_row(const u32x4& klo, const u32x4& khi, const u32x4& vlo, const u32x4& vhi)
+{
+    RowRegs t;
+    t.klo = make_uint4(klo.x, klo.y, klo.z, klo.w);
+    t.khi = make_uint4(khi.x, khi.y, khi.z, khi.w);
+    t.vlo = make_uint4(vlo.x, vlo.y, vlo.z, vlo.w);
+    t.vhi = make_uint4(vhi.x, vhi.y, vhi.z, vhi.w);
+    return t;
+}
+
 __device__ __forceinline__ void load_row(RowRegs& t, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                                          long long row, int c)
 {
@@ -119,7 +145,135 @@ __device__ __forceinline__ void softmax_step(HeadState<G>& st, const float (&s0)
     accumulate_v<G>(st, t1, p1);
 }
 
-constexpr int kStrip = 128;   // rows a wave handles between two refills of its index registers
+
+// Stream the rows [w0, w1) of a source through one wave, 16 rows per iteration (two per group of 8
+// lanes), in strips of 128 rows whose row numbers are fetched with two coalesced loads.
+//
+// kScored = false (exact rows, the hot path): a three-stage software pipeline.  The loads of
+// iterations it+1 and it+2 are in flight while iteration it is consumed; they are issued through
+// inline assembly and waited for by count, because the compiler would otherwise sink each load
+// next to its use.  All eight iterations of a strip issue their loads (rows past the end are
+// clamped to the last valid row and masked), so the counts are static.
+// kScored = true (centroid terms): logits are read ready-made (log2 units, ln N included) and
+// only the value-centroid row is loaded; this stream is short and uses plain loads.
+template <int G, bool kScored, int kIters>
+__device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S, const ValuePassParams& p, int u,
+                                            int w0, int w1, int end, int r, int c, int lane)
+{
+    const uint16_t* __restrict__ Vb = S.V + (long long)u * S.unit_rows * kHeadDim;
+    const int32_t* __restrict__ rows = S.rows ? S.rows + (long long)u * S.rows_stride : nullptr;
+    constexpr int kStrip = 16 * kIters;   // rows a wave handles between two refills of its index registers
+    if constexpr (kScored) {
+        const float* __restrict__ sc = S.scores + (long long)u * S.rows_stride * G;
+        for (int j0 = w0; j0 < w1; j0 += 16) {
+            const int ja = j0 + r, jb = j0 + 8 + r;
+            const bool va = ja < w1, vb = jb < w1;
+            const int pa = va ? ja : w1 - 1, pb = vb ? jb : w1 - 1;
+            const int ia = rows ? rows[pa] : pa, ib = rows ? rows[pb] : pb;
+            RowRegs t0, t1;
+            load_vrow(t0, Vb, ia, c);
+            load_vrow(t1, Vb, ib, c);
+            float s0[G], s1[G];
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                s0[h] = va ? sc[(long long)pa * G + h] : -INFINITY;
+                s1[h] = vb ? sc[(long long)pb * G + h] : -INFINITY;
+            }
+            softmax_step<G>(st, s0, s1, t0, t1);
+        }
+    } else {
+        const uint16_t* __restrict__ Kb = S.K + (long long)u * S.unit_rows * kHeadDim;
+        uint4 qlo[G], qhi[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            const uint4* qp = reinterpret_cast<const uint4*>(p.q + ((long long)u * G + h) * kHeadDim) + c;
+            qlo[h] = qp[0];
+            qhi[h] = qp[8];
+        }
+        const float scale = p.scale_log2e;
+        for (int j0 = w0; j0 < w1; j0 += kStrip) {
+            int pa = j0 + lane, pb = j0 + 64 + lane;
+            pa = pa < end ? pa : end - 1;
+            pb = pb < end ? pb : end - 1;
+            int ia = pa, ib = pb;
+            if (rows) {
+                ia = rows[pa];
+                ib = rows[pb];
+            }
+            if constexpr (G <= 4) {
+                u32x4 buf[3][8];
+                auto issue = [&](int it, u32x4 (&b)[8]) {
+                    const int slot = it * 16 + r;
+                    const int src_reg = (slot < 64) ? ia : ib;   // resolved at compile time after unrolling
+                    const long long i0 = __shfl(src_reg, slot & 63, 64);
+                    const long long i1 = __shfl(src_reg, (slot + 8) & 63, 64);
+                    const uint4* k0 = reinterpret_cast<const uint4*>(Kb + i0 * kHeadDim) + c;
+                    const uint4* v0 = reinterpret_cast<const uint4*>(Vb + i0 * kHeadDim) + c;
+                    const uint4* k1 = reinterpret_cast<const uint4*>(Kb + i1 * kHeadDim) + c;
+                    const uint4* v1 = reinterpret_cast<const uint4*>(Vb + i1 * kHeadDim) + c;
+                    issue_load16(b[0], k0);
+                    issue_load16(b[1], k0 + 8);
+                    issue_load16(b[2], v0);
+                    issue_load16(b[3], v0 + 8);
+                    issue_load16(b[4], k1);
+                    issue_load16(b[5], k1 + 8);
+                    issue_load16(b[6], v1);
+                    issue_load16(b[7], v1 + 8);
+                };
+                issue(0, buf[0]);
+                if (kIters > 1) issue(1, buf[1]);
+#pragma unroll
+                for (int it = 0; it < kIters; ++it) {
+                    const int jj = j0 + it * 16;
+                    if (it + 2 < kIters) issue(it + 2, buf[(it + 2) % 3]);
+                    u32x4(&b)[8] = buf[it % 3];
+                    if (it + 2 < kIters) wait_rows<16>(b);
+                    else if (it + 1 < kIters) wait_rows<8>(b);
+                    else wait_rows<0>(b);
+                    if (jj < w1) {
+                        const RowRegs cur0 = as_row(b[0], b[1], b[2], b[3]);
+                        const RowRegs cur1 = as_row(b[4], b[5], b[6], b[7]);
+                        float s0[G], s1[G];
+                        qk_scores<G>(cur0, qlo, qhi, scale, jj + r < w1, s0);
+                        qk_scores<G>(cur1, qlo, qhi, scale, jj + 8 + r < w1, s1);
+                        softmax_step<G>(st, s0, s1, cur0, cur1);
+                    }
+                }
+            } else {
+                // larger groups leave no registers for the hand-scheduled pipeline (the compiler would have
+                // to spill registers that are still in flight): plain loads, one iteration ahead
+                RowRegs cur0, cur1, nx0, nx1;
+                {
+                    const int i0 = __shfl(ia, r, 64), i1 = __shfl(ia, 8 + r, 64);
+                    load_row(cur0, Kb, Vb, i0, c);
+                    load_row(cur1, Kb, Vb, i1, c);
+                }
+#pragma unroll
+                for (int it = 0; it < kIters; ++it) {
+                    const int jj = j0 + it * 16;
+                    if (jj >= w1) break;
+                    const bool more = (it + 1 < kIters) && (jj + 16 < w1);
+                    if (more) {
+                        const int slot = (it + 1) * 16 + r;
+                        const int src_reg = (slot < 64) ? ia : ib;   // resolved at compile time after unrolling
+                        const int i0 = __shfl(src_reg, slot & 63, 64);
+                        const int i1 = __shfl(src_reg, (slot + 8) & 63, 64);
+                        load_row(nx0, Kb, Vb, i0, c);
+                        load_row(nx1, Kb, Vb, i1, c);
+                    }
+                    float s0[G], s1[G];
+                    qk_scores<G>(cur0, qlo, qhi, scale, jj + r < w1, s0);
+                    qk_scores<G>(cur1, qlo, qhi, scale, jj + 8 + r < w1, s1);
+                    softmax_step<G>(st, s0, s1, cur0, cur1);
+                    if (more) {
+                        cur0 = nx0;
+                        cur1 = nx1;
+                    }
+                }
+            }
+        }
+    }
+}
 
 template <int G>
 __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p)
@@ -127,8 +281,10 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
     constexpr int HB = G < 4 ? G : 4;   // heads combined per round of the epilogue
     extern __shared__ float smem[];
 
-    const int u = blockIdx.x / p.chunks_per_unit;
-    const int cidx = blockIdx.x - u * p.chunks_per_unit;
+    // chunk-major order: the first chunks of every unit are dispatched first, so the workgroups that
+    // run last are the (often partly filled) last chunks of the longest source
+    const int cidx = blockIdx.x / p.n_units;
+    const int u = blockIdx.x - cidx * p.n_units;
     int si = 0;
 #pragma unroll
     for (int i = 1; i < kMaxSources; ++i)
@@ -139,13 +295,13 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
     const int wave = tid >> 6, lane = tid & 63;
     const int r = lane >> 3, c = lane & 7;
 
-    int count = S.count_max;
+    int count = S.row0 + S.count_max;
     if (S.count_dev) {
         const int cd = S.count_dev[u];
         count = cd < count ? cd : count;
     }
-    const int chunk_rows = p.chunk_rows;
-    const int begin = (cidx - S.chunk0) * chunk_rows;
+    const int chunk_rows = S.chunk_rows;
+    const int begin = S.row0 + (cidx - S.chunk0) * chunk_rows;
     const int end = (begin + chunk_rows < count) ? begin + chunk_rows : count;
     float* part = p.partials + ((long long)u * p.chunks_per_unit + cidx) * G * kPartStride;
     if (begin >= end) {   // nothing to do for this chunk: an empty partial
@@ -168,79 +324,12 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
     const int wave_rows = chunk_rows >> 2;
     const int w0 = begin + wave * wave_rows;
     const int w1 = (w0 + wave_rows < end) ? w0 + wave_rows : end;
-    const uint16_t* __restrict__ Vb = S.V + (long long)u * S.unit_rows * kHeadDim;
-    const int32_t* __restrict__ rows = S.rows ? S.rows + (long long)u * S.rows_stride : nullptr;
-
-    if (S.scores == nullptr) {
-        // -------- exact rows: scores from q.k --------
-        const uint16_t* __restrict__ Kb = S.K + (long long)u * S.unit_rows * kHeadDim;
-        uint4 qlo[G], qhi[G];
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            const uint4* qp = reinterpret_cast<const uint4*>(p.q + ((long long)u * G + h) * kHeadDim) + c;
-            qlo[h] = qp[0];
-            qhi[h] = qp[8];
-        }
-        const float scale = p.scale_log2e;
-        for (int j0 = w0; j0 < w1; j0 += kStrip) {
-            // positions of this strip's rows, two per lane, fetched with coalesced loads
-            int pa = j0 + lane, pb = j0 + 64 + lane;
-            pa = pa < end ? pa : end - 1;
-            pb = pb < end ? pb : end - 1;
-            int ia = pa, ib = pb;
-            if (rows) {
-                ia = rows[pa];
-                ib = rows[pb];
-            }
-            RowRegs cur0, cur1, nx0, nx1;
-            {
-                const int i0 = __shfl(ia, r, 64), i1 = __shfl(ia, 8 + r, 64);
-                load_row(cur0, Kb, Vb, i0, c);
-                load_row(cur1, Kb, Vb, i1, c);
-            }
-#pragma unroll
-            for (int it = 0; it < kStrip / 16; ++it) {
-                const int jj = j0 + it * 16;
-                if (jj >= w1) break;
-                const bool more = (it + 1 < kStrip / 16) && (jj + 16 < w1);
-                if (more) {
-                    const int slot = (it + 1) * 16 + r;
-                    const int src_reg = (slot < 64) ? ia : ib;
-                    const int i0 = __shfl(src_reg, slot & 63, 64);
-                    const int i1 = __shfl(src_reg, (slot + 8) & 63, 64);
-                    load_row(nx0, Kb, Vb, i0, c);
-                    load_row(nx1, Kb, Vb, i1, c);
-                }
-                float s0[G], s1[G];
-                qk_scores<G>(cur0, qlo, qhi, scale, jj + r < w1, s0);
-                qk_scores<G>(cur1, qlo, qhi, scale, jj + 8 + r < w1, s1);
-                softmax_step<G>(st, s0, s1, cur0, cur1);
-                if (more) {
-                    cur0 = nx0;
-                    cur1 = nx1;
-                }
-            }
-        }
-    } else {
-        // -------- centroid terms: ready-made logits (already in log2 units, ln N included) --------
-        const float* __restrict__ sc = S.scores + (long long)u * S.rows_stride * G;
-        for (int j0 = w0; j0 < w1; j0 += 16) {
-            const int ja = j0 + r, jb = j0 + 8 + r;
-            const bool va = ja < w1, vb = jb < w1;
-            const int pa = va ? ja : w1 - 1, pb = vb ? jb : w1 - 1;
-            const int ia = rows ? rows[pa] : pa, ib = rows ? rows[pb] : pb;
-            RowRegs t0, t1;
-            load_vrow(t0, Vb, ia, c);
-            load_vrow(t1, Vb, ib, c);
-            float s0[G], s1[G];
-#pragma unroll
-            for (int h = 0; h < G; ++h) {
-                s0[h] = va ? sc[(long long)pa * G + h] : -INFINITY;
-                s1[h] = vb ? sc[(long long)pb * G + h] : -INFINITY;
-            }
-            softmax_step<G>(st, s0, s1, t0, t1);
-        }
-    }
+    if (S.scores != nullptr)
+        stream_rows<G, true, 8>(st, S, p, u, w0, w1, end, r, c, lane);
+    else if (chunk_rows >= 512)
+        stream_rows<G, false, 8>(st, S, p, u, w0, w1, end, r, c, lane);
+    else
+        stream_rows<G, false, 2>(st, S, p, u, w0, w1, end, r, c, lane);
 
     // -------- combine the 32 row groups of the workgroup (4 waves x 8 groups), HB heads per round ----
     float* sm_m = smem;             // [32][HB]
@@ -268,18 +357,24 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
             }
         }
         __syncthreads();
-        if (tid < HB && hb + tid < G) {
-            float M = -INFINITY;
-            for (int s = 0; s < 32; ++s) M = fmaxf(M, sm_m[s * HB + tid]);
+        if (wave < HB && hb + wave < G) {
+            // wave hh handles head hh: lane s < 32 holds the state of row group s
+            const int hh = wave;
+            const float mi = (lane < 32) ? sm_m[lane * HB + hh] : -INFINITY;
+            float M = mi;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
             const float Ms = (M == -INFINITY) ? 0.f : M;
-            float L = 0.f;
-            for (int s = 0; s < 32; ++s) {
-                const float w = __builtin_amdgcn_exp2f(sm_m[s * HB + tid] - Ms);
-                sm_w[s * HB + tid] = w;
-                L += sm_l[s * HB + tid] * w;
+            const float w = (lane < 32) ? __builtin_amdgcn_exp2f(mi - Ms) : 0.f;
+            float L = (lane < 32) ? sm_l[lane * HB + hh] * w : 0.f;
+            if (lane < 32) sm_w[lane * HB + hh] = w;
+            // fixed-order sum over the 32 groups (butterfly: the same order on every run)
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off, 64);
+            if (lane == 0) {
+                sm_ml[2 * hh] = M;
+                sm_ml[2 * hh + 1] = L;
             }
-            sm_ml[2 * tid] = M;
-            sm_ml[2 * tid + 1] = L;
         }
         __syncthreads();
         for (int o = tid; o < HB * 64; o += 256) {

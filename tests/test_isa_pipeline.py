@@ -1,0 +1,85 @@
+"""CPU-only check of the hand-scheduled load pipeline in the value pass.
+
+The exact-row loop issues its 16-byte loads through inline assembly and waits for them by count.
+The compiler does not know those registers are in flight, so nothing it emits may touch a
+destination register between the load and the matching wait.  This test compiles the kernel to
+gfx950 assembly and replays the instruction stream of every instantiation that uses the pipeline.
+"""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "paper_2506_13059_amd", "csrc", "mp_value.hip")
+
+
+def _regs(text):
+    out = set()
+    for a, b in re.findall(r"\bv\[(\d+):(\d+)\]", text):
+        out.update(range(int(a), int(b) + 1))
+    for a in re.findall(r"\bv(\d+)\b", text):
+        out.add(int(a))
+    return out
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not available")
+def test_no_instruction_touches_a_register_that_is_still_in_flight(tmp_path):
+    asm = tmp_path / "mp_value.s"
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                           "-packed-fp32-ops", "-S", "--cuda-device-only", "-o", str(asm), SRC],
+                          stderr=subprocess.DEVNULL)
+    lines = asm.read_text().splitlines()
+    checked = 0
+    i = 0
+    while i < len(lines):
+        m = re.match(r"^(_ZN2mp\S*value_pass_kernelILi(\d+)E\S*):", lines[i])
+        if not m:
+            i += 1
+            continue
+        G = int(m.group(2))
+        j = i + 1
+        pending = []            # destination register sets of the in-flight asm loads, oldest first
+        in_asm = False
+        n_loads = n_waits = 0
+        while j < len(lines) and "s_endpgm" not in lines[j]:
+            ln = lines[j].strip()
+            j += 1
+            if ln.startswith(";;#ASMSTART"):
+                in_asm = True
+                continue
+            if ln.startswith(";;#ASMEND"):
+                in_asm = False
+                continue
+            if not ln or ln.startswith(";") or ln.startswith(".") or ln.endswith(":"):
+                continue
+            if in_asm and ln.startswith("global_load_dwordx4"):
+                dst = re.match(r"global_load_dwordx4 v\[(\d+):(\d+)\]", ln)
+                regs = set(range(int(dst.group(1)), int(dst.group(2)) + 1))
+                addr = _regs(ln.split(",", 1)[1])
+                for pset in pending:
+                    assert not (pset & (regs | addr)), f"G={G}: {ln} overlaps an in-flight load"
+                pending.append(regs)
+                n_loads += 1
+                continue
+            if in_asm and ln.startswith("s_waitcnt vmcnt"):
+                n = int(re.search(r"vmcnt\((\d+)\)", ln).group(1))
+                while len(pending) > n:
+                    pending.pop(0)
+                n_waits += 1
+                continue
+            if ln.startswith("s_waitcnt") and "vmcnt(0)" in ln:
+                pending.clear()
+                continue
+            used = _regs(ln)
+            for pset in pending:
+                assert not (pset & used), f"G={G}: `{ln}` touches a register of a load still in flight"
+        if G <= 4:
+            assert n_loads == 64 + 16 and n_waits == 8 + 2, (G, n_loads, n_waits)
+            checked += 1
+        else:
+            assert n_loads == 0
+        i = j
+    assert checked == 4
