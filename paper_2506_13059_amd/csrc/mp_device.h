@@ -98,30 +98,73 @@ __device__ __forceinline__ double sum4_f64(double v)
     return v;
 }
 
-// ---- whole-wave helpers (wave64) ---------------------------------------------------------------
+// ---- whole-wave helpers (wave64), built from DPP row operations ----------------------------------
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 
+// DPP move that leaves 0 in lanes without a source lane or outside kRowMask.
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ uint32_t dpp_u32_or0(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kCtrl, kRowMask, 0xf, false);
+}
+// Inclusive prefix sum over the 64 lanes: shifts by 1, 2, 4, 8 inside each row of 16, then the last
+// lane of row 0 / row 2 is added to the following row and the last lane of the lower half to the
+// upper half (row_bcast15 / row_bcast31).
 __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v)
 {
-    const int lane = lane_id();
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        uint32_t t = __shfl_up(v, off, 64);
-        if (lane >= off) v += t;
-    }
+    v += dpp_u32_or0<0x111, 0xf>(v);
+    v += dpp_u32_or0<0x112, 0xf>(v);
+    v += dpp_u32_or0<0x114, 0xf>(v);
+    v += dpp_u32_or0<0x118, 0xf>(v);
+    v += dpp_u32_or0<0x142, 0xa>(v);
+    v += dpp_u32_or0<0x143, 0xc>(v);
     return v;
 }
+__device__ __forceinline__ double readlane_f64(double v, int src)
+{
+    const long long b = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_readlane((int)(b & 0xffffffffll), src);
+    const int hi = __builtin_amdgcn_readlane((int)(b >> 32), src);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+// Reductions over a row of 16 lanes; every lane of the row receives the result.
+__device__ __forceinline__ double row_sum_f64(double v)
+{
+    v += dpp_f64<kDppXor1>(v);
+    v += dpp_f64<kDppXor2>(v);
+    v += dpp_f64<kDppHalfMirror>(v);
+    v += dpp_f64<kDppMirror>(v);
+    return v;
+}
+__device__ __forceinline__ double row_max_f64(double v)
+{
+    v = fmax(v, dpp_f64<kDppXor1>(v));
+    v = fmax(v, dpp_f64<kDppXor2>(v));
+    v = fmax(v, dpp_f64<kDppHalfMirror>(v));
+    v = fmax(v, dpp_f64<kDppMirror>(v));
+    return v;
+}
+__device__ __forceinline__ float row_max_f32(float v)
+{
+    v = fmaxf(v, dpp_f32<kDppXor1>(v));
+    v = fmaxf(v, dpp_f32<kDppXor2>(v));
+    v = fmaxf(v, dpp_f32<kDppHalfMirror>(v));
+    v = fmaxf(v, dpp_f32<kDppMirror>(v));
+    return v;
+}
+// Whole-wave reductions; the result is wave-uniform.
 __device__ __forceinline__ double wave_sum_f64(double v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v = row_sum_f64(v);
+    return (readlane_f64(v, 0) + readlane_f64(v, 16)) + (readlane_f64(v, 32) + readlane_f64(v, 48));
 }
-__device__ __forceinline__ double wave_max_f64(double v)
+__device__ __forceinline__ float wave_max_f32(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmax(v, __shfl_xor(v, off, 64));
-    return v;
+    v = row_max_f32(v);
+    const int b = __float_as_int(v);
+    const float a0 = __int_as_float(__builtin_amdgcn_readlane(b, 0)), a1 = __int_as_float(__builtin_amdgcn_readlane(b, 16));
+    const float a2 = __int_as_float(__builtin_amdgcn_readlane(b, 32)), a3 = __int_as_float(__builtin_amdgcn_readlane(b, 48));
+    return fmaxf(fmaxf(a0, a1), fmaxf(a2, a3));
 }
 
 }  // namespace mp

@@ -1,26 +1,28 @@
 // Centroid scoring and budgeted cluster selection for gfx950 (Eq. 1, Sec. 3.1; two levels: Sec. 3.4).
 //
 // One launch per decode step, one workgroup of 512 threads per unit; the coarse level and the fine
-// level run back to back in the same workgroup, so candidate ids, counts and the unpromising
-// clusters' log-sum never leave the chip.
+// level run back to back in the same workgroup.
 //
 // Logits l[h,i] = scale * q_h . Kc_i are accumulated in fp64 (products of bf16 numbers are exact,
 // so the sum carries ~1e-16 relative error and the ranking agrees with an fp64 reference except on
-// ties far below any tolerance).  16 lanes share one centroid row (one coalesced 16-byte load per
-// lane), each lane keeps its 8 query dims of every head in registers as doubles, partial sums are
-// combined with DPP.  The rank key is log(mean_h exp(l[h,i] - LSE_h)), the logarithm of Eq. 1
-// averaged over the query heads of the group.  Selection = "take clusters in descending key order
-// (ties: lower id) while the running token count stays within the budget, stop at the first that
-// does not fit"; token counts are positive, so this is a threshold on (key, id), found by a
-// weighted most-significant-digit radix select instead of a sort.
+// ties far below any tolerance).  A group of 8 lanes (16 for more than 4 heads) shares one centroid
+// row with coalesced 16-byte loads; each lane keeps its slice of every query head in registers as
+// doubles and partial sums are combined with DPP.  The rank key is log(mean_h exp(l[h,i] - LSE_h)),
+// the logarithm of Eq. 1 averaged over the query heads of the group.  Selection = "take clusters in
+// descending key order (ties: lower id) while the running token count stays within the budget, stop
+// at the first that does not fit"; token counts are positive, so this is a threshold on (key, id),
+// found by a weighted most-significant-digit radix select instead of a sort.
 //
 // Per-entry working arrays (logits, keys, counts, ids, row starts, flags) live in LDS when a level
-// has at most lds_cap entries and in a global scratch area otherwise; they are reached through
-// generic pointers chosen per level at run time.
+// has at most lds_cap entries and in a global scratch area otherwise.  The two cases are separate
+// template instantiations, so that the LDS case uses LDS instructions and LDS-only barriers (the
+// kernel's global stores are never read back by the same workgroup in that case).
 //
 // Outputs for the value pass: the flat list of stored rows of the selected clusters' keys, and one
 // "centroid term" entry (value-centroid row + ready-made logits) per cluster that stays behind at
 // either level (unpromising coarse clusters, unselected fine candidates).
+#include <type_traits>
+
 #include "mp_device.h"
 #include "mp_internal.h"
 
@@ -37,17 +39,21 @@ __device__ __forceinline__ uint64_t descending_key(double r)
     b = (b >> 63) ? ~b : (b | 0x8000000000000000ull);   // ascending in r
     return ~b;                                           // ascending key = descending r
 }
+__device__ __forceinline__ double key_to_rank(uint64_t key)
+{
+    uint64_t b = ~key;
+    b = (b >> 63) ? (b & 0x7fffffffffffffffull) : ~b;
+    return __longlong_as_double((long long)b);
+}
 
 struct Scratch {
-    double red[kWaves * 8];      // cross-wave reductions, up to 8 heads
-    double bc[8];                // broadcast values (per head)
-    double extra[8];             // log-sum of the unpromising coarse clusters' N e^l, per head
-    uint32_t hist_w[256];
-    uint32_t hist_c[256];
-    uint32_t wsum[kWaves];
-    uint32_t carry;
-    uint32_t sel_digit, sel_found, sel_cnt;
-    unsigned long long sel_acc;
+    double red_m[(kWaves + 1) * 8];   // per wave (and one extra slot), per head: shift
+    double red_s[(kWaves + 1) * 8];   // ... and sum
+    double extra[8];                  // log-sum of the unpromising coarse clusters' N e^l, per head
+    unsigned long long hist[3][256];  // radix digit histograms: entry count << 40 | token count
+    unsigned long long rk_min[kWaves], rk_max[kWaves];  // per wave: smallest / largest key that takes part
+    uint32_t rk_wt[kWaves], rk_cn[kWaves];              // ... their token total and their number
+    uint32_t wsum[2][kWaves][2];      // per-wave totals of the two-value scan, double-buffered
     unsigned long long sel_key;
 };
 
@@ -58,168 +64,287 @@ struct Arrays {
     uint32_t* wts;
     int32_t* ids;
     int32_t* aux;          // fine: first stored row; coarse: first child
-    int32_t* aux2;         // coarse: end of children
+    int32_t* aux2;         // coarse: end of children; fine: offset of the cluster's rows in the row list
     uint8_t* flags;
 };
 
-template <int G>
-__device__ __forceinline__ void block_max(double (&v)[G], Scratch& s)
+// Barrier between phases.  With the working arrays in LDS nothing written to global memory is read
+// back inside the kernel, so only LDS traffic has to be ordered and outstanding global stores may
+// stay in flight.
+template <bool kLds>
+__device__ __forceinline__ void phase_sync()
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-        const double w = wave_max_f64(v[h]);
-        if (lane == 0) s.red[wave * 8 + h] = w;
+    if constexpr (kLds) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    } else {
+        __syncthreads();
     }
-    __syncthreads();
-    if (threadIdx.x < G) {
-        double m = s.red[threadIdx.x];
-        for (int w = 1; w < kWaves; ++w) m = fmax(m, s.red[w * 8 + threadIdx.x]);
-        s.bc[threadIdx.x] = m;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int h = 0; h < G; ++h) v[h] = s.bc[h];
-    __syncthreads();
 }
 
-// sum over the workgroup in a fixed order (bit-reproducible)
-template <int G>
-__device__ __forceinline__ void block_sum(double (&v)[G], Scratch& s)
+// lse[h] = log( sum over the entries with pred(i) of N_i e^{l[h,i]}  [+ e^{extra_h}] ) for every head.
+// Each wave reduces its entries to a (shift, sum) pair per head; after one barrier every wave
+// combines the pairs of all waves by itself (one row of 16 lanes per head), so the result needs no
+// second barrier.  S.red_* are reused by the next call: callers have a barrier between two calls.
+template <int G, bool kLds, typename Pred>
+__device__ __forceinline__ void weighted_lse(const Arrays& A, Scratch& S, int n, bool with_extra, Pred pred,
+                                             double (&lse)[G])
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float mxf[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) mxf[h] = -INFINITY;
+    for (int i = tid; i < n; i += kThreads)
+        if (pred(i))
+#pragma unroll
+            for (int h = 0; h < G; ++h) mxf[h] = fmaxf(mxf[h], (float)A.lg[h * A.lg_stride + i]);
+    double mw[G], sm[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-        const double w = wave_sum_f64(v[h]);
-        if (lane == 0) s.red[wave * 8 + h] = w;
+        mw[h] = (double)wave_max_f32(mxf[h]);     // a shift close to the wave's maximum is all that is needed
+        sm[h] = 0.0;
     }
-    __syncthreads();
-    if (threadIdx.x < G) {
-        double m = 0.0;
-        for (int w = 0; w < kWaves; ++w) m += s.red[w * 8 + threadIdx.x];
-        s.bc[threadIdx.x] = m;
-    }
-    __syncthreads();
+    for (int i = tid; i < n; i += kThreads)
+        if (pred(i)) {
+            const double w = (double)A.wts[i];
 #pragma unroll
-    for (int h = 0; h < G; ++h) v[h] = s.bc[h];
-    __syncthreads();
+            for (int h = 0; h < G; ++h) sm[h] += w * exp(A.lg[h * A.lg_stride + i] - mw[h]);
+        }
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        const double t = wave_sum_f64(sm[h]);
+        if (lane == 0) {
+            S.red_m[wave * 8 + h] = mw[h];
+            S.red_s[wave * 8 + h] = t;
+        }
+    }
+    if (tid < G) {
+        S.red_m[kWaves * 8 + tid] = with_extra ? S.extra[tid] : -INFINITY;
+        S.red_s[kWaves * 8 + tid] = with_extra ? 1.0 : 0.0;
+    }
+    phase_sync<kLds>();
+#pragma unroll
+    for (int h0 = 0; h0 < G; h0 += 4) {
+        const int h = h0 + (lane >> 4), w = lane & 15;
+        const bool live = h < G && w <= kWaves;
+        double m = live ? S.red_m[w * 8 + h] : -INFINITY;
+        const double sv = live ? S.red_s[w * 8 + h] : 0.0;
+        if (!(sv > 0.0)) m = -INFINITY;
+        const double M = row_max_f64(m);
+        double t = (m == -INFINITY) ? 0.0 : sv * exp(m - M);
+        t = row_sum_f64(t);
+        const double r = (M == -INFINITY) ? -INFINITY : M + log(t);
+#pragma unroll
+        for (int hh = 0; hh < 4; ++hh)
+            if (h0 + hh < G) lse[h0 + hh] = readlane_f64(r, 16 * hh);
+    }
 }
 
-// Exclusive prefix sum over one chunk of kThreads values (one per thread) with a running carry in
-// s.carry; returns the exclusive prefix including the carry.  All threads must call.
-__device__ __forceinline__ uint32_t chunk_excl_scan(uint32_t v, Scratch& s)
+// Exclusive prefix sums of two values per thread over one chunk of kThreads threads, with running
+// totals carried in registers (every thread adds the same chunk totals, so they stay uniform).
+// One barrier per call: the per-wave totals are double-buffered by the parity of `calls`.
+struct ScanState {
+    uint32_t carry_a = 0, carry_b = 0, calls = 0;
+};
+template <bool kLds>
+__device__ __forceinline__ void chunk_excl_scan2(uint32_t a, uint32_t b, Scratch& s, ScanState& st, uint32_t& ex_a,
+                                                 uint32_t& ex_b)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t incl = wave_incl_scan_u32(v);
-    if (lane == 63) s.wsum[wave] = incl;
-    __syncthreads();
-    uint32_t woff = 0;
-    for (int w = 0; w < wave; ++w) woff += s.wsum[w];
-    const uint32_t carry = s.carry;
-    const uint32_t excl = carry + woff + incl - v;
-    __syncthreads();
-    if (threadIdx.x == kThreads - 1) s.carry = carry + woff + incl;
-    __syncthreads();
-    return excl;
+    const uint32_t ia = wave_incl_scan_u32(a), ib = wave_incl_scan_u32(b);
+    const int par = st.calls & 1;
+    ++st.calls;
+    if (lane == 63) {
+        s.wsum[par][wave][0] = ia;
+        s.wsum[par][wave][1] = ib;
+    }
+    phase_sync<kLds>();
+    uint32_t off_a = 0, off_b = 0, tot_a = 0, tot_b = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t wa = s.wsum[par][w][0], wb = s.wsum[par][w][1];
+        off_a += (w < wave) ? wa : 0u;
+        off_b += (w < wave) ? wb : 0u;
+        tot_a += wa;
+        tot_b += wb;
+    }
+    ex_a = st.carry_a + off_a + ia - a;
+    ex_b = st.carry_b + off_b + ib - b;
+    st.carry_a += tot_a;
+    st.carry_b += tot_b;
+}
+
+template <typename T, typename Op>
+__device__ __forceinline__ T wave_reduce(T v, Op op)
+{
+    auto moved = [](T x, auto ctrl) {
+        constexpr int kCtrl = decltype(ctrl)::value;
+        if constexpr (sizeof(T) == 4) {
+            return (T)__builtin_amdgcn_mov_dpp((int)x, kCtrl, 0xf, 0xf, true);
+        } else {
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)x, kCtrl, 0xf, 0xf, true);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(x >> 32), kCtrl, 0xf, 0xf, true);
+            return (T)(((uint64_t)hi << 32) | lo);
+        }
+    };
+    auto lane_value = [](T x, int src) {
+        if constexpr (sizeof(T) == 4) {
+            return (T)__builtin_amdgcn_readlane((int)x, src);
+        } else {
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, src);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), src);
+            return (T)(((uint64_t)hi << 32) | lo);
+        }
+    };
+    v = op(v, moved(v, std::integral_constant<int, kDppXor1>{}));
+    v = op(v, moved(v, std::integral_constant<int, kDppXor2>{}));
+    v = op(v, moved(v, std::integral_constant<int, kDppHalfMirror>{}));
+    v = op(v, moved(v, std::integral_constant<int, kDppMirror>{}));
+    return op(op(lane_value(v, 0), lane_value(v, 16)), op(lane_value(v, 32), lane_value(v, 48)));
 }
 
 // Weighted radix select.  keys[i] ascending = rank order, wts[i] > 0 for entries that take part
 // (entries with wts == 0 are never selected).  Finds the key K* of the first entry (in (key, index)
 // order) at which the running weight exceeds `budget`, the weight `acc` of all entries with key <
 // K*, and how many entries carry exactly K*.  Returns false if everything fits.
+//
+// Digits are taken from key - min(key), starting at the top bit of max - min, so that the first
+// digit already spreads the entries over the histogram instead of piling them onto a few LDS
+// addresses.  One barrier per digit of up to 8 bits: the histogram (entry count and token count
+// packed in one 64-bit LDS atomic) is scanned by every wave for itself, which leaves the chosen
+// digit wave-uniform in registers.  Three histogram buffers rotate: pass p fills buffer p%3 and
+// clears buffer (p+1)%3, whose last readers (pass p-2) all finished before the barrier of pass p-1.
+template <bool kLds>
 __device__ __forceinline__ bool radix_select(const uint64_t* keys, const uint32_t* wts, int n, long long budget,
                                              Scratch& s, uint64_t& kstar, uint64_t& acc_out, uint32_t& ties_out)
 {
-    const int tid = threadIdx.x;
-    uint64_t prefix = 0;
-    uint64_t acc = 0;
-    for (int pass = 0; pass < 8; ++pass) {
-        const int shift = 56 - 8 * pass;
-        if (tid < 256) {
-            s.hist_w[tid] = 0;
-            s.hist_c[tid] = 0;
-        }
-        __syncthreads();
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr unsigned long long kWtMask = (1ull << 40) - 1;
+    // token totals fit 31 bits
+    const uint32_t bud = budget < 0 ? 0u : (budget > 0xffffffffll ? 0xffffffffu : (uint32_t)budget);
+    {
+        uint64_t kmin = ~0ull, kmax = 0;
+        uint32_t wt = 0, cn = 0;
         for (int i = tid; i < n; i += kThreads) {
             const uint32_t w = wts[i];
             if (w == 0) continue;
             const uint64_t k = keys[i];
-            if (pass == 0 || (k >> (shift + 8)) == prefix) {
-                const uint32_t d = (uint32_t)(k >> shift) & 255u;
-                atomicAdd(&s.hist_w[d], w);
-                atomicAdd(&s.hist_c[d], 1u);
-            }
+            kmin = k < kmin ? k : kmin;
+            kmax = k > kmax ? k : kmax;
+            wt += w;
+            ++cn;
         }
-        __syncthreads();
-        if (tid < 64) {
-            const uint4 w4 = *reinterpret_cast<const uint4*>(&s.hist_w[4 * tid]);
-            const uint32_t sum = w4.x + w4.y + w4.z + w4.w;
-            const uint32_t incl = wave_incl_scan_u32(sum);
-            const bool cross = (long long)(acc + incl) > budget;
-            const unsigned long long mask = __ballot(cross);
-            if (mask == 0ull) {
-                if (tid == 0) s.sel_found = 0;
-            } else {
-                const int first = __ffsll((long long)mask) - 1;
-                if (tid == first) {
-                    uint64_t a = acc + incl - sum;
-                    uint32_t d = 4 * tid;
-                    const uint32_t ws[4] = {w4.x, w4.y, w4.z, w4.w};
-                    for (int j = 0; j < 4; ++j) {
-                        if ((long long)(a + ws[j]) > budget) { d = 4 * tid + j; break; }
-                        a += ws[j];
-                    }
-                    s.sel_found = 1;
-                    s.sel_digit = d;
-                    s.sel_acc = a;
-                    s.sel_cnt = s.hist_c[d];
+        kmin = wave_reduce(kmin, [](uint64_t a, uint64_t b) { return a < b ? a : b; });
+        kmax = wave_reduce(kmax, [](uint64_t a, uint64_t b) { return a > b ? a : b; });
+        wt = wave_reduce(wt, [](uint32_t a, uint32_t b) { return a + b; });
+        cn = wave_reduce(cn, [](uint32_t a, uint32_t b) { return a + b; });
+        if (lane == 0) {
+            s.rk_min[wave] = kmin;
+            s.rk_max[wave] = kmax;
+            s.rk_wt[wave] = wt;
+            s.rk_cn[wave] = cn;
+        }
+    }
+    if (tid < 256) s.hist[0][tid] = 0;
+    phase_sync<kLds>();
+    uint64_t kmin = ~0ull, kmax = 0;
+    uint32_t total = 0, cnt = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint64_t a = s.rk_min[w], b = s.rk_max[w];
+        kmin = a < kmin ? a : kmin;
+        kmax = b > kmax ? b : kmax;
+        total += s.rk_wt[w];
+        cnt += s.rk_cn[w];
+    }
+    if (total <= bud) return false;           // everything fits
+    const uint64_t range = kmax - kmin;
+    int hi = range ? 64 - __clzll((long long)range) : 0;   // number of low bits of key - kmin still undecided
+    uint64_t prefix = 0;                                   // the decided bits of K* - kmin
+    uint32_t acc = 0;
+    for (int pass = 0; hi > 0; ++pass) {
+        const int bits = hi < 8 ? hi : 8, shift = hi - bits;
+        const uint32_t dmask = (1u << bits) - 1u;
+        unsigned long long* H = s.hist[pass % 3];
+        if (tid < 256) s.hist[(pass + 1) % 3][tid] = 0;
+        for (int i = tid; i < n; i += kThreads) {
+            const uint32_t w = wts[i];
+            if (w == 0) continue;
+            const uint64_t k = keys[i] - kmin;
+            if (hi >= 64 || (k >> hi) == prefix) atomicAdd(&H[(uint32_t)(k >> shift) & dmask], (1ull << 40) | w);
+        }
+        phase_sync<kLds>();
+        unsigned long long h4[4];
+        uint32_t sum = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            h4[j] = H[4 * lane + j];
+            sum += (uint32_t)(h4[j] & kWtMask);
+        }
+        const uint32_t incl = wave_incl_scan_u32(sum);
+        // the bucket being split weighs more than what is left of the budget, so some lane crosses
+        const unsigned long long mask = __ballot((unsigned long long)acc + incl > bud);
+        const int first = mask ? __ffsll((long long)mask) - 1 : 63;
+        uint32_t a = acc + incl - sum, d = 4 * lane, c = 0;
+        bool done = false;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t wj = (uint32_t)(h4[j] & kWtMask);
+            if (!done) {
+                if ((unsigned long long)a + wj > bud) {
+                    d = 4 * lane + j;
+                    c = (uint32_t)(h4[j] >> 40);
+                    done = true;
+                } else {
+                    a += wj;
                 }
             }
         }
-        __syncthreads();
-        if (!s.sel_found) return false;       // only possible in pass 0: everything fits
-        acc = s.sel_acc;
-        prefix = (prefix << 8) | s.sel_digit;
-        const uint32_t cnt = s.sel_cnt;
-        __syncthreads();
-        if (cnt == 1 && pass < 7) {
+        acc = (uint32_t)__builtin_amdgcn_readlane((int)a, first);
+        cnt = (uint32_t)__builtin_amdgcn_readlane((int)c, first);
+        prefix = (prefix << bits) | (uint32_t)__builtin_amdgcn_readlane((int)d, first);
+        hi = shift;
+        if (cnt == 1 && hi > 0) {
             // a single entry carries the boundary: its full key is K*
             for (int i = tid; i < n; i += kThreads) {
                 if (wts[i] == 0) continue;
                 const uint64_t k = keys[i];
-                if ((k >> shift) == prefix) s.sel_key = k;
+                if (((k - kmin) >> hi) == prefix) s.sel_key = k;
             }
-            __syncthreads();
+            phase_sync<kLds>();
             kstar = s.sel_key;
             acc_out = acc;
             ties_out = 1;
-            __syncthreads();
             return true;
         }
     }
-    kstar = prefix;
+    kstar = kmin + prefix;
     acc_out = acc;
-    ties_out = s.sel_cnt;
+    ties_out = cnt;
     return true;
 }
 
-__device__ __forceinline__ double sum16_f64(double v)
+template <int kLanes>
+__device__ __forceinline__ double group_sum_f64(double v)
 {
     v += dpp_f64<kDppXor1>(v);
     v += dpp_f64<kDppXor2>(v);
     v += dpp_f64<kDppHalfMirror>(v);
-    v += dpp_f64<kDppMirror>(v);
+    if constexpr (kLanes == 16) v += dpp_f64<kDppMirror>(v);
     return v;
 }
 
 // One level: logits, Eq. 1 normaliser, rank keys, budgeted selection.  On return A.flags holds the
-// selected / promising mask, A.wts the member counts (0 = takes no part), A.lg the logits.
-// Entry i stands for cluster id (use_ids ? A.ids[i] : i).
-template <int G>
+// selected / promising mask, A.wts the member counts (0 = takes no part), A.lg the logits, A.keys
+// the rank keys.  Entry i stands for cluster id (use_ids ? A.ids[i] : i).
+template <int G, bool kLds, int LPE>
 __device__ __forceinline__ void score_level(const ScoreParams& p, const Arrays& A, Scratch& S, int u, int n,
-                                            bool use_ids, bool coarse, const double (&qreg)[G][8], long long budget,
-                                            bool with_extra, double* r_out, uint8_t* flag_out)
+                                            bool use_ids, bool coarse, const double (&qreg)[G][128 / LPE],
+                                            long long budget, bool with_extra)
 {
+    constexpr int DPL = 128 / LPE;           // dims per lane: 16 or 8
+    constexpr int EPI = kThreads / LPE;      // entries per pass of the workgroup
     const int tid = threadIdx.x;
     const int row_off = coarse ? p.fcap : 0;
     const int32_t* Nu = p.N + (long long)u * p.tab_rows + row_off;
@@ -238,36 +363,52 @@ __device__ __forceinline__ void score_level(const ScoreParams& p, const Arrays& 
             if (coarse) pre_b[k] = st[id + 1];
         }
     }
-    // ---- logits: 16 lanes per entry, 8 dims per lane, 4 entries in flight per lane ----
+    // ---- logits: LPE lanes per entry, DPL dims per lane; two entries per lane and pass, the rows of
+    // the next pass are requested before the current ones are used ----
     {
-        const int sub = tid & 15, grp = tid >> 4;
-        for (int i0 = 0; i0 < n; i0 += 4 * (kThreads / 16)) {
-            uint4 kv[4];
+        const int sub = tid % LPE, grp = tid / LPE;
+        uint4 nxt[2][DPL / 8];
+        auto request = [&](int i0) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i = i0 + j * (kThreads / 16) + grp;
-                kv[j] = make_uint4(0, 0, 0, 0);
+            for (int j = 0; j < 2; ++j) {
+                const int i = i0 + j * EPI + grp;
+#pragma unroll
+                for (int v = 0; v < DPL / 8; ++v) nxt[j][v] = make_uint4(0, 0, 0, 0);
                 if (i < n) {
                     const int id = use_ids ? A.ids[i] : i;
-                    kv[j] = reinterpret_cast<const uint4*>(Kcu + (long long)id * kHeadDim)[sub];
+                    const uint4* kp = reinterpret_cast<const uint4*>(Kcu + (long long)id * kHeadDim + DPL * sub);
+#pragma unroll
+                    for (int v = 0; v < DPL / 8; ++v) nxt[j][v] = kp[v];
                 }
             }
+        };
+        request(0);
+        for (int i0 = 0; i0 < n; i0 += 2 * EPI) {
+            uint4 kv[2][DPL / 8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i = i0 + j * (kThreads / 16) + grp;
-                const uint32_t w[4] = {kv[j].x, kv[j].y, kv[j].z, kv[j].w};
-                double kd[8];
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    kd[2 * e] = (double)bf16lo_to_f32(w[e]);
-                    kd[2 * e + 1] = (double)bf16hi_to_f32(w[e]);
+                for (int v = 0; v < DPL / 8; ++v) kv[j][v] = nxt[j][v];
+            if (i0 + 2 * EPI < n) request(i0 + 2 * EPI);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int i = i0 + j * EPI + grp;
+                double kd[DPL];
+#pragma unroll
+                for (int v = 0; v < DPL / 8; ++v) {
+                    const uint32_t w[4] = {kv[j][v].x, kv[j][v].y, kv[j][v].z, kv[j][v].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        kd[8 * v + 2 * e] = (double)bf16lo_to_f32(w[e]);
+                        kd[8 * v + 2 * e + 1] = (double)bf16hi_to_f32(w[e]);
+                    }
                 }
 #pragma unroll
                 for (int h = 0; h < G; ++h) {
                     double a = 0.0;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) a = fma(qreg[h][e], kd[e], a);
-                    a = sum16_f64(a);
+                    for (int e = 0; e < DPL; ++e) a = fma(qreg[h][e], kd[e], a);
+                    a = group_sum_f64<LPE>(a);
                     if (sub == 0 && i < n) A.lg[h * A.lg_stride + i] = a * p.scale;
                 }
             }
@@ -289,41 +430,15 @@ __device__ __forceinline__ void score_level(const ScoreParams& p, const Arrays& 
         A.aux[i] = st[id];
         if (coarse) A.aux2[i] = st[id + 1];
     }
-    __syncthreads();
+    phase_sync<kLds>();
 
     // ---- per-head normaliser of Eq. 1: LSE_h = log( sum_i N_i e^{l[h,i]} + e^{extra_h} ) ----
     double lse[G];
-    {
-        double mx[G];
-#pragma unroll
-        for (int h = 0; h < G; ++h) mx[h] = with_extra ? S.extra[h] : -INFINITY;
-        for (int i = tid; i < n; i += kThreads)
-            if (A.wts[i])
-#pragma unroll
-                for (int h = 0; h < G; ++h) mx[h] = fmax(mx[h], A.lg[h * A.lg_stride + i]);
-        block_max<G>(mx, S);
-        double sm[G];
-#pragma unroll
-        for (int h = 0; h < G; ++h) sm[h] = 0.0;
-        for (int i = tid; i < n; i += kThreads) {
-            const uint32_t w = A.wts[i];
-            if (w)
-#pragma unroll
-                for (int h = 0; h < G; ++h) sm[h] += (double)w * exp(A.lg[h * A.lg_stride + i] - mx[h]);
-        }
-        if (tid == 0 && with_extra)
-#pragma unroll
-            for (int h = 0; h < G; ++h)
-                if (S.extra[h] != -INFINITY) sm[h] += exp(S.extra[h] - mx[h]);
-        block_sum<G>(sm, S);
-#pragma unroll
-        for (int h = 0; h < G; ++h) lse[h] = (mx[h] == -INFINITY) ? -INFINITY : mx[h] + log(sm[h]);
-    }
+    weighted_lse<G, kLds>(A, S, n, with_extra, [&](int i) { return A.wts[i] != 0; }, lse);
 
     // ---- rank keys ----
     const double logG = log((double)G);
     for (int i = tid; i < n; i += kThreads) {
-        double r = __longlong_as_double(0x7ff8000000000000ll);
         uint64_t key = ~0ull;
         if (A.wts[i]) {
             double t[G], tm = -INFINITY;
@@ -332,21 +447,23 @@ __device__ __forceinline__ void score_level(const ScoreParams& p, const Arrays& 
                 t[h] = A.lg[h * A.lg_stride + i] - lse[h];
                 tm = fmax(tm, t[h]);
             }
-            double ssum = 0.0;
+            double r = tm - logG;
+            if constexpr (G > 1) {
+                double ssum = 0.0;
 #pragma unroll
-            for (int h = 0; h < G; ++h) ssum += exp(t[h] - tm);
-            r = tm + log(ssum) - logG;
+                for (int h = 0; h < G; ++h) ssum += exp(t[h] - tm);
+                r += log(ssum);
+            }
             key = descending_key(r);
         }
         A.keys[i] = key;
-        r_out[i] = r;
     }
-    __syncthreads();
+    // (the barrier that publishes the keys is the first one inside radix_select)
 
     // ---- budgeted selection ----
     uint64_t kstar = 0, acc = 0;
     uint32_t ties = 0;
-    const bool bounded = radix_select(A.keys, A.wts, n, budget, S, kstar, acc, ties);
+    const bool bounded = radix_select<kLds>(A.keys, A.wts, n, budget, S, kstar, acc, ties);
     for (int i = tid; i < n; i += kThreads) {
         uint8_t f = 0;
         if (A.wts[i]) {
@@ -364,176 +481,211 @@ __device__ __forceinline__ void score_level(const ScoreParams& p, const Arrays& 
             }
         }
         A.flags[i] = f;
-        flag_out[i] = f;
     }
-    __syncthreads();
+    phase_sync<kLds>();
 }
 
-// Centroid-term entries for every entry that takes part but was not kept at this level.
+// Per-position views for the getters: rank key (NaN where the entry took no part) and flag.
+__device__ __forceinline__ void write_views(const Arrays& A, int n, double* r_out, uint8_t* flag_out)
+{
+    for (int i = threadIdx.x; i < n; i += kThreads) {
+        r_out[i] = A.wts[i] ? key_to_rank(A.keys[i]) : __longlong_as_double(0x7ff8000000000000ll);
+        flag_out[i] = A.flags[i];
+    }
+}
+
+// One centroid-term entry (Eq. 2): the row of the value centroid and log2( N_i e^{l[h,i]} ) per head.
 template <int G>
-__device__ __forceinline__ uint32_t emit_terms(const ScoreParams& p, const Arrays& A, Scratch& S, int u, int n,
-                                               bool use_ids, int row_off, uint32_t base)
+__device__ __forceinline__ void emit_term(const ScoreParams& p, const Arrays& A, int u, int i, int row, uint32_t slot)
+{
+    const double kLog2e = 1.4426950408889634;
+    const long long o = (long long)u * p.mp_stride + slot;
+    p.mp_rows[o] = row;
+    const double lnN = log((double)A.wts[i]);
+#pragma unroll
+    for (int h = 0; h < G; ++h) p.mp_scores[o * G + h] = (float)((A.lg[h * A.lg_stride + i] + lnN) * kLog2e);
+}
+
+template <int G, bool kLds>
+__device__ __forceinline__ Arrays make_arrays(unsigned char* lds, const ScoreParams& p, int u)
+{
+    Arrays A;
+    if constexpr (kLds) {
+        A.lg = reinterpret_cast<double*>(lds);
+        A.lg_stride = p.lds_cap;
+        A.keys = reinterpret_cast<uint64_t*>(A.lg + (size_t)G * p.lds_cap);
+        A.wts = reinterpret_cast<uint32_t*>(A.keys + p.lds_cap);
+        A.ids = reinterpret_cast<int32_t*>(A.wts + p.lds_cap);
+        A.aux = A.ids + p.lds_cap;
+        A.aux2 = A.aux + p.lds_cap;
+        A.flags = reinterpret_cast<uint8_t*>(A.aux2 + p.lds_cap);
+    } else {
+        A.lg = p.lg + (long long)u * G * p.lg_stride;
+        A.lg_stride = p.lg_stride;
+        A.keys = reinterpret_cast<uint64_t*>(p.g_keys) + (long long)u * p.g_stride;
+        A.wts = p.g_wts + (long long)u * p.g_stride;
+        A.ids = p.cand + (long long)u * p.f_stride;       // the candidate list itself
+        A.aux = p.g_aux + (long long)u * p.g_stride;
+        A.aux2 = p.g_aux2 + (long long)u * p.g_stride;
+        A.flags = p.g_flags + (long long)u * p.g_stride;
+    }
+    return A;
+}
+
+// Coarse level (Sec. 3.4): score all coarse clusters, keep the promising ones, emit centroid terms
+// for the others, leave the log-sum of their N e^l in S.extra and the candidate list (children of
+// the promising clusters, ascending fine id) in global memory and, as far as it fits, in the LDS
+// slot the fine level reads its ids from (unused by the coarse level, whose entries are 0..n-1).
+template <int G, bool kLds, int LPE>
+__device__ __forceinline__ void coarse_phase(const ScoreParams& p, unsigned char* lds, Scratch& S, ScanState& sc,
+                                             int u, const double (&qreg)[G][128 / LPE], int& n_cand,
+                                             uint32_t& n_terms)
 {
     const int tid = threadIdx.x;
-    const double kLog2e = 1.4426950408889634;
-    if (tid == 0) S.carry = 0;
-    __syncthreads();
-    for (int i0 = 0; i0 < n; i0 += kThreads) {
-        const int i = i0 + tid;
-        const bool emit = (i < n) && A.wts[i] && !A.flags[i];
-        const uint32_t pos = chunk_excl_scan(emit ? 1u : 0u, S);
-        if (emit) {
-            const int id = use_ids ? A.ids[i] : i;
-            const long long o = (long long)u * p.mp_stride + base + pos;
-            p.mp_rows[o] = row_off + id;
-            const double lnN = log((double)A.wts[i]);
+    const int n_c = p.n_coarse;
+    const Arrays C = make_arrays<G, kLds>(lds, p, u);
+    score_level<G, kLds, LPE>(p, C, S, u, n_c, false, true, qreg, p.coarse_budget, false);
+    double ex[G];
+    weighted_lse<G, kLds>(C, S, n_c, false, [&](int i) { return C.wts[i] != 0 && !C.flags[i]; }, ex);
 #pragma unroll
-            for (int h = 0; h < G; ++h) p.mp_scores[o * G + h] = (float)((A.lg[h * A.lg_stride + i] + lnN) * kLog2e);
+    for (int h = 0; h < G; ++h)
+        if (tid == h) S.extra[h] = ex[h];
+    int32_t* cand_g = p.cand + (long long)u * p.f_stride;
+    int32_t* cand_l = make_arrays<G, true>(lds, p, u).ids;
+    sc.carry_a = sc.carry_b = 0;
+    for (int i0 = 0; i0 < n_c; i0 += kThreads) {
+        const int i = i0 + tid;
+        const bool part = i < n_c && C.wts[i] != 0;
+        const bool keep = part && C.flags[i];
+        const bool emit = part && !keep && p.use_mp;
+        int c0 = 0, c1 = 0;
+        if (keep) { c0 = C.aux[i]; c1 = C.aux2[i]; }
+        uint32_t pos, slot;
+        chunk_excl_scan2<kLds>((uint32_t)(c1 - c0), emit ? 1u : 0u, S, sc, pos, slot);
+        for (int f = c0; f < c1; ++f) {
+            const uint32_t o = pos + (uint32_t)(f - c0);
+            cand_g[o] = f;
+            if (o < (uint32_t)p.lds_cap) cand_l[o] = f;
         }
+        if (emit) emit_term<G>(p, C, u, i, p.fcap + i, slot);
     }
-    const uint32_t cnt = S.carry;
+    n_cand = (int)sc.carry_a;
+    n_terms = sc.carry_b;
+    write_views(C, n_c, p.r_c + (long long)u * p.c_stride, p.flag_c + (long long)u * p.c_stride);
+    if (tid == 0) {
+        p.n_cand[u] = n_cand;
+        p.counters[4 * u + 2] = n_c;
+    }
+    // the fine level reuses the coarse level's working arrays; with more candidates than fit in LDS
+    // it also reads the candidate list back from global memory
     __syncthreads();
-    return cnt;
 }
 
-template <int G>
-__global__ __launch_bounds__(kThreads) void score_select_kernel(const ScoreParams p)
+// Fine level: score the candidates, select within the key budget, emit centroid terms for the
+// unselected candidates and the flat list of stored rows of the selected clusters.
+template <int G, bool kLds, int LPE>
+__device__ __forceinline__ void fine_phase(const ScoreParams& p, unsigned char* lds, Scratch& S, ScanState& sc,
+                                           int u, const double (&qreg)[G][128 / LPE], int n_f, bool two,
+                                           uint32_t n_terms)
 {
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    Scratch& S = *reinterpret_cast<Scratch*>(smem_raw);
-    // LDS working arrays for a level with at most lds_cap entries
-    unsigned char* base = smem_raw + ((sizeof(Scratch) + 15) & ~size_t(15));
-    Arrays L;
-    L.lg = reinterpret_cast<double*>(base);
-    L.lg_stride = p.lds_cap;
-    L.keys = reinterpret_cast<uint64_t*>(L.lg + (size_t)G * p.lds_cap);
-    L.wts = reinterpret_cast<uint32_t*>(L.keys + p.lds_cap);
-    L.ids = reinterpret_cast<int32_t*>(L.wts + p.lds_cap);
-    L.aux = L.ids + p.lds_cap;
-    L.aux2 = L.aux + p.lds_cap;
-    L.flags = reinterpret_cast<uint8_t*>(L.aux2 + p.lds_cap);
-    const int u = blockIdx.x, tid = threadIdx.x;
-    // the same arrays in global scratch, for levels that do not fit
-    Arrays Gm;
-    Gm.lg = p.lg + (long long)u * G * p.lg_stride;
-    Gm.lg_stride = p.lg_stride;
-    Gm.keys = reinterpret_cast<uint64_t*>(p.g_keys) + (long long)u * p.g_stride;
-    Gm.wts = p.g_wts + (long long)u * p.g_stride;
-    Gm.ids = p.g_ids + (long long)u * p.g_stride;
-    Gm.aux = p.g_aux + (long long)u * p.g_stride;
-    Gm.aux2 = p.g_aux2 + (long long)u * p.g_stride;
-    Gm.flags = p.g_flags + (long long)u * p.g_stride;
+    const int tid = threadIdx.x;
+    const Arrays F = make_arrays<G, kLds>(lds, p, u);
+    score_level<G, kLds, LPE>(p, F, S, u, n_f, two, false, qreg, p.key_budget, two);
+    write_views(F, n_f, p.r_f + (long long)u * p.f_stride, p.flag_f + (long long)u * p.f_stride);
 
-    // query slice of this lane: dims [8*sub, 8*sub+8) of every head, as doubles
-    double qreg[G][8];
-    {
-        const int sub = tid & 15;
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            const uint4 qv = reinterpret_cast<const uint4*>(p.q + ((long long)u * G + h) * kHeadDim)[sub];
-            const uint32_t w[4] = {qv.x, qv.y, qv.z, qv.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                qreg[h][2 * e] = (double)bf16lo_to_f32(w[e]);
-                qreg[h][2 * e + 1] = (double)bf16hi_to_f32(w[e]);
-            }
-        }
-    }
-    if (tid == 0) S.carry = 0;
-    __syncthreads();
-
-    const bool two = p.levels == 2;
-    uint32_t n_terms = 0;
-    int n_f = p.n_fine;
-    bool fine_ids = false;
-    Arrays F = (p.n_fine <= p.lds_cap) ? L : Gm;
-    if (two) {
-        const int n_c = p.n_coarse;
-        const Arrays C = (n_c <= p.lds_cap) ? L : Gm;
-        score_level<G>(p, C, S, u, n_c, false, true, qreg, p.coarse_budget, false, p.r_c + (long long)u * p.c_stride,
-                       p.flag_c + (long long)u * p.c_stride);
-        // log-sum of the unpromising clusters' N e^{l}: joins the fine level's Eq. 1 denominator
-        {
-            double mx[G], sm[G];
-#pragma unroll
-            for (int h = 0; h < G; ++h) { mx[h] = -INFINITY; sm[h] = 0.0; }
-            for (int i = tid; i < n_c; i += kThreads)
-                if (C.wts[i] && !C.flags[i])
-#pragma unroll
-                    for (int h = 0; h < G; ++h) mx[h] = fmax(mx[h], C.lg[h * C.lg_stride + i]);
-            block_max<G>(mx, S);
-            for (int i = tid; i < n_c; i += kThreads)
-                if (C.wts[i] && !C.flags[i])
-#pragma unroll
-                    for (int h = 0; h < G; ++h) sm[h] += (double)C.wts[i] * exp(C.lg[h * C.lg_stride + i] - mx[h]);
-            block_sum<G>(sm, S);
-            if (tid < G) {
-                double v = -INFINITY;
-#pragma unroll
-                for (int h = 0; h < G; ++h)
-                    if (h == tid) v = (mx[h] == -INFINITY) ? -INFINITY : mx[h] + log(sm[h]);
-                S.extra[tid] = v;
-            }
-        }
-        if (p.use_mp) n_terms = emit_terms<G>(p, C, S, u, n_c, false, p.fcap, 0);
-        // candidates: the children of the promising clusters, ascending fine id, written to the global
-        // candidate list first (the coarse arrays may share LDS with the fine ones and are still read).
-        if (tid == 0) S.carry = 0;
-        __syncthreads();
-        int32_t* cand_g = p.cand + (long long)u * p.f_stride;
-        for (int i0 = 0; i0 < n_c; i0 += kThreads) {
-            const int i = i0 + tid;
-            int c0 = 0, c1 = 0;
-            if (i < n_c && C.flags[i]) { c0 = C.aux[i]; c1 = C.aux2[i]; }
-            const uint32_t pos = chunk_excl_scan((uint32_t)(c1 - c0), S);
-            for (int f = c0; f < c1; ++f) cand_g[pos + (f - c0)] = f;
-        }
-        n_f = (int)S.carry;
-        __syncthreads();               // every read of the coarse arrays is done, the candidate list is written
-        F = (n_f <= p.lds_cap) ? L : Gm;
-        for (int i = tid; i < n_f; i += kThreads) F.ids[i] = cand_g[i];
-        fine_ids = true;
-        if (tid == 0) {
-            p.n_cand[u] = n_f;
-            p.counters[4 * u + 2] = n_c;
-        }
-        __syncthreads();
-    } else if (tid == 0) {
-        p.counters[4 * u + 2] = 0;
-    }
-
-    score_level<G>(p, F, S, u, n_f, fine_ids, false, qreg, p.key_budget, two, p.r_f + (long long)u * p.f_stride,
-                   p.flag_f + (long long)u * p.f_stride);
-    if (p.use_mp) n_terms += emit_terms<G>(p, F, S, u, n_f, fine_ids, 0, n_terms);
-
-    // flat list of stored rows of the selected clusters, ascending fine id
-    if (tid == 0) S.carry = 0;
-    __syncthreads();
-    uint32_t* offs = reinterpret_cast<uint32_t*>(F.keys);   // keys are no longer needed
+    // One scan gives every selected cluster (ascending fine id) its slot in a compact list and the
+    // offset of its rows in the flat row list, and every unselected candidate its centroid-term slot.
+    // The compact list reuses the storage of the keys, which nobody reads after the views above.
+    int2* sel_rc = reinterpret_cast<int2*>(F.keys);      // (first stored row, count)
+    int32_t* sel_off = F.aux2;
+    sc.carry_a = sc.carry_b = 0;
     for (int i0 = 0; i0 < n_f; i0 += kThreads) {
         const int i = i0 + tid;
-        const uint32_t w = (i < n_f && F.flags[i]) ? F.wts[i] : 0u;
-        const uint32_t pos = chunk_excl_scan(w, S);
-        if (i < n_f) offs[i] = pos;
+        const bool part = i < n_f && F.wts[i] != 0;
+        const bool sel = part && F.flags[i];
+        const bool emit = part && !sel && p.use_mp;
+        const uint32_t w = sel ? F.wts[i] : 0u;
+        const int r0 = sel ? F.aux[i] : 0;
+        uint32_t off, packed;       // packed: selected clusters in the low half, terms in the high half
+        chunk_excl_scan2<kLds>(w, (sel ? 1u : 0u) | (emit ? 0x10000u : 0u), S, sc, off, packed);
+        if (sel) {
+            sel_rc[packed & 0xffffu] = make_int2(r0, (int)w);
+            sel_off[packed & 0xffffu] = (int32_t)off;
+        }
+        if (emit) emit_term<G>(p, F, u, i, two ? F.ids[i] : i, n_terms + (packed >> 16));
     }
-    const uint32_t total = S.carry;
-    __syncthreads();
+    const uint32_t total = sc.carry_a, n_sel = sc.carry_b & 0xffffu;
+    n_terms += sc.carry_b >> 16;
+    phase_sync<kLds>();
+    // expansion: one row of 16 lanes per selected cluster, the next cluster's entry fetched early
     int32_t* ro = p.rows + (long long)u * p.rows_stride;
-    const int wave = tid >> 6, lane = tid & 63;
-    for (int i = wave; i < n_f; i += kWaves) {
-        if (!F.flags[i]) continue;
-        const int r0 = F.aux[i];
-        const int cnt = (int)F.wts[i];
-        const uint32_t o = offs[i];
-        for (int j = lane; j < cnt; j += 64) ro[o + j] = r0 + j;
+    const int grp = tid >> 4, sub = tid & 15;
+    int2 rc_n = make_int2(0, 0);
+    int off_n = 0;
+    if ((uint32_t)grp < n_sel) {
+        rc_n = sel_rc[grp];
+        off_n = sel_off[grp];
+    }
+    for (uint32_t k = grp; k < n_sel; k += kThreads / 16) {
+        const int2 rc = rc_n;
+        const int off = off_n;
+        const uint32_t kn = k + kThreads / 16;
+        if (kn < n_sel) {
+            rc_n = sel_rc[kn];
+            off_n = sel_off[kn];
+        }
+        for (int j = sub; j < rc.y; j += 16) ro[off + j] = rc.x + j;
     }
     if (tid == 0) {
         p.n_rows[u] = (int32_t)total;
         p.n_mp[u] = (int32_t)n_terms;
         p.counters[4 * u + 0] = (int32_t)total + p.n_tail;
         p.counters[4 * u + 1] = n_f;
+        if (!two) p.counters[4 * u + 2] = 0;
         p.counters[4 * u + 3] = (int32_t)n_terms;
     }
+}
+
+template <int G>
+__global__ __launch_bounds__(kThreads) void score_select_kernel(const ScoreParams p)
+{
+    constexpr int LPE = (G <= 4) ? 8 : 16;   // lanes per entry in the logits phase
+    constexpr int DPL = 128 / LPE;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    Scratch& S = *reinterpret_cast<Scratch*>(smem_raw);
+    unsigned char* lds = smem_raw + ((sizeof(Scratch) + 15) & ~size_t(15));
+    const int u = blockIdx.x, tid = threadIdx.x;
+
+    // query slice of this lane: dims [DPL*sub, DPL*sub + DPL) of every head, as doubles
+    double qreg[G][DPL];
+    {
+        const int sub = tid % LPE;
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            const uint4* qp = reinterpret_cast<const uint4*>(p.q + ((long long)u * G + h) * kHeadDim + DPL * sub);
+#pragma unroll
+            for (int v = 0; v < DPL / 8; ++v) {
+                const uint4 qv = qp[v];
+                const uint32_t w[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    qreg[h][8 * v + 2 * e] = (double)bf16lo_to_f32(w[e]);
+                    qreg[h][8 * v + 2 * e + 1] = (double)bf16hi_to_f32(w[e]);
+                }
+            }
+        }
+    }
+
+    const bool two = p.levels == 2;
+    ScanState sc;
+    uint32_t n_terms = 0;
+    int n_f = p.n_fine;
+    if (two) {
+        if (p.n_coarse <= p.lds_cap) coarse_phase<G, true, LPE>(p, lds, S, sc, u, qreg, n_f, n_terms);
+        else coarse_phase<G, false, LPE>(p, lds, S, sc, u, qreg, n_f, n_terms);
+    }
+    if (n_f <= p.lds_cap) fine_phase<G, true, LPE>(p, lds, S, sc, u, qreg, n_f, two, n_terms);
+    else fine_phase<G, false, LPE>(p, lds, S, sc, u, qreg, n_f, two, n_terms);
 }
 
 }  // namespace
