@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmp.so")
-SOURCES = ["mp_api.hip", "mp_value.hip", "mp_score.hip", "mp_index.hip", "mp_cluster.hip"]
+SOURCES = ["mp_api.hip", "mp_value.hip", "mp_score.hip", "mp_index.hip", "mp_assign.hip", "mp_cluster.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

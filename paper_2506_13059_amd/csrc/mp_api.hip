@@ -161,6 +161,7 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     A(km_assign, U * N); A(km_list, U * N); A(km_cnt, U * T); A(km_start, U * (T + 2));
     A(km_Cf, U * F * D); A(km_Cc, U * Cc * D); A(km_parent, U * F); A(km_plist, U * F); A(km_newid, U * F);
     A(km_seed_f, U * F); A(km_seed_c, U * Cc); A(blocks_dev, 3 * (size_t)ctx->max_blocks * 4);
+    A(km_amb, U * (size_t)ctx->max_blocks);
     ctx->Lcap = (int32_t)std::max(F, Cc);
     const size_t Lc = ctx->Lcap;
     A(lg, U * G * Lc); A(sc_keys, U * Lc); A(sc_wts, U * Lc); A(sc_ids, U * Lc); A(sc_aux, U * Lc); A(sc_aux2, U * Lc);

@@ -37,63 +37,6 @@ __global__ __launch_bounds__(256) void init_centroids_kernel(const uint16_t* __r
     }
 }
 
-// Exact nearest-centroid assignment.  One thread per point, 256 points per workgroup; the block's
-// centroids pass through LDS as doubles, 32 at a time.  grid = (ceil(max points per block/256), nb, U)
-constexpr int kAssignTile = 32;
-__global__ __launch_bounds__(256) void assign_exact_kernel(const uint16_t* __restrict__ X, long long x_unit_rows,
-                                                           const int32_t* __restrict__ blocks,
-                                                           const uint16_t* __restrict__ C, long long c_unit_rows,
-                                                           int32_t* __restrict__ assign, long long assign_stride)
-{
-    __shared__ double ct[kAssignTile * kHeadDim];
-    const int u = blockIdx.z, b = blockIdx.y;
-    const int x0 = blocks[4 * b + 0], x1 = blocks[4 * b + 1], k0 = blocks[4 * b + 2], k1 = blocks[4 * b + 3];
-    const int t = x0 + blockIdx.x * 256 + threadIdx.x;
-    if (x0 + (int)blockIdx.x * 256 >= x1) return;
-    const bool live = t < x1;
-    float x[kHeadDim];
-    {
-        const uint4* xp = reinterpret_cast<const uint4*>(X + ((long long)u * x_unit_rows + (live ? t : x0)) * kHeadDim);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const uint4 w = xp[i];
-            x[8 * i + 0] = bf16lo_to_f32(w.x); x[8 * i + 1] = bf16hi_to_f32(w.x);
-            x[8 * i + 2] = bf16lo_to_f32(w.y); x[8 * i + 3] = bf16hi_to_f32(w.y);
-            x[8 * i + 4] = bf16lo_to_f32(w.z); x[8 * i + 5] = bf16hi_to_f32(w.z);
-            x[8 * i + 6] = bf16lo_to_f32(w.w); x[8 * i + 7] = bf16hi_to_f32(w.w);
-        }
-    }
-    double best = INFINITY;
-    int bj = k0;
-    for (int j0 = k0; j0 < k1; j0 += kAssignTile) {
-        const int nj = (k1 - j0 < kAssignTile) ? k1 - j0 : kAssignTile;
-        __syncthreads();
-        for (int e = threadIdx.x; e < nj * (kHeadDim / 2); e += 256) {
-            const int j = e >> 6, w = e & 63;
-            const uint32_t cw = reinterpret_cast<const uint32_t*>(C + ((long long)u * c_unit_rows + j0 + j) * kHeadDim)[w];
-            ct[j * kHeadDim + 2 * w] = (double)bf16lo_to_f32(cw);
-            ct[j * kHeadDim + 2 * w + 1] = (double)bf16hi_to_f32(cw);
-        }
-        __syncthreads();
-        for (int j = 0; j < nj; ++j) {
-            double s = 0.0;
-#pragma unroll
-            for (int i = 0; i < kHeadDim; i += 2) {
-                const double2 c2 = *reinterpret_cast<const double2*>(&ct[j * kHeadDim + i]);
-                const double d0 = __dsub_rn((double)x[i], c2.x);
-                const double d1 = __dsub_rn((double)x[i + 1], c2.y);
-                s = __dadd_rn(s, __dmul_rn(d0, d0));
-                s = __dadd_rn(s, __dmul_rn(d1, d1));
-            }
-            if (s < best) {
-                best = s;
-                bj = j0 + j;
-            }
-        }
-    }
-    if (live) assign[u * assign_stride + t] = bj;
-}
-
 // inv[u][perm[u][p0 + p]] = v0 + p for p in [0, n)
 __global__ void invert_perm_kernel(const int32_t* __restrict__ perm, long long perm_stride, int p0, int n, int v0,
                                    int32_t* __restrict__ inv, long long inv_stride)
@@ -189,9 +132,9 @@ struct Problem {
 
 mp_status launch_assign(mp_ctx* ctx, const Problem& pr, hipStream_t s)
 {
-    hipLaunchKernelGGL(assign_exact_kernel, dim3((pr.max_pts + 255) / 256, pr.nb, ctx->U), dim3(256), 0, s, pr.X,
-                       pr.x_unit_rows, pr.blocks_dev, pr.C, pr.c_unit_rows, pr.assign, pr.assign_stride);
-    MP_HIPC(hipGetLastError());
+    // the member-list array is free during the assignment step and holds the points of the exact pass
+    MP_HIPC(mp::launch_assign(pr.X, pr.x_unit_rows, pr.blocks_dev, pr.nb, pr.max_pts, ctx->U, pr.C, pr.c_unit_rows,
+                              pr.assign, pr.assign_stride, pr.list, pr.list_stride, ctx->km_amb, ctx->max_blocks, s));
     return MP_OK;
 }
 
@@ -609,9 +552,8 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* v_new
         MP_HIPC(hipGetLastError());
     }
     // ---- one-shot assignment of the appended tokens + running mean of the touched centroids ----
-    hipLaunchKernelGGL(assign_exact_kernel, dim3((n_new + 255) / 256, 1, U), dim3(256), 0, s, ctx->Kfb,
-                       (long long)ctx->FBcap, ctx->blocks_dev, ctx->km_Cf, Fcap, ctx->km_assign, Ncap);
-    MP_HIPC(hipGetLastError());
+    MP_HIPC(mp::launch_assign(ctx->Kfb, (long long)ctx->FBcap, ctx->blocks_dev, 1, n_new, U, ctx->km_Cf, Fcap,
+                              ctx->km_assign, Ncap, ctx->km_list, Ncap, ctx->km_amb, ctx->max_blocks, s));
     MP_HIPC(hipMemcpy2DAsync(ctx->km_assign, (size_t)Ncap * 4, ctx->fot + t0, (size_t)Ncap * 4, (size_t)nb_old * 4, U,
                              hipMemcpyDeviceToDevice, s));
     hipLaunchKernelGGL(running_mean_kernel, dim3((kf + 3) / 4, U), dim3(256), 0, s, ctx->Kfb, (long long)ctx->FBcap,
