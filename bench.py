@@ -51,6 +51,7 @@ def main():
     ap.add_argument("--workload", default="cfg3_128k_b16")
     ap.add_argument("--coarse-mult", type=int, default=2, help="coarse budget = mult * key budget")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-online", action="store_true", help="skip the online-generation (cfg4_online) extra")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
     args = ap.parse_args()
@@ -122,7 +123,9 @@ def main():
                 step_bytes += sb / min(n_t, n_sets)
                 vp_bytes += vb / min(n_t, n_sets)
         ctx.mp_enable_stage_timing(False)
-        results[kb] = dict(us=us, stage_us={k_[:-3]: v * 1e3 for k_, v in stage.items()}, step_bytes=step_bytes,
+        stage_us = {"score": (stage["coarse_ms"] + stage["fine_ms"]) * 1e3, "value": stage["value_ms"] * 1e3,
+                    "merge": stage["merge_ms"] * 1e3}
+        results[kb] = dict(us=us, stage_us=stage_us, step_bytes=step_bytes,
                            vp_bytes=vp_bytes, gbps=step_bytes / us / 1e3,
                            vp_gbps=vp_bytes / (stage["value_ms"] * 1e3) / 1e3 if stage["value_ms"] > 0 else 0.0)
 
@@ -178,6 +181,8 @@ def main():
                                     "speedup_vs_dense": round(dense_us / r["us"], 3)}
                           for kb, r in results.items() if kb != kb0},
         "cluster_build_ms": round(cluster_ms, 2),
+        "cluster_build_mtokens_per_s": round(w.units * w.context / cluster_ms / 1e3, 1),
+        "online_generation": None if args.no_online else online_generation(mp, inputs, dev),
         "input_generation_s": round(t_gen, 2),
         "paper_context": "paper reports up to 4.5x attention speedup vs FlashDecoding on an NVIDIA A6000 "
                          "(2.8x on A100), batch 16, 128K context",
@@ -188,6 +193,58 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
+
+
+def online_generation(mp, inputs, dev):
+    """cfg4_online: an 8K-token index grows by 16384 generated tokens.  Every token is one decode step
+    over the index plus the tail of tokens appended since the last refresh; every 128 tokens the
+    tail goes into the index with mp_update_clusters (Sec. 3.3).  Reports GPU time per token."""
+    import torch
+    w = inputs.WORKLOADS["cfg4_online"]
+    every, rounds = w.update_every, w.gen_tokens // w.update_every
+    n_max = w.context + w.gen_tokens
+    max_fine = w.n_fine + rounds * w.new_fine_per_update
+    max_coarse = w.n_coarse + rounds * w.new_coarse_per_update
+    seed = 1000 * list(inputs.WORKLOADS).index(w.name)
+    data = inputs.make_workload(w, dev, seed=seed, n_query_sets=16)
+    ctx = mp.MpContext(w.batch, w.n_q_heads, w.n_kv_heads, max_tokens=n_max, levels=w.levels, max_fine=max_fine,
+                       max_coarse=max_coarse, block_w=w.block_w, block_alpha=w.block_alpha, max_tail=every)
+    ctx.mp_cluster_kv(data["K"], data["V"], w.n_fine, w.n_coarse, iters=w.kmeans_iters, init_fine=data["init_fine"],
+                      init_coarse=data["init_coarse"])
+    Q, centers = data["q"], data["centers"]
+    out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.bfloat16, device=dev)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    dec_ms = upd_ms = 0.0
+    n = w.context
+    torch.cuda.synchronize()
+    t0 = time.time()
+    for r in range(rounds):
+        centers = inputs.drift_modes(centers, seed + 100 + r)
+        Kn, Vn = inputs.draw_tokens(centers, every, seed + 200 + r)
+        Kn, Vn = Kn.view(w.batch, w.n_kv_heads, every, 128), Vn.view(w.batch, w.n_kv_heads, every, 128)
+        kb = n // 8
+        ev[0].record()
+        for i in range(every):      # token i sees the i tokens generated since the last refresh as tail
+            ctx.mp_decode_attention(Q[i % 16], kb, 2 * kb, k_tail=Kn, v_tail=Vn, n_tail=i, out=out)
+        ev[1].record()
+        ctx.mp_update_clusters(Kn, Vn, w.new_fine_per_update, w.new_coarse_per_update, refine_iters=w.refine_iters,
+                               split_iters=w.kmeans_iters, seed=seed + 300 + r)
+        ev[2].record()
+        torch.cuda.synchronize()
+        dec_ms += ev[0].elapsed_time(ev[1])
+        upd_ms += ev[1].elapsed_time(ev[2])
+        n += every
+    wall = time.time() - t0
+    sizes = ctx.mp_get_sizes()
+    ctx.close()
+    return {"workload": w.name, "batch": w.batch, "tokens_generated": w.gen_tokens, "context": [w.context, n],
+            "refresh_every": every, "key_budget": "context/8", "final_sizes": sizes,
+            "decode_us_per_token": round(dec_ms * 1e3 / w.gen_tokens, 2),
+            "update_us_per_refresh": round(upd_ms * 1e3 / rounds, 1),
+            "update_us_per_token": round(upd_ms * 1e3 / w.gen_tokens, 2),
+            "total_us_per_token": round((dec_ms + upd_ms) * 1e3 / w.gen_tokens, 2),
+            "update_share": round(upd_ms / (dec_ms + upd_ms), 4),
+            "wall_us_per_token_incl_input_generation": round(wall * 1e6 / w.gen_tokens, 1)}
 
 
 def measured_traffic(workload, key_budget):

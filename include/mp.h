@@ -178,8 +178,11 @@ mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* v_new, 
  * mp_decode_attention -- one decode step for every unit (Eq. 1, Eq. 2, Sec. 3.4, Sec. 4).
  *
  *   q               device bf16 [B, Hq, 128]
- *   k_tail, v_tail  device bf16 [B, Hkv, n_tail, 128]: newest tokens that are not clustered yet
- *                   (the local buffer of Sec. 4); always attended exactly; NULL with n_tail == 0.
+ *   k_tail, v_tail  device bf16 [B, Hkv, tail_stride, 128], of which the first n_tail rows of every
+ *                   unit are used: newest tokens that are not clustered yet (the local buffer of
+ *                   Sec. 4); always attended exactly; NULL with n_tail == 0.
+ *   tail_stride     rows between consecutive units in k_tail / v_tail (>= n_tail), so that a buffer
+ *                   of fixed capacity can fill up in place; 0 means n_tail (densely packed).
  *   key_budget      keys of selected fine clusters per unit (>= 0; >= n_tokens => full attention;
  *                   0 => every cluster enters through its centroid).  Tail tokens do not count.
  *   coarse_budget   keys covered by the "promising" coarse clusters whose children are scored at
@@ -201,11 +204,12 @@ mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* v_new, 
  * fp32 accumulation.
  *
  * Allocates nothing, never waits for the GPU, reads nothing back.
- * Errors: MP_ESTATE (no index), MP_EINVAL (null, negative sizes), MP_ECAPACITY (n_tail > max_tail).
+ * Errors: MP_ESTATE (no index), MP_EINVAL (null, negative sizes, 0 < tail_stride < n_tail),
+ * MP_ECAPACITY (n_tail > max_tail).
  * ------------------------------------------------------------------------------------------- */
 #define MP_DECODE_NO_MULTIPOLE 1u
 mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, const void* v_tail,
-                              int32_t n_tail, int32_t key_budget, int32_t coarse_budget,
+                              int32_t n_tail, int32_t tail_stride, int32_t key_budget, int32_t coarse_budget,
                               uint32_t flags, void* out, float* lse, void* stream);
 
 /* ---------------------------------------------------------------------------------------------

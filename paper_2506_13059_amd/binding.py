@@ -62,7 +62,7 @@ def lib():
         L.mp_cluster_kv.argtypes = [vp, vp, vp, i32, i32, i32, i32, u64, vp, vp, vp]
         L.mp_set_clustering.argtypes = [vp, vp, vp, i32, vp, i32, vp, i32, vp]
         L.mp_update_clusters.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, u64, vp, vp]
-        L.mp_decode_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, u32, vp, vp, vp]
+        L.mp_decode_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, u32, vp, vp, vp]
         L.mp_update_seed_counts.argtypes = [vp, i32, i32, i32, vp]
         L.mp_update_seed_counts.restype = i32
         L.mp_enable_stage_timing.argtypes = [vp, i32]
@@ -191,11 +191,14 @@ class MpContext:
         return list(buf)
 
     def mp_decode_attention(self, q, key_budget, coarse_budget=0, k_tail=None, v_tail=None, out=None, lse=None,
-                            flags=0):
-        n_tail = 0 if k_tail is None else k_tail.shape[2]
+                            flags=0, n_tail=None):
+        """k_tail / v_tail [B, Hkv, rows, 128]; n_tail (default: all rows) = rows of every unit in use."""
+        tail_stride = 0 if k_tail is None else k_tail.shape[2]
+        if n_tail is None:
+            n_tail = tail_stride
         if out is None:
             out = torch.empty_like(q)
-        st = lib().mp_decode_attention(self.h, _ptr(q), _ptr(k_tail), _ptr(v_tail), n_tail, key_budget,
+        st = lib().mp_decode_attention(self.h, _ptr(q), _ptr(k_tail), _ptr(v_tail), n_tail, tail_stride, key_budget,
                                        coarse_budget, flags, _ptr(out), _ptr(lse), _stream())
         _check(st, self.h)
         return out

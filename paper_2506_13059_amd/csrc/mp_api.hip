@@ -279,6 +279,7 @@ mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* v_new, 
 }
 
 mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, const void* v_tail, int32_t n_tail,
+                              int32_t tail_stride,
                               int32_t key_budget, int32_t coarse_budget, uint32_t flags, void* out, float* lse, void* stream)
 {
     if (!ctx) return fail(nullptr, MP_EINVAL, "mp_decode_attention: null context");
@@ -286,6 +287,7 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
     if (!q || !out) return fail(ctx, MP_EINVAL, "mp_decode_attention: null q/out");
     if (n_tail < 0 || key_budget < 0 || coarse_budget < 0) return fail(ctx, MP_EINVAL, "mp_decode_attention: negative size or budget");
     if (n_tail > 0 && (!k_tail || !v_tail)) return fail(ctx, MP_EINVAL, "mp_decode_attention: null tail with n_tail > 0");
+    if (tail_stride != 0 && tail_stride < n_tail) return fail(ctx, MP_EINVAL, "mp_decode_attention: tail_stride %d < n_tail %d", tail_stride, n_tail);
     if (n_tail > ctx->Tcap) return fail(ctx, MP_ECAPACITY, "mp_decode_attention: n_tail %d > max_tail %d", n_tail, ctx->Tcap);
     if (flags & ~MP_DECODE_NO_MULTIPOLE) return fail(ctx, MP_EINVAL, "mp_decode_attention: unknown flags 0x%x", flags);
     hipStream_t s = (hipStream_t)stream;
@@ -330,7 +332,7 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
     }
     if (n_tail > 0) {
         RowSource& r = vp.src[ns++];
-        r.K = (const uint16_t*)k_tail; r.V = (const uint16_t*)v_tail; r.unit_rows = n_tail; r.rows = nullptr; r.rows_stride = 0;
+        r.K = (const uint16_t*)k_tail; r.V = (const uint16_t*)v_tail; r.unit_rows = tail_stride ? tail_stride : n_tail; r.rows = nullptr; r.rows_stride = 0;
         r.count_dev = nullptr; r.count_max = n_tail; r.scores = nullptr; r.chunk0 = chunk0;
         r.chunk_rows = cr; r.row0 = 0; r.n_chunks = ceil_div(n_tail, cr); chunk0 += r.n_chunks;
     }

@@ -168,6 +168,34 @@ def test_exact_ties_take_lower_id_first():
     ctx.close()
 
 
+def test_tail_in_a_buffer_of_fixed_capacity():
+    """The first n_tail rows of a larger tail buffer give the same bits as a densely packed tail."""
+    from paper_2506_13059_amd import binding as mp
+    B, Hq, Hkv, n = 2, 4, 2, 600
+    K, V, q = _mk(B, Hq, Hkv, n, 12, seed=21, softness=0.5)
+    g = torch.Generator(device="cuda").manual_seed(22)
+    fot = torch.randint(0, 12, (B * Hkv, n), generator=g, device="cuda").to(torch.int32)
+    ctx = mp.MpContext(B, Hq, Hkv, max_tokens=n, levels=1, max_fine=12, max_tail=32)
+    ctx.mp_set_clustering(K, V, fot, 12)
+    kt = torch.randn(B, Hkv, 32, 128, generator=g, device="cuda").to(torch.bfloat16)
+    vt = torch.randn(B, Hkv, 32, 128, generator=g, device="cuda").to(torch.bfloat16)
+    for n_tail in (0, 1, 7, 32):
+        a = ctx.mp_decode_attention(q[0].contiguous(), 100, k_tail=kt, v_tail=vt, n_tail=n_tail)
+        if n_tail:
+            b = ctx.mp_decode_attention(q[0].contiguous(), 100, k_tail=kt[:, :, :n_tail].contiguous(),
+                                        v_tail=vt[:, :, :n_tail].contiguous())
+        else:
+            b = ctx.mp_decode_attention(q[0].contiguous(), 100)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b), f"n_tail={n_tail}"
+    with pytest.raises(mp.MpError):
+        lib_call = mp.lib().mp_decode_attention      # 0 < tail_stride < n_tail is refused
+        st = lib_call(ctx.h, q[0].contiguous().data_ptr(), kt.data_ptr(), vt.data_ptr(), 8, 4, 100, 0, 0,
+                      torch.empty_like(q[0]).data_ptr(), None, None)
+        mp._check(st, ctx.h)
+    ctx.close()
+
+
 def test_decode_argument_errors():
     from paper_2506_13059_amd import binding as mp
     ctx = mp.MpContext(1, 4, 1, max_tokens=64, levels=1, max_fine=4, max_tail=2)

@@ -8,13 +8,18 @@ import torch
 pytestmark = pytest.mark.gpu
 
 
-def _run_case(B, Hq, Hkv, n, modes, levels, nf, nc, W, alpha, iters, seed, noise=0.3):
+def _run_case(B, Hq, Hkv, n, modes, levels, nf, nc, W, alpha, iters, seed, noise=0.3, distinct_rows=0):
     from paper_2506_13059_amd import binding as mp, inputs
     from oracle import mp_oracle as O
     from tests.gpu_util import f64, i32
     U = B * Hkv
     centers = inputs.make_modes(U, modes, "cuda", seed)
     K, V = inputs.draw_tokens(centers, n, seed + 1, noise=noise)
+    if distinct_rows:
+        # every token is a copy of one of a few rows: many points and seeds are exactly equal
+        g = torch.Generator(device="cuda").manual_seed(seed + 9)
+        pick = torch.randint(0, distinct_rows, (U, n), generator=g, device="cuda")
+        K = torch.gather(K[:, :distinct_rows], 1, pick[..., None].expand(U, n, 128)).contiguous()
     K4, V4 = K.view(B, Hkv, n, 128), V.view(B, Hkv, n, 128)
     blocks = mp.mp_plan_blocks(n, W, alpha, nf, nc if levels == 2 else 0)
     assert blocks == O.plan_blocks(n, W, alpha, nf, nc if levels == 2 else 0)
@@ -64,6 +69,12 @@ def test_cluster_two_level_blockwise_ragged():
 def test_cluster_more_centroids_than_modes_gives_near_ties_and_empties():
     # few, tight modes and many centroids: duplicated seeds inside a mode, empty clusters, near ties
     ctx, K, V = _run_case(2, 2, 1, 1500, 5, 2, 40, 6, 0, 0, iters=5, seed=13, noise=0.05)
+    ctx.close()
+
+
+def test_cluster_exact_duplicates_take_the_lowest_index():
+    # 12 distinct key rows, 32 centroids seeded from them: duplicate centroids, exactly equal distances
+    ctx, K, V = _run_case(1, 2, 2, 700, 12, 2, 32, 4, 0, 0, iters=3, seed=14, distinct_rows=12)
     ctx.close()
 
 
