@@ -14,8 +14,11 @@
 //      further apart than 2^-13 of that scale has a unique nearest centroid in exact arithmetic
 //      too (and by far more than fp64 rounding), which is the fp64 answer.
 //   2. Every other point (near-equal or equal distances) goes onto a per-block list and
-//      assign_exact_list_kernel recomputes it exactly as defined above, over all centroids of the
-//      block, in fp64 without fused multiply-adds.
+//      assign_recheck_kernel decides it exactly as defined above: it collects the centroids whose
+//      score is within the same margin of the best one and evaluates their distances in fp64
+//      without fused multiply-adds.
+#include <algorithm>
+
 #include "mp_device.h"
 #include "mp_internal.h"
 
@@ -142,87 +145,175 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
     }
 }
 
-// Exact assignment of the listed points.  A workgroup takes 32 listed points; the 8 threads that
-// share a point split every tile of 32 centroids among them (thread s takes centroids s, s+8, ...),
-// each computing whole distances in the defining order, and the 8 partial results are merged with
-// the lower centroid index winning equal distances.  The block's centroids pass through LDS as
-// doubles, 32 at a time.  grid = (nb, U, ceil(max points per block / 32)): the list position is the
-// slowest grid dimension, so that the few workgroups that have work (short lists) are neighbours
-// in dispatch order and spread over the whole chip; the others leave at once.
-constexpr int kExactPts = 32;
-__global__ __launch_bounds__(256) void assign_exact_list_kernel(const uint16_t* __restrict__ X, long long x_unit_rows,
-                                                                const int32_t* __restrict__ blocks,
-                                                                const uint16_t* __restrict__ C, long long c_unit_rows,
-                                                                int32_t* __restrict__ assign, long long assign_stride,
-                                                                const int32_t* __restrict__ amb_list, long long list_stride,
-                                                                const int32_t* __restrict__ amb_cnt, int cnt_stride)
+// Stage 2.  One wave per listed point, three passes over the block's centroids:
+//   1. fp32 scores s_j = x.c_j - |c_j|^2/2 again (8 lanes per centroid, 16 dims each, sequential
+//      fused multiply-adds: error far below the bound of stage 1), their maximum and max_j |c_j|^2;
+//   2. every centroid whose score (kept in LDS, or computed once more for blocks with more than
+//      kScoreCache centroids) is within the margin of the maximum is a candidate: the nearest
+//      centroid in exact arithmetic, and everything tied with it, is among them;
+//   3. the candidates' distances exactly as defined, one lane per candidate, fp64, no fused
+//      multiply-adds, sum in index order; smallest distance wins, equal distances -> lowest index.
+// More than kCandCap candidates (many coinciding centroids): every centroid is treated as one.
+// grid = (nb, U, Z): the waves of a (block, unit) walk its list with stride 4 Z.  The list position
+// is the slowest grid dimension, so that the few workgroups that have work are neighbours in
+// dispatch order and spread over the whole chip.
+constexpr int kCandCap = 64;
+constexpr int kScoreCache = 2048;     // scores of pass 1 kept in LDS for pass 2 when the block has no more centroids
+
+__device__ __forceinline__ void wave_lds_sync()
 {
-    __shared__ double ct[kTile * kHeadDim];
-    __shared__ double part_d[8][kExactPts];
-    __shared__ int part_j[8][kExactPts];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// |x - c|^2 in fp64, dims in index order, rounding after every operation
+__device__ __forceinline__ double exact_distance(const uint16_t* xrow /*LDS*/, const uint16_t* crow /*global*/)
+{
+    double s = 0.0;
+    const uint4* cp = reinterpret_cast<const uint4*>(crow);
+    const uint4* xp = reinterpret_cast<const uint4*>(xrow);
+#pragma unroll 2
+    for (int i = 0; i < 16; ++i) {
+        const uint4 cw = cp[i], xw = xp[i];
+        const uint32_t c4[4] = {cw.x, cw.y, cw.z, cw.w}, x4[4] = {xw.x, xw.y, xw.z, xw.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const double d0 = __dsub_rn((double)bf16lo_to_f32(x4[e]), (double)bf16lo_to_f32(c4[e]));
+            const double d1 = __dsub_rn((double)bf16hi_to_f32(x4[e]), (double)bf16hi_to_f32(c4[e]));
+            s = __dadd_rn(s, __dmul_rn(d0, d0));
+            s = __dadd_rn(s, __dmul_rn(d1, d1));
+        }
+    }
+    return s;
+}
+
+__global__ __launch_bounds__(256) void assign_recheck_kernel(const uint16_t* __restrict__ X, long long x_unit_rows,
+                                                             const int32_t* __restrict__ blocks,
+                                                             const uint16_t* __restrict__ C, long long c_unit_rows,
+                                                             int32_t* __restrict__ assign, long long assign_stride,
+                                                             const int32_t* __restrict__ amb_list, long long list_stride,
+                                                             const int32_t* __restrict__ amb_cnt, int cnt_stride)
+{
+    __shared__ __align__(16) uint16_t xrow[4][kHeadDim];
+    __shared__ int cand[4][kCandCap];
+    __shared__ int ncand[4];
+    __shared__ float sc_cache[4][kScoreCache];
     const int b = blockIdx.x, u = blockIdx.y;
     const int x0 = blocks[4 * b + 0], x1 = blocks[4 * b + 1], k0 = blocks[4 * b + 2], k1 = blocks[4 * b + 3];
     int n = amb_cnt[u * cnt_stride + b];
     if (n > x1 - x0) n = x1 - x0;
-    const int e0 = (int)blockIdx.z * kExactPts;
-    if (e0 >= n) return;
-    const int pt = threadIdx.x & (kExactPts - 1), slice = threadIdx.x / kExactPts;
-    const bool live = e0 + pt < n;
-    const int t = amb_list[u * list_stride + x0 + (live ? e0 + pt : e0)];
-    float x[kHeadDim];
-    {
-        const uint4* xp = reinterpret_cast<const uint4*>(X + ((long long)u * x_unit_rows + t) * kHeadDim);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const uint4 w = xp[i];
-            x[8 * i + 0] = bf16lo_to_f32(w.x); x[8 * i + 1] = bf16hi_to_f32(w.x);
-            x[8 * i + 2] = bf16lo_to_f32(w.y); x[8 * i + 3] = bf16hi_to_f32(w.y);
-            x[8 * i + 4] = bf16lo_to_f32(w.z); x[8 * i + 5] = bf16hi_to_f32(w.z);
-            x[8 * i + 6] = bf16lo_to_f32(w.w); x[8 * i + 7] = bf16hi_to_f32(w.w);
-        }
-    }
-    double best = INFINITY;
-    int bj = k0;
-    for (int j0 = k0; j0 < k1; j0 += kTile) {
-        const int nj = (k1 - j0 < kTile) ? k1 - j0 : kTile;
-        __syncthreads();
-        for (int e = threadIdx.x; e < nj * (kHeadDim / 2); e += 256) {
-            const int j = e >> 6, w = e & 63;
-            const uint32_t cw = reinterpret_cast<const uint32_t*>(C + ((long long)u * c_unit_rows + j0 + j) * kHeadDim)[w];
-            ct[j * kHeadDim + 2 * w] = (double)bf16lo_to_f32(cw);
-            ct[j * kHeadDim + 2 * w + 1] = (double)bf16hi_to_f32(cw);
-        }
-        __syncthreads();
-        for (int j = slice; j < nj; j += 8) {
-            double s = 0.0;
-#pragma unroll
-            for (int i = 0; i < kHeadDim; i += 2) {
-                const double2 c2 = *reinterpret_cast<const double2*>(&ct[j * kHeadDim + i]);
-                const double d0 = __dsub_rn((double)x[i], c2.x);
-                const double d1 = __dsub_rn((double)x[i + 1], c2.y);
-                s = __dadd_rn(s, __dmul_rn(d0, d0));
-                s = __dadd_rn(s, __dmul_rn(d1, d1));
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane & 7, grp = lane >> 3;
+    const uint16_t* Cu = C + (long long)u * c_unit_rows * kHeadDim;
+    for (int e = (int)blockIdx.z * 4 + wave; e < n; e += (int)gridDim.z * 4) {
+        const int t = amb_list[u * list_stride + x0 + e];
+        const uint16_t* xg = X + ((long long)u * x_unit_rows + t) * kHeadDim;
+        float xs[16];
+        float x2 = 0.f;
+        {
+            const uint4 a = reinterpret_cast<const uint4*>(xg)[2 * sub], bq = reinterpret_cast<const uint4*>(xg)[2 * sub + 1];
+            if (grp == 0) {
+                reinterpret_cast<uint4*>(xrow[wave])[2 * sub] = a;
+                reinterpret_cast<uint4*>(xrow[wave])[2 * sub + 1] = bq;
             }
-            if (s < best) {
-                best = s;
-                bj = j0 + j;
-            }
-        }
-    }
-    part_d[slice][pt] = best;
-    part_j[slice][pt] = bj;
-    __syncthreads();
-    if (slice == 0 && live) {
+            const uint32_t w[8] = {a.x, a.y, a.z, a.w, bq.x, bq.y, bq.z, bq.w};
 #pragma unroll
-        for (int sl = 1; sl < 8; ++sl) {
-            const double od = part_d[sl][pt];
-            const int oj = part_j[sl][pt];
-            if (od < best || (od == best && oj < bj)) {
-                best = od;
-                bj = oj;
+            for (int q = 0; q < 8; ++q) {
+                xs[2 * q] = bf16lo_to_f32(w[q]);
+                xs[2 * q + 1] = bf16hi_to_f32(w[q]);
+                x2 = fmaf(xs[2 * q], xs[2 * q], x2);
+                x2 = fmaf(xs[2 * q + 1], xs[2 * q + 1], x2);
+            }
+            x2 = sum8(x2);
+        }
+        // s_j and |c_j|^2 of four centroids j, j+8, j+16, j+24 by the 8 lanes of a group (every lane of
+        // the group gets them); all eight row loads are issued before the first is used
+        auto scores4 = [&](int j, float (&sc)[4], float (&cc)[4]) {
+            uint4 a[4], bq[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int jr = (j + 8 * r < k1) ? j + 8 * r : k1 - 1;
+                const uint4* cp = reinterpret_cast<const uint4*>(Cu + (long long)jr * kHeadDim);
+                a[r] = cp[2 * sub];
+                bq[r] = cp[2 * sub + 1];
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t w[8] = {a[r].x, a[r].y, a[r].z, a[r].w, bq[r].x, bq[r].y, bq[r].z, bq[r].w};
+                float dot = 0.f, c2 = 0.f;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const float lo = bf16lo_to_f32(w[q]), hi = bf16hi_to_f32(w[q]);
+                    dot = fmaf(xs[2 * q], lo, dot);
+                    dot = fmaf(xs[2 * q + 1], hi, dot);
+                    c2 = fmaf(lo, lo, c2);
+                    c2 = fmaf(hi, hi, c2);
+                }
+                dot = sum8(dot);
+                c2 = sum8(c2);
+                cc[r] = c2;
+                sc[r] = (j + 8 * r < k1) ? fmaf(-0.5f, c2, dot) : -INFINITY;
+            }
+        };
+        const bool cached = k1 - k0 <= kScoreCache;
+        float best = -INFINITY, c2max = 0.f;
+        for (int j = k0 + grp; j < k1; j += 32) {
+            float sc[4], cc[4];
+            scores4(j, sc, cc);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                best = fmaxf(best, sc[r]);
+                c2max = fmaxf(c2max, cc[r]);        // (a clamped row repeats a real one)
+                if (cached && sub == 0 && j + 8 * r < k1) sc_cache[wave][j + 8 * r - k0] = sc[r];
             }
         }
-        assign[u * assign_stride + t] = bj;
+        best = wave_max_f32(best);
+        c2max = wave_max_f32(c2max);
+        const float thr = best - kMarginScale * fmaxf(x2, c2max);
+        if (lane == 0) ncand[wave] = 0;
+        wave_lds_sync();
+        auto consider = [&](int j, float sc) {
+            if (!(sc < thr)) {                       // also true for NaN
+                const int pos = atomicAdd(&ncand[wave], 1);
+                if (pos < kCandCap) cand[wave][pos] = j;
+            }
+        };
+        if (cached) {
+            for (int j = k0 + lane; j < k1; j += 64) consider(j, sc_cache[wave][j - k0]);
+        } else {
+            for (int j = k0 + grp; j < k1; j += 32) {
+                float sc[4], cc[4];
+                scores4(j, sc, cc);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (sub == 0 && j + 8 * r < k1) consider(j + 8 * r, sc[r]);
+            }
+        }
+        wave_lds_sync();
+        const int nc = ncand[wave];
+        double bd = INFINITY;
+        int bj = k0;
+        if (nc <= kCandCap) {
+            if (lane < nc) {
+                const int j = cand[wave][lane];
+                const double d = exact_distance(xrow[wave], Cu + (long long)j * kHeadDim);
+                if (d < bd) { bd = d; bj = j; }
+            }
+        } else {
+            for (int j = k0 + lane; j < k1; j += 64) {
+                const double d = exact_distance(xrow[wave], Cu + (long long)j * kHeadDim);
+                if (d < bd) { bd = d; bj = j; }
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const double od = __shfl_xor(bd, off, 64);
+            const int oj = __shfl_xor(bj, off, 64);
+            if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
+        }
+        if (lane == 0) assign[u * assign_stride + t] = bj;
+        wave_lds_sync();       // xrow / cand are reused by the next point
     }
 }
 
@@ -233,14 +324,15 @@ hipError_t launch_assign(const uint16_t* X, long long x_unit_rows, const int32_t
                          int32_t* amb_list, long long list_stride, int32_t* amb_cnt, int cnt_stride, hipStream_t s)
 {
     if (nb <= 0 || max_pts <= 0 || U <= 0) return hipSuccess;
-    if (nb > cnt_stride || U > 65535 || (max_pts + kExactPts - 1) / kExactPts > 65535) return hipErrorInvalidValue;
+    if (nb > cnt_stride || U > 65535) return hipErrorInvalidValue;
     hipError_t e = launch_fill_i32(amb_cnt, (long long)U * cnt_stride, 0, s);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(assign_mfma_kernel, dim3((max_pts + 127) / 128, nb, U), dim3(256), 0, s, X, x_unit_rows,
                        blocks_dev, C, c_unit_rows, assign, assign_stride, amb_list, list_stride, amb_cnt, cnt_stride);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(assign_exact_list_kernel, dim3(nb, U, (max_pts + kExactPts - 1) / kExactPts), dim3(256), 0, s, X, x_unit_rows,
+    const int z = std::min(32, (max_pts + 3) / 4);
+    hipLaunchKernelGGL(assign_recheck_kernel, dim3(nb, U, z), dim3(256), 0, s, X, x_unit_rows,
                        blocks_dev, C, c_unit_rows, assign, assign_stride, amb_list, list_stride, amb_cnt, cnt_stride);
     return hipGetLastError();
 }

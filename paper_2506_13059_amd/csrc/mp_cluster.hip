@@ -142,12 +142,8 @@ mp_status launch_assign(mp_ctx* ctx, const Problem& pr, hipStream_t s)
 mp_status build_lists(mp_ctx* ctx, const Problem& pr, hipStream_t s)
 {
     const int U = ctx->U;
-    MP_HIPC(launch_fill_i32(pr.cnt, (long long)U * pr.cnt_stride, 0, s));
-    MP_HIPC(launch_histogram(pr.assign + pr.p_first, pr.assign_stride, pr.n_points - pr.p_first, U, pr.cnt,
-                             pr.cnt_stride, s));
-    MP_HIPC(launch_exclusive_scan(pr.cnt, pr.cnt_stride, pr.k_total, U, pr.start, pr.cnt_stride + 1, s));
-    MP_HIPC(launch_member_lists(pr.assign, pr.assign_stride, pr.blocks_dev, pr.nb, pr.max_k, U, pr.start,
-                                pr.cnt_stride + 1, pr.list, pr.list_stride, s));
+    MP_HIPC(launch_block_lists(pr.assign, pr.assign_stride, pr.blocks_dev, pr.nb, pr.max_k, pr.p_first, U, pr.start,
+                               pr.cnt_stride + 1, pr.list, pr.list_stride, s));
     return MP_OK;
 }
 
@@ -238,10 +234,7 @@ mp_status finalize_range(mp_ctx* ctx, const void* Xk, const void* Xv, long long 
     if (ids != ctx->fot + pt0)
         MP_HIPC(hipMemcpy2DAsync(ctx->fot + pt0, (size_t)Ncap * 4, ids, (size_t)ids_stride * 4, (size_t)n_pts * 4, U,
                                  hipMemcpyDeviceToDevice, s));
-    MP_HIPC(launch_fill_i32(ctx->km_cnt, (long long)U * tab, 0, s));
-    MP_HIPC(launch_histogram(ids, ids_stride, n_pts, U, ctx->km_cnt, tab, s));
-    MP_HIPC(launch_exclusive_scan(ctx->km_cnt, tab, f1, U, ctx->km_start, tab + 1, s));
-    MP_HIPC(launch_member_lists(ids, ids_stride, bdev, nb, max_kf, U, ctx->km_start, tab + 1, ctx->km_list, Ncap, s));
+    MP_HIPC(launch_block_lists(ids, ids_stride, bdev, nb, max_kf, 0, U, ctx->km_start, tab + 1, ctx->km_list, Ncap, s));
     MP_HIPC(launch_offset_lists(ctx->km_start, tab + 1, f0, f1, ctx->km_list, Ncap, n_pts, pt0, U, ctx->fstart,
                                 ctx->Fcap + 1, ctx->perm, Ncap, s));
     MP_HIPC(launch_gather_rows(Xk, Xv, x_unit_rows, ctx->km_list, Ncap, n_pts, U, ctx->Kp, ctx->Vp, Ncap, pt0, s));

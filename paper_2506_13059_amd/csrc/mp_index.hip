@@ -4,6 +4,8 @@
 //
 // Member sums run over the members in sequence order, one wave per cluster, in fp64: the result
 // does not depend on the launch shape and repeats bit for bit.
+#include <type_traits>
+
 #include "mp_device.h"
 #include "mp_internal.h"
 
@@ -92,6 +94,106 @@ __global__ __launch_bounds__(256) void member_list_kernel(const int32_t* __restr
                 if (tile[i] == my) lp[wr++] = t0 + i;
         }
     }
+}
+
+// Member lists and their offsets for every block of a unit in one launch: a stable counting sort of
+// the block's points by cluster id.  One workgroup of 16 waves per (block, unit); `waves` of them
+// walk one contiguous segment of the block's points each, 64 points at a time.
+//   Among the 64 points of a step, the lanes that share this lane's id are found with one ballot per
+//   id bit; a point's rank among them is the number of such lanes below it, and the lowest of them
+//   adds their number to the segment's counter of that id (LDS, touched by this wave only).
+//   walk 1 counts; then counter[w][id] becomes the position of the first member of id in segment w
+//   (block offset + exclusive prefix over ids + members in earlier segments); walk 2 writes the
+//   members at counter + rank.  Within a cluster the members end up in ascending point order.
+// start[u][id] = first list position of cluster id (positions count from the first point of the
+// launch, `p_first`); the last block also writes the end position after its last cluster.
+// Dynamic LDS: (waves + 1) * max clusters per block int32.
+constexpr int kListWaves = 16;
+__global__ __launch_bounds__(1024) void block_lists_kernel(const int32_t* __restrict__ ids, long long ids_stride,
+                                                           const int32_t* __restrict__ blocks /*[nb][4]: x0,x1,k0,k1*/,
+                                                           int p_first, int waves, int32_t* __restrict__ start,
+                                                           long long start_stride, int32_t* __restrict__ list,
+                                                           long long list_stride)
+{
+    extern __shared__ int32_t lists_lds[];
+    __shared__ int32_t wave_tot[kListWaves];
+    const int b = blockIdx.x, u = blockIdx.y;
+    const int x0 = blocks[4 * b + 0], x1 = blocks[4 * b + 1], k0 = blocks[4 * b + 2], k1 = blocks[4 * b + 3];
+    const int k = k1 - k0, n = x1 - x0;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int32_t* ctr = lists_lds;                  // [waves][k]
+    int32_t* tot = lists_lds + waves * k;      // [k]
+    const int32_t* idp = ids + u * ids_stride;
+    int32_t* lp = list + u * list_stride;
+    const int bits = k > 1 ? 32 - __clz(k - 1) : 0;
+    const int seg = (((n + waves - 1) / waves) + 63) & ~63;
+    const int s0 = x0 + wave * seg, s1 = (s0 + seg < x1) ? s0 + seg : x1;
+    const unsigned long long below = (1ull << lane) - 1ull;
+
+    for (int i = tid; i < waves * k; i += 1024) ctr[i] = 0;
+    __syncthreads();
+    // one walk over the wave's segment; kWrite = false: count, true: place
+    auto walk = [&](auto write_tag) {
+        constexpr bool kWrite = decltype(write_tag)::value;
+        if (wave >= waves) return;
+        int32_t* my = ctr + wave * k;
+        for (int t0 = s0; t0 < s1; t0 += 256) {
+            int id4[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int t = t0 + 64 * r + lane;
+                id4[r] = t < s1 ? idp[t] - k0 : -1;
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int t = t0 + 64 * r + lane;
+                const int id = id4[r];
+                const bool valid = id >= 0;
+                unsigned long long same = __ballot(valid);
+                for (int bit = 0; bit < bits; ++bit) {
+                    const bool one = (id >> bit) & 1;
+                    const unsigned long long m = __ballot(valid && one);
+                    same &= one ? m : ~m;
+                }
+                const int rank = __popcll(same & below);
+                if (valid) {
+                    const int base = my[id];
+                    if (kWrite) lp[base + rank] = t;
+                    if (rank == 0) my[id] = base + __popcll(same);
+                }
+            }
+        }
+    };
+    walk(std::false_type{});
+    __syncthreads();
+    // counts per segment -> first positions: totals per id, exclusive prefix over ids, segments in order
+    const int per = (k + 1023) / 1024;          // consecutive ids per thread
+    const int i0 = tid * per, i1 = (i0 + per < k) ? i0 + per : k;
+    int run = 0;
+    for (int id = i0; id < i1; ++id) {
+        int c = 0;
+        for (int w = 0; w < waves; ++w) c += ctr[w * k + id];
+        tot[id] = c;
+        run += c;
+    }
+    const int incl = (int)wave_incl_scan_u32((uint32_t)run);
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int pos = x0 - p_first + incl - run;
+    for (int w = 0; w < wave; ++w) pos += wave_tot[w];
+    for (int id = i0; id < i1; ++id) {
+        start[u * start_stride + k0 + id] = pos;
+        int q = pos;
+        for (int w = 0; w < waves; ++w) {
+            const int c = ctr[w * k + id];
+            ctr[w * k + id] = q;
+            q += c;
+        }
+        pos += tot[id];
+    }
+    if (b == (int)gridDim.x - 1 && tid == 0) start[u * start_stride + k1] = x1 - p_first;
+    __syncthreads();
+    walk(std::true_type{});
 }
 
 // dst[u][p] = src[u][list[u][p]] for 256-byte rows; one thread moves 16 bytes.
@@ -281,6 +383,28 @@ hipError_t launch_member_lists(const int32_t* ids, long long ids_stride, const i
     if (nb <= 0 || max_k_per_block <= 0) return hipSuccess;
     hipLaunchKernelGGL(member_list_kernel, dim3((max_k_per_block + 255) / 256, nb, U), dim3(256), 0, s, ids,
                        ids_stride, blocks_dev, start, start_stride, list, list_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_block_lists(const int32_t* ids, long long ids_stride, const int32_t* blocks_dev, int nb,
+                              int max_k_per_block, int p_first, int U, int32_t* start, long long start_stride,
+                              int32_t* list, long long list_stride, hipStream_t s)
+{
+    if (nb <= 0 || max_k_per_block <= 0) return hipSuccess;
+    constexpr int kLdsInts = 16384;            // 64 KiB
+    if (2 * max_k_per_block > kLdsInts) return hipErrorInvalidValue;
+    int waves = kLdsInts / max_k_per_block - 1;
+    if (waves > kListWaves) waves = kListWaves;
+    const size_t smem = (size_t)(waves + 1) * max_k_per_block * sizeof(int32_t);
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&block_lists_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsInts * 4);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL(block_lists_kernel, dim3(nb, U), dim3(1024), smem, s, ids, ids_stride, blocks_dev, p_first,
+                       waves, start, start_stride, list, list_stride);
     return hipGetLastError();
 }
 

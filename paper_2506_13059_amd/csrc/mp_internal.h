@@ -115,6 +115,12 @@ hipError_t launch_histogram(const int32_t* ids, long long ids_stride, int n, int
                             long long cnt_stride, hipStream_t s);
 hipError_t launch_exclusive_scan(const int32_t* cnt, long long cnt_stride, int k, int U, int32_t* start,
                                  long long start_stride, hipStream_t s);
+// Member lists of all blocks in one launch (stable counting sort by cluster id):
+// start[u][id] = first list position of cluster id, counted from point p_first; the entry after the
+// last block's last cluster receives the end position; list[u][position] = point index.
+hipError_t launch_block_lists(const int32_t* ids, long long ids_stride, const int32_t* blocks_dev, int nb,
+                              int max_k_per_block, int p_first, int U, int32_t* start, long long start_stride,
+                              int32_t* list, long long list_stride, hipStream_t s);
 // blocks_dev: int32 [nb][4] = {first point, end point, first cluster, end cluster}
 hipError_t launch_member_lists(const int32_t* ids, long long ids_stride, const int32_t* blocks_dev, int nb,
                                int max_k_per_block, int U, const int32_t* start, long long start_stride,
