@@ -170,6 +170,12 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     A(mp_rows, U * T); A(mp_scores, U * T * G); A(n_mp, U); A(counters, U * 4);
     A(partials, U * (size_t)ctx->Pcap * G * kPartStride);
 #undef A
+    if (e == hipSuccess) {
+        ctx->pin_bytes = 1u << 20;
+        e = hipHostMalloc((void**)&ctx->pin, ctx->pin_bytes, hipHostMallocDefault);
+        if (e != hipSuccess) ctx->pin = nullptr;
+    }
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->pin_ev, hipEventDisableTiming);
     if (e == hipSuccess) e = hipMemset(ctx->counters, 0, U * 4 * sizeof(int32_t));
     if (e == hipSuccess) e = hipMemset(ctx->n_mp, 0, U * sizeof(int32_t));
     if (e == hipSuccess) e = hipMemset(ctx->n_rows, 0, U * sizeof(int32_t));
@@ -191,6 +197,8 @@ void mp_destroy(mp_ctx* ctx)
     (void)hipDeviceSynchronize();
     for (hipEvent_t e : ctx->ev)
         if (e) (void)hipEventDestroy(e);
+    if (ctx->pin_ev) (void)hipEventDestroy(ctx->pin_ev);
+    if (ctx->pin) (void)hipHostFree(ctx->pin);
     free_all(ctx);
     delete ctx;
 }

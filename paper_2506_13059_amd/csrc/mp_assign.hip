@@ -10,7 +10,8 @@
 //      v_mfma_f32_32x32x16_bf16, fp32 accumulation.  Per point it keeps the best and the second
 //      best score.  The products are exact and every one of the 128 accumulation steps loses at
 //      most one unit in the last place of a partial sum bounded by |x||c|, so each score is within
-//      2^-16 max(|x|^2, max_j |c_j|^2) of its exact value.  A point whose two best scores are
+//      2^-16 max(|x|^2, max_j |c_j|^2) of its exact value (2^-19 more for four mantissa bits that
+//      carry an index during the comparison).  A point whose two best scores are
 //      further apart than 2^-13 of that scale has a unique nearest centroid in exact arithmetic
 //      too (and by far more than fp64 rounding), which is the fp64 answer.
 //   2. Every other point (near-equal or equal distances) goes onto a per-block list and
@@ -32,11 +33,15 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 constexpr int kTile = 32;                 // centroids per tile = rows of the MFMA A operand
 constexpr int kRowBytes = 256 + 16;       // padded LDS row of one centroid
 constexpr float kMarginScale = 1.0f / 8192.0f;   // 2^-13
+constexpr float kNoCentroid = -3.0e38f;          // score of a padded row (finite: index bits are packed into scores)
 
-// grid = (ceil(max points per block / 128), nb, U); 256 threads = 4 waves of 32 points.
+// grid = (ceil(max points per block / 256), nb, U); 256 threads = 4 waves of 64 points (two MFMA
+// column tiles that share every centroid fragment).  Centroid tiles are double-buffered in LDS: the
+// rows of the next tile are requested before the current tile is multiplied and stored after it.
 // blocks: int32 [nb][4] = {first point, end point, first centroid, end centroid}.
 // assign[u][t] receives the best centroid of stage 1; amb_list[u][first point + i], i < amb_cnt[u][b],
-// the points of block b that stage 2 has to recompute.
+// the points of block b that stage 2 has to decide.
+constexpr int kPtsPerWg = 256;
 __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __restrict__ X, long long x_unit_rows,
                                                           const int32_t* __restrict__ blocks,
                                                           const uint16_t* __restrict__ C, long long c_unit_rows,
@@ -44,48 +49,57 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
                                                           int32_t* __restrict__ amb_list, long long list_stride,
                                                           int32_t* __restrict__ amb_cnt, int cnt_stride)
 {
-    __shared__ __align__(16) unsigned char tile[kTile * kRowBytes];
-    __shared__ __align__(16) float tile_c2[kTile];       // -|c|^2 / 2, -inf past the last centroid
+    __shared__ __align__(16) unsigned char tile[2][kTile * kRowBytes];
+    __shared__ __align__(16) float tile_c2[2][kTile];    // -|c|^2 / 2, kNoCentroid past the last centroid
     const int u = blockIdx.z, b = blockIdx.y;
     const int x0 = blocks[4 * b + 0], x1 = blocks[4 * b + 1], k0 = blocks[4 * b + 2], k1 = blocks[4 * b + 3];
-    const int p0 = x0 + (int)blockIdx.x * 128;
+    const int p0 = x0 + (int)blockIdx.x * kPtsPerWg;
     if (p0 >= x1) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
-    const int t = p0 + wave * 32 + col;
-    const bool live = t < x1;
 
-    // B operand: this lane's point, dims [16 ks + 8 half, +8) for ks = 0..7
-    bf16x8_t xb[8];
-    float x2 = 0.f;
-    {
-        const uint4* xp = reinterpret_cast<const uint4*>(X + ((long long)u * x_unit_rows + (live ? t : x0)) * kHeadDim);
+    // B operands: this lane's two points, dims [16 ks + 8 half, +8) for ks = 0..7
+    bf16x8_t xb[2][8];
+    float x2[2];
+    int tpt[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        tpt[c] = p0 + wave * 64 + 32 * c + col;
+        const int tl = tpt[c] < x1 ? tpt[c] : x0;
+        const uint4* xp = reinterpret_cast<const uint4*>(X + ((long long)u * x_unit_rows + tl) * kHeadDim);
+        x2[c] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             const uint4 w = xp[2 * ks + half];
-            xb[ks] = __builtin_bit_cast(bf16x8_t, w);
+            xb[c][ks] = __builtin_bit_cast(bf16x8_t, w);
             const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float lo = bf16lo_to_f32(ww[e]), hi = bf16hi_to_f32(ww[e]);
-                x2 = fmaf(lo, lo, x2);
-                x2 = fmaf(hi, hi, x2);
+                x2[c] = fmaf(lo, lo, x2[c]);
+                x2[c] = fmaf(hi, hi, x2[c]);
             }
         }
     }
-    float best = -INFINITY, second = -INFINITY, c2max = 0.f;
-    int bj = k0;
-    for (int j0 = k0; j0 < k1; j0 += kTile) {
-        const int nj = (k1 - j0 < kTile) ? k1 - j0 : kTile;
-        __syncthreads();
-        // centroid tile -> LDS (zero rows past the end) and its squared norms: 8 threads per row
+    // this thread's share of a centroid tile: two 16-byte pieces, 16 threads per row
+    const uint16_t* Cu = C + (long long)u * c_unit_rows * kHeadDim;
+    uint4 pre[2];
+    auto request = [&](int j0) {
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
             const int e = pass * 256 + tid;
             const int row = e >> 4, seg = e & 15;
-            uint4 w = make_uint4(0, 0, 0, 0);
-            if (row < nj) w = reinterpret_cast<const uint4*>(C + ((long long)u * c_unit_rows + j0 + row) * kHeadDim)[seg];
-            *reinterpret_cast<uint4*>(tile + row * kRowBytes + seg * 16) = w;
+            pre[pass] = make_uint4(0, 0, 0, 0);
+            if (j0 + row < k1) pre[pass] = reinterpret_cast<const uint4*>(Cu + (long long)(j0 + row) * kHeadDim)[seg];
+        }
+    };
+    auto deposit = [&](int j0, int buf) {
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            const int e = pass * 256 + tid;
+            const int row = e >> 4, seg = e & 15;
+            const uint4 w = pre[pass];
+            *reinterpret_cast<uint4*>(tile[buf] + row * kRowBytes + seg * 16) = w;
             const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
             float s = 0.f;
 #pragma unroll
@@ -96,51 +110,76 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
             }
             s = sum8(s);
             s += dpp_f32<kDppMirror>(s);      // the other 8 lanes of the row of 16
-            if (seg == 0) tile_c2[row] = row < nj ? -0.5f * s : -INFINITY;
+            if (seg == 0) tile_c2[buf][row] = (j0 + row < k1) ? -0.5f * s : kNoCentroid;
         }
-        __syncthreads();
+    };
+    float best[2] = {-INFINITY, -INFINITY}, second[2] = {-INFINITY, -INFINITY}, c2max = 0.f;
+    int btile[2] = {k0, k0};
+    request(k0);
+    deposit(k0, 0);
+    __syncthreads();
+    int buf = 0;
+    for (int j0 = k0; j0 < k1; j0 += kTile, buf ^= 1) {
+        const bool more = j0 + kTile < k1;
+        if (more) request(j0 + kTile);
         // accumulator rows of this lane: m(i) = 8 (i / 4) + 4 half + i % 4
-        f32x16_t acc;
+        f32x16_t acc[2];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const float4 c = *reinterpret_cast<const float4*>(&tile_c2[8 * g + 4 * half]);
-            acc[4 * g + 0] = c.x; acc[4 * g + 1] = c.y; acc[4 * g + 2] = c.z; acc[4 * g + 3] = c.w;
+            const float4 c = *reinterpret_cast<const float4*>(&tile_c2[buf][8 * g + 4 * half]);
+            acc[0][4 * g + 0] = c.x; acc[0][4 * g + 1] = c.y; acc[0][4 * g + 2] = c.z; acc[0][4 * g + 3] = c.w;
         }
+        acc[1] = acc[0];
 #pragma unroll
         for (int i = 0; i < 16; ++i)
-            if (acc[i] != -INFINITY) c2max = fmaxf(c2max, -2.f * acc[i]);
+            if (acc[0][i] > kNoCentroid) c2max = fmaxf(c2max, -2.f * acc[0][i]);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(tile + col * kRowBytes + 32 * ks + 16 * half);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[ks], acc, 0, 0, 0);
+            const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(tile[buf] + col * kRowBytes + 32 * ks + 16 * half);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[0][ks], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[1][ks], acc[1], 0, 0, 0);
         }
+        // best and second best per point.  The slot i of a score inside the tile rides in its four
+        // lowest mantissa bits (a change of at most 2^-19 of its magnitude), so that a pair of scores
+        // costs one max3, one med3 and one max; the tile of the best score is noted per tile.
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float v = acc[i];
-            const int j = j0 + 8 * (i >> 2) + 4 * half + (i & 3);
-            second = fmaxf(second, fminf(best, v));
-            bj = v > best ? j : bj;
-            best = fmaxf(best, v);
+        for (int c = 0; c < 2; ++c) {
+            const float before = best[c];
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float va = __uint_as_float((__float_as_uint(acc[c][i]) & ~15u) | (uint32_t)i);
+                const float vb = __uint_as_float((__float_as_uint(acc[c][i + 1]) & ~15u) | (uint32_t)(i + 1));
+                second[c] = fmaxf(second[c], __builtin_amdgcn_fmed3f(best[c], va, vb));
+                best[c] = fmaxf(fmaxf(va, vb), best[c]);
+            }
+            btile[c] = best[c] != before ? j0 : btile[c];
         }
+        if (more) deposit(j0 + kTile, buf ^ 1);
+        __syncthreads();
     }
-    // the two halves of the wave hold the other rows of the same point
-    {
-        const float ob = __shfl_xor(best, 32, 64), os = __shfl_xor(second, 32, 64), oc = __shfl_xor(c2max, 32, 64);
+    // the two halves of the wave hold the other rows of the same points
+    c2max = fmaxf(c2max, __shfl_xor(c2max, 32, 64));
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int slot = (int)(__float_as_uint(best[c]) & 15u);
+        const int bj = btile[c] + 8 * (slot >> 2) + 4 * half + (slot & 3);
+        const float ob = __shfl_xor(best[c], 32, 64), os = __shfl_xor(second[c], 32, 64);
         const int oj = __shfl_xor(bj, 32, 64);
-        const float ox = __shfl_xor(x2, 32, 64);
-        second = fmaxf(fmaxf(second, os), fminf(best, ob));
-        if (ob > best || (ob == best && oj < bj)) bj = oj;
-        best = fmaxf(best, ob);
-        c2max = fmaxf(c2max, oc);
-        x2 += ox;
-    }
-    if (live && half == 0) {
-        assign[u * assign_stride + t] = bj;
-        const float margin = kMarginScale * fmaxf(x2, c2max);
-        // (written so that a NaN score also sends the point to the exact pass)
-        if (!(best - second > margin)) {
-            const int pos = atomicAdd(&amb_cnt[u * cnt_stride + b], 1);
-            amb_list[u * list_stride + x0 + pos] = t;
+        const float ox = __shfl_xor(x2[c], 32, 64);
+        const float sec = fmaxf(fmaxf(second[c], os), fminf(best[c], ob));
+        int j = bj;
+        if (ob > best[c] || (ob == best[c] && oj < j)) j = oj;
+        const float bst = fmaxf(best[c], ob);
+        const float xx = x2[c] + ox;
+        const int t = tpt[c];
+        if (t < x1 && half == 0) {
+            assign[u * assign_stride + t] = j;
+            const float margin = kMarginScale * fmaxf(xx, c2max);
+            // (written so that a point without any comparable score also goes to the exact pass)
+            if (!(bst - sec > margin)) {
+                const int pos = atomicAdd(&amb_cnt[u * cnt_stride + b], 1);
+                amb_list[u * list_stride + x0 + pos] = t;
+            }
         }
     }
 }
@@ -327,11 +366,11 @@ hipError_t launch_assign(const uint16_t* X, long long x_unit_rows, const int32_t
     if (nb > cnt_stride || U > 65535) return hipErrorInvalidValue;
     hipError_t e = launch_fill_i32(amb_cnt, (long long)U * cnt_stride, 0, s);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(assign_mfma_kernel, dim3((max_pts + 127) / 128, nb, U), dim3(256), 0, s, X, x_unit_rows,
+    hipLaunchKernelGGL(assign_mfma_kernel, dim3((max_pts + kPtsPerWg - 1) / kPtsPerWg, nb, U), dim3(256), 0, s, X, x_unit_rows,
                        blocks_dev, C, c_unit_rows, assign, assign_stride, amb_list, list_stride, amb_cnt, cnt_stride);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int z = std::min(32, (max_pts + 3) / 4);
+    const int z = std::min(128, (max_pts + 3) / 4);
     hipLaunchKernelGGL(assign_recheck_kernel, dim3(nb, U, z), dim3(256), 0, s, X, x_unit_rows,
                        blocks_dev, C, c_unit_rows, assign, assign_stride, amb_list, list_stride, amb_cnt, cnt_stride);
     return hipGetLastError();

@@ -11,6 +11,7 @@
 // dimension without fused multiply-add, scanning centroids in ascending id with a strict "<":
 // equal distances keep the lowest id.
 #include <algorithm>
+#include <cstring>
 #include <vector>
 
 #include "mp_ctx.h"
@@ -108,6 +109,48 @@ __global__ __launch_bounds__(256) void running_mean_kernel(const uint16_t* __res
     } while (0)
 
 inline unsigned blocks_for(long long n, int per) { return (unsigned)((n + per - 1) / per); }
+
+// Start of an entry point that uploads small host arrays: the pinned staging buffer may be reused
+// once the copies of the previous call have been carried out.
+mp_status stage_open(mp_ctx* ctx)
+{
+    if (ctx->pin_pending) {
+        MP_HIPC(hipEventSynchronize(ctx->pin_ev));
+        ctx->pin_pending = false;
+    }
+    ctx->pin_used = 0;
+    return MP_OK;
+}
+
+// Host -> device copy of `height` rows of `width` bytes.  What fits goes through the pinned staging
+// buffer (packed there at once, so the caller's array is free again on return; the copy itself is
+// asynchronous); larger arrays are copied directly from the caller's memory.
+mp_status upload_2d(mp_ctx* ctx, void* dst, size_t dpitch, const void* src, size_t spitch, size_t width, size_t height,
+                    hipStream_t s)
+{
+    if (width == 0 || height == 0) return MP_OK;
+    const size_t bytes = width * height;
+    if (ctx->pin && ctx->pin_used + bytes <= ctx->pin_bytes) {
+        char* p = ctx->pin + ctx->pin_used;
+        for (size_t r = 0; r < height; ++r) memcpy(p + r * width, (const char*)src + r * spitch, width);
+        ctx->pin_used += (bytes + 255) & ~(size_t)255;
+        MP_HIPC(hipMemcpy2DAsync(dst, dpitch, p, width, width, height, hipMemcpyHostToDevice, s));
+        MP_HIPC(hipEventRecord(ctx->pin_ev, s));
+        ctx->pin_pending = true;
+    } else {
+        MP_HIPC(hipMemcpy2DAsync(dst, dpitch, src, spitch, width, height, hipMemcpyHostToDevice, s));
+    }
+    return MP_OK;
+}
+mp_status upload(mp_ctx* ctx, void* dst, const void* src, size_t bytes, hipStream_t s)
+{
+    return upload_2d(ctx, dst, bytes, src, bytes, bytes, 1, s);
+}
+#define MP_TRY(expr)                       \
+    do {                                   \
+        const mp_status st_ = (expr);      \
+        if (st_ != MP_OK) return st_;      \
+    } while (0)
 
 struct Problem {
     const uint16_t* X;
@@ -319,8 +362,7 @@ mp_status cluster_range(mp_ctx* ctx, const Range& r, int iters, hipStream_t s)
     int max_pts, max_kf, max_kc;
     upload_descs(r, ctx->max_blocks, ctx->stage_blocks2, max_pts, max_kf, max_kc);
     int32_t* bdev_f = ctx->blocks_dev + 4 * (size_t)ctx->max_blocks;
-    MP_HIPC(hipMemcpyAsync(bdev_f, ctx->stage_blocks2.data(), ctx->stage_blocks2.size() * sizeof(int32_t),
-                           hipMemcpyHostToDevice, s));
+    MP_TRY(upload(ctx, bdev_f, ctx->stage_blocks2.data(), ctx->stage_blocks2.size() * sizeof(int32_t), s));
     Problem pf{};
     pf.X = r.Xk; pf.x_unit_rows = r.x_unit_rows; pf.n_points = r.n_pts; pf.p_first = 0; pf.blocks_dev = bdev_f; pf.nb = nb;
     pf.max_pts = max_pts; pf.max_k = max_kf; pf.k_total = r.f1; pf.k_first = r.f0; pf.C = ctx->km_Cf; pf.c_unit_rows = ctx->Fcap;
@@ -342,6 +384,7 @@ mp_status cluster_kv_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_t
                           int32_t n_coarse, int32_t iters, uint64_t seed, const int32_t* init_fine,
                           const int32_t* init_coarse, hipStream_t s)
 {
+    MP_TRY(stage_open(ctx));
     const int U = ctx->U;
     const bool two = ctx->cfg.levels == 2;
     const std::vector<BlockPlan> blocks = plan_blocks(n_tokens, ctx->cfg.block_w, ctx->cfg.block_alpha, n_fine, n_coarse);
@@ -367,11 +410,10 @@ mp_status cluster_kv_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_t
                               gen_c.data() + (size_t)u * n_coarse + blocks[b].c0);
         init_coarse = gen_c.data();
     }
-    MP_HIPC(hipMemcpy2DAsync(ctx->km_seed_f, (size_t)ctx->Fcap * 4, init_fine, (size_t)n_fine * 4, (size_t)n_fine * 4, U,
-                             hipMemcpyHostToDevice, s));
+    MP_TRY(upload_2d(ctx, ctx->km_seed_f, (size_t)ctx->Fcap * 4, init_fine, (size_t)n_fine * 4, (size_t)n_fine * 4, U, s));
     if (two)
-        MP_HIPC(hipMemcpy2DAsync(ctx->km_seed_c, (size_t)std::max(ctx->Ccap, 1) * 4, init_coarse, (size_t)n_coarse * 4,
-                                 (size_t)n_coarse * 4, U, hipMemcpyHostToDevice, s));
+        MP_TRY(upload_2d(ctx, ctx->km_seed_c, (size_t)std::max(ctx->Ccap, 1) * 4, init_coarse, (size_t)n_coarse * 4,
+                         (size_t)n_coarse * 4, U, s));
 
     Range r;
     r.Xk = (const uint16_t*)k; r.Xv = (const uint16_t*)v; r.x_unit_rows = n_tokens; r.pt0 = 0; r.n_pts = n_tokens;
@@ -402,6 +444,7 @@ mp_status cluster_kv_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_t
 mp_status set_clustering_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, const int32_t* fine_of_token,
                               int32_t n_fine, const int32_t* coarse_of_fine, int32_t n_coarse, hipStream_t s)
 {
+    MP_TRY(stage_open(ctx));
     const int U = ctx->U;
     const bool two = ctx->cfg.levels == 2;
     MP_HIPC(hipMemcpy2DAsync(ctx->fot, (size_t)ctx->Ncap * 4, fine_of_token, (size_t)n_tokens * 4, (size_t)n_tokens * 4, U,
@@ -413,8 +456,8 @@ mp_status set_clustering_impl(mp_ctx* ctx, const void* k, const void* v, int32_t
     r.blocks.assign(1, BlockPlan{0, n_tokens, 0, n_fine, 0, n_coarse});
     int max_pts, max_kf, max_kc;
     upload_descs(r, ctx->max_blocks, ctx->stage_blocks2, max_pts, max_kf, max_kc);
-    MP_HIPC(hipMemcpyAsync(ctx->blocks_dev + 4 * (size_t)ctx->max_blocks, ctx->stage_blocks2.data(),
-                           ctx->stage_blocks2.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
+    MP_TRY(upload(ctx, ctx->blocks_dev + 4 * (size_t)ctx->max_blocks, ctx->stage_blocks2.data(),
+                  ctx->stage_blocks2.size() * sizeof(int32_t), s));
     const mp_status st = finalize_range(ctx, k, v, n_tokens, 0, n_tokens, ctx->fot, ctx->Ncap, 0, n_fine, 0, n_coarse, 1,
                                         max_kf, false, s);
     if (st != MP_OK) return st;
@@ -458,6 +501,7 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* v_new
                                int32_t n_new_coarse, int32_t refine_iters, int32_t split_iters, uint64_t seed,
                                const int32_t* seeds, hipStream_t s)
 {
+    MP_TRY(stage_open(ctx));
     const int U = ctx->U;
     const bool two = ctx->cfg.levels == 2;
     if (!ctx->updatable) return fail(ctx, MP_ESTATE, "mp_update_clusters: the last block does not fit the update workspace");
@@ -512,11 +556,11 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* v_new
                              (size_t)n_new * row, U, hipMemcpyDeviceToDevice, s));
     // seeds of the new clusters, at their global ids
     if (n_new_fine > 0)
-        MP_HIPC(hipMemcpy2DAsync(ctx->km_seed_f + lb.f1, (size_t)Fcap * 4, seeds + off[0], (size_t)total * 4,
-                                 (size_t)n_new_fine * 4, U, hipMemcpyHostToDevice, s));
+        MP_TRY(upload_2d(ctx, ctx->km_seed_f + lb.f1, (size_t)Fcap * 4, seeds + off[0], (size_t)total * 4,
+                         (size_t)n_new_fine * 4, U, s));
     if (two && n_new_coarse > 0)
-        MP_HIPC(hipMemcpy2DAsync(ctx->km_seed_c + lb.c1, (size_t)Ccap1 * 4, seeds + off[1], (size_t)total * 4,
-                                 (size_t)n_new_coarse * 4, U, hipMemcpyHostToDevice, s));
+        MP_TRY(upload_2d(ctx, ctx->km_seed_c + lb.c1, (size_t)Ccap1 * 4, seeds + off[1], (size_t)total * 4,
+                         (size_t)n_new_coarse * 4, U, s));
 
     // block descriptors: slot 1 = [fine: all points of the last block | coarse], slot 0 (scratch) = appended points / new clusters
     Range r;
@@ -526,14 +570,13 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* v_new
     int max_pts, max_kf, max_kc;
     upload_descs(r, ctx->max_blocks, ctx->stage_blocks2, max_pts, max_kf, max_kc);
     int32_t* bdev_f = ctx->blocks_dev + 4 * (size_t)ctx->max_blocks;
-    MP_HIPC(hipMemcpyAsync(bdev_f, ctx->stage_blocks2.data(), ctx->stage_blocks2.size() * sizeof(int32_t),
-                           hipMemcpyHostToDevice, s));
+    MP_TRY(upload(ctx, bdev_f, ctx->stage_blocks2.data(), ctx->stage_blocks2.size() * sizeof(int32_t), s));
     std::vector<int32_t>& sd = ctx->stage_blocks;
     sd.assign(12, 0);
     sd[0] = nb_old; sd[1] = nb; sd[2] = f0; sd[3] = f1;             // appended points vs all fine centroids
     sd[4] = nb_old; sd[5] = nb; sd[6] = lb.f1; sd[7] = f1;          // new fine centroids seeded from appended points
     sd[8] = lb.f1; sd[9] = f1; sd[10] = lb.c1; sd[11] = c1;         // new coarse centroids seeded from new fine centroids
-    MP_HIPC(hipMemcpyAsync(ctx->blocks_dev, sd.data(), sd.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
+    MP_TRY(upload(ctx, ctx->blocks_dev, sd.data(), sd.size() * sizeof(int32_t), s));
 
     // ---- working fine centroids: the stored key centroids, then the new seeds ----
     hipLaunchKernelGGL(gather1_rows_kernel, dim3(blocks_for((long long)kf_old * 16, 256), U), dim3(256), 0, s,
@@ -585,11 +628,11 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* v_new
 
     if (split) {
         // ---- the last block reached W + alpha tokens: cluster its first W tokens and the rest afresh ----
-        MP_HIPC(hipMemcpy2DAsync(ctx->km_seed_f + f0, (size_t)Fcap * 4, seeds + off[2], (size_t)total * 4,
-                                 (size_t)(cnts[2] + cnts[3]) * 4, U, hipMemcpyHostToDevice, s));
+        MP_TRY(upload_2d(ctx, ctx->km_seed_f + f0, (size_t)Fcap * 4, seeds + off[2], (size_t)total * 4,
+                         (size_t)(cnts[2] + cnts[3]) * 4, U, s));
         if (two)
-            MP_HIPC(hipMemcpy2DAsync(ctx->km_seed_c + c0, (size_t)Ccap1 * 4, seeds + off[4], (size_t)total * 4,
-                                     (size_t)(cnts[4] + cnts[5]) * 4, U, hipMemcpyHostToDevice, s));
+            MP_TRY(upload_2d(ctx, ctx->km_seed_c + c0, (size_t)Ccap1 * 4, seeds + off[4], (size_t)total * 4,
+                             (size_t)(cnts[4] + cnts[5]) * 4, U, s));
         Range r2 = r;
         r2.blocks.clear();
         r2.blocks.push_back(BlockPlan{0, W, f0, f0 + cnts[2], c0, c0 + cnts[4]});

@@ -135,6 +135,13 @@ struct mp_ctx {
 
     // host staging for small uploads (kept alive until the next call that uploads)
     std::vector<int32_t> stage_blocks, stage_blocks2, stage_seed_f, stage_seed_c;
+    // Pinned staging buffer: small host arrays (block descriptors, seed lists) are packed into it
+    // and copied from there, so that the copies are asynchronous and the stream never drains for
+    // them.  pin_ev marks the last such copy; the next call that stages waits for it first.
+    char* pin = nullptr;
+    size_t pin_bytes = 0, pin_used = 0;
+    hipEvent_t pin_ev = nullptr;
+    bool pin_pending = false;
 };
 
 namespace mp {

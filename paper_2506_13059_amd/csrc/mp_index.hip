@@ -232,21 +232,27 @@ __global__ __launch_bounds__(256) void cluster_mean_kernel(const uint16_t* __res
     const uint32_t* Xu = reinterpret_cast<const uint32_t*>(X + (long long)u * x_unit_rows * kHeadDim);
     const int32_t* lp = list ? list + u * list_stride : nullptr;
     double a0 = 0.0, a1 = 0.0;
-    int p = s0;
-    for (; p + 4 <= s1; p += 4) {
-        const long long r0 = lp ? lp[p] : p, r1 = lp ? lp[p + 1] : p + 1, r2 = lp ? lp[p + 2] : p + 2,
-                        r3 = lp ? lp[p + 3] : p + 3;
-        const uint32_t w0 = Xu[r0 * 64 + lane], w1 = Xu[r1 * 64 + lane], w2 = Xu[r2 * 64 + lane],
-                       w3 = Xu[r3 * 64 + lane];
-        a0 += (double)bf16lo_to_f32(w0); a1 += (double)bf16hi_to_f32(w0);
-        a0 += (double)bf16lo_to_f32(w1); a1 += (double)bf16hi_to_f32(w1);
-        a0 += (double)bf16lo_to_f32(w2); a1 += (double)bf16hi_to_f32(w2);
-        a0 += (double)bf16lo_to_f32(w3); a1 += (double)bf16hi_to_f32(w3);
-    }
-    for (; p < s1; ++p) {
-        const long long r0 = lp ? lp[p] : p;
-        const uint32_t w0 = Xu[r0 * 64 + lane];
-        a0 += (double)bf16lo_to_f32(w0); a1 += (double)bf16hi_to_f32(w0);
+    // 64 member indices at a time (one per lane), then their rows eight at a time: the row numbers
+    // reach every lane through a lane broadcast, so that eight row loads are in flight at once while
+    // the additions keep the members' order
+    for (int base = s0; base < s1; base += 64) {
+        const int nm = (s1 - base < 64) ? s1 - base : 64;
+        const int mine = (lane < nm) ? (lp ? lp[base + lane] : base + lane) : 0;
+        for (int m = 0; m < nm; m += 8) {
+            uint32_t w[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const long long r = __builtin_amdgcn_readlane(mine, (m + q) & 63);
+                w[q] = (m + q < nm) ? Xu[r * 64 + lane] : 0u;
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (m + q < nm) {
+                    a0 += (double)bf16lo_to_f32(w[q]);
+                    a1 += (double)bf16hi_to_f32(w[q]);
+                }
+            }
+        }
     }
     const int n = s1 - s0;
     uint32_t outw;
