@@ -78,6 +78,18 @@ def test_cluster_exact_duplicates_take_the_lowest_index():
     ctx.close()
 
 
+def test_cluster_all_points_equal_many_coinciding_centroids():
+    # one distinct key row, 100 centroids: more tied candidates than the exact pass lists per point
+    ctx, K, V = _run_case(1, 2, 1, 500, 4, 1, 100, 0, 0, 0, iters=2, seed=15, distinct_rows=1)
+    ctx.close()
+
+
+def test_cluster_thousands_of_centroids_in_one_block():
+    # 4100 centroids in a single block: few list-building waves, scores of the exact pass not cached
+    ctx, K, V = _run_case(1, 2, 1, 6000, 300, 1, 4100, 0, 0, 0, iters=2, seed=16)
+    ctx.close()
+
+
 def test_cluster_then_decode_end_to_end():
     from tests.gpu_util import compare_decode
     from paper_2506_13059_amd import inputs
