@@ -52,6 +52,8 @@ def main():
     ap.add_argument("--coarse-mult", type=int, default=2, help="coarse budget = mult * key budget")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-online", action="store_true", help="skip the online-generation (cfg4_online) extra")
+    ap.add_argument("--only-online", action="store_true",
+                    help="run only the online-generation workload and print its record (for profiling)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
     args = ap.parse_args()
@@ -66,8 +68,11 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
-    w = inputs.WORKLOADS[args.workload]
     dev = "cuda"
+    if args.only_online:
+        print(json.dumps(online_generation(mp, inputs, dev)))
+        return
+    w = inputs.WORKLOADS[args.workload]
     n_sets = 16
     t0 = time.time()
     data = inputs.make_workload(w, dev, seed=1000 * list(inputs.WORKLOADS).index(args.workload), n_query_sets=n_sets)

@@ -49,7 +49,7 @@ typedef struct {
     int32_t head_dim;      /* must be 128                                                       */
     int32_t max_tokens;    /* capacity: clustered tokens per unit                               */
     int32_t levels;        /* 1 = fine clusters only (Sec. 3.1-3.2), 2 = coarse + fine (Sec. 3.4) */
-    int32_t max_fine;      /* capacity: fine clusters per unit (<= 65536)                       */
+    int32_t max_fine;      /* capacity: fine clusters per unit (<= 8192)                        */
     int32_t max_coarse;    /* capacity: coarse clusters per unit (0 allowed when levels == 1)   */
     int32_t block_w;       /* W of Sec. 3.3: clustering block length; 0 = one block             */
     int32_t block_alpha;   /* alpha of Sec. 3.3: the last block holds alpha .. W+alpha-1 tokens */
