@@ -45,13 +45,24 @@ mp_status fail(mp_ctx* ctx, mp_status st, const char* fmt, ...)
 
 // Rows per workgroup of the value pass for a stream of n rows per unit: large enough that the
 // partials stay a small fraction of the traffic, small enough that there are many workgroups.
-constexpr int kFineChunkRows = 128;   // 4 waves x 32 rows
+// Two workgroups of the value pass are resident per compute unit, 512 on the chip.
+constexpr int kResidentWgs = 512;
 
 int pick_chunk_rows(long long n_rows_per_unit, int n_units)
 {
     int cr = kChunkRowsMin;
     while (cr < 4096 && n_units * ((n_rows_per_unit + cr - 1) / cr) > 8192) cr *= 2;
     return cr;
+}
+
+// Rows per workgroup for the stream of selected keys.  Long chunks (4 strips of 128 rows per wave)
+// spread the prologue and epilogue of a workgroup over more bytes, but only pay off while the launch
+// still has a workgroup for every resident slot; otherwise one strip per wave (measured on cfg3: 2048
+// at key budget 8192 = 512 workgroups, 512 at budget 4096 = 1024 workgroups).
+int pick_main_chunk_rows(int rows_max, int n_units)
+{
+    const long long long_chunks = (long long)n_units * ((rows_max + 2047) / 2048);
+    return long_chunks >= kResidentWgs ? 2048 : kChunkRowsMin;
 }
 
 }  // namespace mp
@@ -148,7 +159,7 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     ctx->tab_rows = (long long)ctx->Fcap + ctx->Ccap;
     ctx->FBcap = c.block_w > 0 ? (int32_t)std::min<long long>(c.max_tokens, 2ll * c.block_w) : c.max_tokens;
     ctx->max_blocks = std::max(4, c.block_w > 0 ? c.max_tokens / c.block_w + 2 : 2);
-    ctx->Pcap = 2 * ceil_div(ctx->Ncap, kChunkRowsMin) + 2 + ceil_div(ctx->Tcap, kChunkRowsMin) +
+    ctx->Pcap = ceil_div(ctx->Ncap, kChunkRowsMin) + 2 + ceil_div(ctx->Tcap, kChunkRowsMin) +
                 ceil_div(ctx->tab_rows, kChunkRowsMin) + 1;
 
     hipError_t e = hipGetDevice(&ctx->device);
@@ -328,7 +339,7 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
     vp.n_units = U;
     vp.scale_log2e = (float)(ctx->scale_d * 1.4426950408889634);
     const int main_max = std::min(key_budget, ctx->n_tokens);
-    const int cr = pick_chunk_rows(std::max(main_max, 1), U);
+    const int cr = kChunkRowsMin;      // centroid terms and tail: short streams
     int ns = 0, chunk0 = 0;
     // order: centroid terms, tail, selected keys -- the longest stream goes last (see the kernel's block mapping)
     if (use_mp) {
@@ -345,21 +356,11 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
         r.chunk_rows = cr; r.row0 = 0; r.n_chunks = ceil_div(n_tail, cr); chunk0 += r.n_chunks;
     }
     if (main_max > 0) {
-        // the selected keys: large chunks first, and the last eighth of the stream in small chunks,
-        // so that the workgroups still running when the grid drains are short ones
-        int bulk = main_max;
-        if (main_max >= 4 * cr) bulk = ((main_max - main_max / 8) / cr) * cr;
-        const int fine = main_max - bulk;
+        const int crm = pick_main_chunk_rows(main_max, U);
         RowSource& r = vp.src[ns++];
         r.K = ctx->Kp; r.V = ctx->Vp; r.unit_rows = ctx->Ncap; r.rows = ctx->rows; r.rows_stride = ctx->Ncap;
-        r.count_dev = ctx->n_rows; r.count_max = bulk; r.scores = nullptr; r.chunk0 = chunk0;
-        r.chunk_rows = cr; r.row0 = 0; r.n_chunks = ceil_div(bulk, cr); chunk0 += r.n_chunks;
-        if (fine > 0) {
-            RowSource& f = vp.src[ns++];
-            f = r;
-            f.count_max = fine; f.chunk0 = chunk0; f.chunk_rows = kFineChunkRows; f.row0 = bulk;
-            f.n_chunks = ceil_div(fine, kFineChunkRows); chunk0 += f.n_chunks;
-        }
+        r.count_dev = ctx->n_rows; r.count_max = main_max; r.scores = nullptr; r.chunk0 = chunk0;
+        r.chunk_rows = crm; r.row0 = 0; r.n_chunks = ceil_div(main_max, crm); chunk0 += r.n_chunks;
     }
     vp.n_sources = ns;
     vp.chunks_per_unit = chunk0;

@@ -191,15 +191,20 @@ __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S
             qhi[h] = qp[8];
         }
         const float scale = p.scale_log2e;
-        for (int j0 = w0; j0 < w1; j0 += kStrip) {
+        // row numbers of a strip: requested one strip ahead, so that a strip starts with one memory
+        // latency (its first rows) instead of two (row numbers, then rows)
+        auto strip_rows = [&](int j0, int& ia, int& ib) {
             int pa = j0 + lane, pb = j0 + 64 + lane;
             pa = pa < end ? pa : end - 1;
             pb = pb < end ? pb : end - 1;
-            int ia = pa, ib = pb;
-            if (rows) {
-                ia = rows[pa];
-                ib = rows[pb];
-            }
+            ia = rows ? rows[pa] : pa;
+            ib = rows ? rows[pb] : pb;
+        };
+        int na, nb;
+        strip_rows(w0, na, nb);
+        for (int j0 = w0; j0 < w1; j0 += kStrip) {
+            const int ia = na, ib = nb;
+            if (j0 + kStrip < w1) strip_rows(j0 + kStrip, na, nb);
             if constexpr (G <= 4) {
                 u32x4 buf[3][8];
                 auto issue = [&](int it, u32x4 (&b)[8]) {
