@@ -99,6 +99,15 @@ CASES = [
          budgets=[(300, 0), (2100, 0)], tail=5),
     dict(name="mha_many_units", B=3, Hq=3, Hkv=3, n=900, modes=30, levels=2, nf=40, nc=5,
          budgets=[(100, 400)], tail=0),
+    dict(name="group2", B=1, Hq=4, Hkv=2, n=1100, modes=40, levels=2, nf=40, nc=5, budgets=[(150, 500)], tail=3),
+    dict(name="group3", B=1, Hq=3, Hkv=1, n=1000, modes=40, levels=1, nf=50, nc=0, budgets=[(200, 0)], tail=0),
+    dict(name="group6", B=1, Hq=6, Hkv=1, n=1000, modes=40, levels=2, nf=50, nc=6, budgets=[(120, 480)], tail=17),
+    dict(name="group7", B=1, Hq=7, Hkv=1, n=1000, modes=40, levels=1, nf=50, nc=0, budgets=[(333, 0)], tail=0),
+    # more entries per level than the scoring kernel keeps in LDS (1024): working arrays in global scratch
+    dict(name="one_level_1300_clusters", B=1, Hq=4, Hkv=1, n=5200, modes=400, levels=1, nf=1300, nc=0,
+         budgets=[(700, 0), (0, 0), (5200, 0)], tail=0, iters=2),
+    dict(name="two_level_1300_candidates", B=1, Hq=4, Hkv=1, n=7800, modes=500, levels=2, nf=2600, nc=40,
+         budgets=[(900, 3900), (300, 7800)], tail=9, iters=2),
 ]
 
 
