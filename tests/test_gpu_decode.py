@@ -205,6 +205,40 @@ def test_tail_in_a_buffer_of_fixed_capacity():
     ctx.close()
 
 
+def test_decode_step_in_a_hip_graph():
+    """A decode step allocates nothing and never waits for the GPU, so it can be captured once and
+    replayed: every replay, with eager work and synchronisations in between, must give the bits of
+    an eager call on the same inputs."""
+    from paper_2506_13059_amd import binding as mp
+    B, Hq, Hkv, n = 2, 8, 2, 2500
+    K, V, q = _mk(B, Hq, Hkv, n, 60, seed=31, softness=0.5, n_sets=4)
+    g = torch.Generator(device="cuda").manual_seed(32)
+    fot = torch.randint(0, 80, (B * Hkv, n), generator=g, device="cuda").to(torch.int32)
+    cof = (torch.arange(80, device="cuda", dtype=torch.int32) // 10)[None].repeat(B * Hkv, 1).contiguous()
+    ctx = mp.MpContext(B, Hq, Hkv, max_tokens=n, levels=2, max_fine=80, max_coarse=8, max_tail=16)
+    ctx.mp_set_clustering(K, V, fot, 80, cof, 8)
+    kt = torch.randn(B, Hkv, 16, 128, generator=g, device="cuda").to(torch.bfloat16)
+    vt = torch.randn(B, Hkv, 16, 128, generator=g, device="cuda").to(torch.bfloat16)
+    q_in = q[0].clone()
+    out = torch.empty_like(q_in)
+    lse = torch.empty(B, Hq, dtype=torch.float32, device="cuda")
+    ctx.mp_decode_attention(q_in, 300, 900, k_tail=kt, v_tail=vt, n_tail=11, out=out, lse=lse)   # warm-up, eager
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ctx.mp_decode_attention(q_in, 300, 900, k_tail=kt, v_tail=vt, n_tail=11, out=out, lse=lse)
+    for s in range(4):
+        q_in.copy_(q[s])
+        graph.replay()
+        torch.cuda.synchronize()
+        got, got_lse = out.clone(), lse.clone()
+        ref_lse = torch.empty_like(lse)
+        ref = ctx.mp_decode_attention(q[s].contiguous(), 300, 900, k_tail=kt, v_tail=vt, n_tail=11, lse=ref_lse)
+        torch.cuda.synchronize()
+        assert torch.equal(got, ref) and torch.equal(got_lse, ref_lse), f"replay {s}"
+    ctx.close()
+
+
 def test_decode_argument_errors():
     from paper_2506_13059_amd import binding as mp
     ctx = mp.MpContext(1, 4, 1, max_tokens=64, levels=1, max_fine=4, max_tail=2)
