@@ -213,6 +213,37 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
                               uint32_t flags, void* out, float* lse, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Library-managed local buffer (Sec. 4 and Sec. 5.1: the newest L to 2L tokens are kept out of the
+ * clusters and attended exactly at every step; every L steps the oldest L of them are appended to
+ * the clusters; a few first "sink" tokens are never clustered).  Optional: callers that keep
+ * their own tail buffer use mp_decode_attention and mp_update_clusters directly.
+ *
+ * mp_local_buffer_init sets the window L, copies n_sink sink tokens and the n_recent newest tokens
+ * (0 <= n_recent < 2L, in sequence order) into the context's buffer.  k_* / v_*: device bf16
+ * [B, Hkv, n, 128], read on the stream, may be NULL when n == 0.  Needs n_sink + 2L <= max_tail.
+ * May be called again to reset the buffer.
+ *
+ * mp_decode_step is one decoding step of a generation loop:
+ *   1. the new token's key and value (device bf16 [B, Hkv, 1, 128]) join the buffer;
+ *   2. mp_decode_attention with the buffer (sinks, then the recent tokens including the new one) as
+ *      the tail;
+ *   3. when the buffer holds 2L recent tokens, mp_update_clusters with the oldest L of them
+ *      (n_new_fine, n_new_coarse, refine_iters, split_iters, seed, seeds as for that call; `seeds`
+ *      is read only in such a step), and the newer L move to the front.
+ * Whether a step will refresh is known beforehand: n_recent + 1 == 2L (mp_local_buffer_size).
+ * Errors: those of the two calls it is made of; MP_ESTATE without an index or a local buffer.  If
+ * the update of step 3 fails (e.g. MP_ECAPACITY), `out` is valid, the error is returned, and the
+ * next call retries the update before anything else.
+ * ------------------------------------------------------------------------------------------- */
+mp_status mp_local_buffer_init(mp_ctx* ctx, int32_t window, const void* k_sink, const void* v_sink, int32_t n_sink,
+                               const void* k_recent, const void* v_recent, int32_t n_recent, void* stream);
+mp_status mp_local_buffer_size(const mp_ctx* ctx, int32_t* window, int32_t* n_sink, int32_t* n_recent);
+mp_status mp_decode_step(mp_ctx* ctx, const void* q, const void* k_new, const void* v_new, int32_t key_budget,
+                         int32_t coarse_budget, uint32_t flags, int32_t n_new_fine, int32_t n_new_coarse,
+                         int32_t refine_iters, int32_t split_iters, uint64_t seed, const int32_t* seeds, void* out,
+                         float* lse, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Stage timing (for benchmarks).  While enabled, mp_decode_attention records HIP events on the
  * call's own stream before and after each of its launches.  mp_get_stage_timing waits for the last
  * timed call and writes its four durations in milliseconds:

@@ -21,7 +21,7 @@ EXPORTS = [
     "mp_create", "mp_destroy", "mp_last_error", "mp_device_bytes", "mp_plan_blocks", "mp_cluster_kv",
     "mp_set_clustering", "mp_update_clusters", "mp_decode_attention", "mp_get_sizes", "mp_get_assignments",
     "mp_get_centroids", "mp_get_selection", "mp_get_counters", "mp_get_layout", "mp_dense_workspace_bytes",
-    "mp_dense_attention", "mp_version", "mp_enable_stage_timing", "mp_get_stage_timing", "mp_update_seed_counts",
+    "mp_dense_attention", "mp_version", "mp_enable_stage_timing", "mp_get_stage_timing", "mp_update_seed_counts", "mp_local_buffer_init", "mp_local_buffer_size", "mp_decode_step",
 ]
 
 
@@ -64,6 +64,9 @@ def lib():
         L.mp_update_clusters.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, u64, vp, vp]
         L.mp_decode_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, u32, vp, vp, vp]
         L.mp_update_seed_counts.argtypes = [vp, i32, i32, i32, vp]
+        L.mp_local_buffer_init.argtypes = [vp, i32, vp, vp, i32, vp, vp, i32, vp]
+        L.mp_local_buffer_size.argtypes = [vp, vp, vp, vp]
+        L.mp_decode_step.argtypes = [vp, vp, vp, vp, i32, i32, u32, i32, i32, i32, i32, u64, vp, vp, vp, vp]
         L.mp_update_seed_counts.restype = i32
         L.mp_enable_stage_timing.argtypes = [vp, i32]
         L.mp_get_stage_timing.argtypes = [vp, vp]
@@ -182,6 +185,31 @@ class MpContext:
         st = lib().mp_update_clusters(self.h, _ptr(k_new), _ptr(v_new), n_new, n_new_fine, n_new_coarse,
                                       refine_iters, split_iters, seed, s_ptr, _stream())
         _check(st, self.h)
+
+    def mp_local_buffer_init(self, window, k_sink=None, v_sink=None, k_recent=None, v_recent=None):
+        n_sink = 0 if k_sink is None else k_sink.shape[2]
+        n_recent = 0 if k_recent is None else k_recent.shape[2]
+        st = lib().mp_local_buffer_init(self.h, window, _ptr(k_sink), _ptr(v_sink), n_sink, _ptr(k_recent),
+                                        _ptr(v_recent), n_recent, _stream())
+        _check(st, self.h)
+
+    def mp_local_buffer_size(self):
+        buf = (C.c_int32 * 3)()
+        base = C.addressof(buf)
+        st = lib().mp_local_buffer_size(self.h, C.c_void_p(base), C.c_void_p(base + 4), C.c_void_p(base + 8))
+        _check(st, self.h)
+        return dict(window=buf[0], n_sink=buf[1], n_recent=buf[2])
+
+    def mp_decode_step(self, q, k_new, v_new, key_budget, coarse_budget=0, n_new_fine=0, n_new_coarse=0,
+                       refine_iters=3, split_iters=10, seed=0, seeds=None, out=None, lse=None, flags=0):
+        if out is None:
+            out = torch.empty_like(q)
+        s_keep, s_ptr = _host_i32(seeds)
+        st = lib().mp_decode_step(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), key_budget, coarse_budget, flags,
+                                  n_new_fine, n_new_coarse, refine_iters, split_iters, seed, s_ptr, _ptr(out),
+                                  _ptr(lse), _stream())
+        _check(st, self.h)
+        return out
 
     def mp_update_seed_counts(self, n_new, n_new_fine, n_new_coarse=0):
         buf = (C.c_int32 * 6)()

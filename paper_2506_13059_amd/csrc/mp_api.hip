@@ -180,6 +180,10 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     A(cand, U * F); A(n_cand, U); A(unprom_lse, U * G); A(rows, U * N); A(n_rows, U);
     A(mp_rows, U * T); A(mp_scores, U * T * G); A(n_mp, U); A(counters, U * 4);
     A(partials, U * (size_t)ctx->Pcap * G * kPartStride);
+    if (ctx->Tcap > 0) {
+        const size_t Tc = ctx->Tcap;
+        A(Kt, U * Tc * D); A(Vt, U * Tc * D); A(Kts, U * Tc * D); A(Vts, U * Tc * D);
+    }
 #undef A
     if (e == hipSuccess) {
         ctx->pin_bytes = 1u << 20;
@@ -371,6 +375,101 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
     if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[4], s));
     ctx->timed_levels = two ? 2 : 1;
     ctx->decoded = true;
+    return MP_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Library-managed local buffer (Sec. 4: the newest L .. 2L tokens stay unclustered and are attended
+// exactly; every L steps the oldest L of them go into the clusters) and sink tokens
+// ------------------------------------------------------------------------------------------------
+mp_status mp_local_buffer_init(mp_ctx* ctx, int32_t window, const void* k_sink, const void* v_sink, int32_t n_sink,
+                               const void* k_recent, const void* v_recent, int32_t n_recent, void* stream)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_local_buffer_init: null context");
+    if (window < 1 || n_sink < 0 || n_recent < 0 || n_recent >= 2 * window)
+        return fail(ctx, MP_EINVAL, "mp_local_buffer_init: need window >= 1, n_sink >= 0, 0 <= n_recent < 2 * window");
+    if ((n_sink > 0 && (!k_sink || !v_sink)) || (n_recent > 0 && (!k_recent || !v_recent)))
+        return fail(ctx, MP_EINVAL, "mp_local_buffer_init: null rows with a positive count");
+    if ((long long)n_sink + 2ll * window > ctx->Tcap)
+        return fail(ctx, MP_ECAPACITY, "mp_local_buffer_init: n_sink + 2 * window = %lld > max_tail %d", (long long)n_sink + 2ll * window, ctx->Tcap);
+    hipStream_t s = (hipStream_t)stream;
+    const size_t row = kHeadDimHost * sizeof(uint16_t), pitch = (size_t)ctx->Tcap * row;
+    if (n_sink > 0) {
+        MP_HIP(ctx, hipMemcpy2DAsync(ctx->Kt, pitch, k_sink, n_sink * row, n_sink * row, ctx->U, hipMemcpyDeviceToDevice, s));
+        MP_HIP(ctx, hipMemcpy2DAsync(ctx->Vt, pitch, v_sink, n_sink * row, n_sink * row, ctx->U, hipMemcpyDeviceToDevice, s));
+    }
+    if (n_recent > 0) {
+        MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Kt + n_sink * row, pitch, k_recent, n_recent * row, n_recent * row, ctx->U, hipMemcpyDeviceToDevice, s));
+        MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Vt + n_sink * row, pitch, v_recent, n_recent * row, n_recent * row, ctx->U, hipMemcpyDeviceToDevice, s));
+    }
+    ctx->lb_window = window;
+    ctx->lb_sink = n_sink;
+    ctx->lb_recent = n_recent;
+    return MP_OK;
+}
+
+mp_status mp_local_buffer_size(const mp_ctx* ctx, int32_t* window, int32_t* n_sink, int32_t* n_recent)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_local_buffer_size: null context");
+    if (ctx->lb_window == 0) return fail(const_cast<mp_ctx*>(ctx), MP_ESTATE, "mp_local_buffer_size: no local buffer (call mp_local_buffer_init first)");
+    if (window) *window = ctx->lb_window;
+    if (n_sink) *n_sink = ctx->lb_sink;
+    if (n_recent) *n_recent = ctx->lb_recent;
+    return MP_OK;
+}
+
+namespace {
+// The oldest L tokens of the local buffer go into the clusters; the newer L move down.
+mp_status refresh_local_buffer(mp_ctx* ctx, int32_t n_new_fine, int32_t n_new_coarse, int32_t refine_iters,
+                               int32_t split_iters, uint64_t seed, const int32_t* seeds, hipStream_t s)
+{
+    const int L = ctx->lb_window, ns = ctx->lb_sink;
+    if (n_new_fine < 0 || n_new_fine > L || refine_iters < 0 || split_iters < 1)
+        return fail(ctx, MP_EINVAL, "mp_decode_step: bad update counts n_new_fine=%d refine=%d split=%d", n_new_fine, refine_iters, split_iters);
+    if (ctx->cfg.levels == 2 && (n_new_coarse < 0 || n_new_coarse > n_new_fine))
+        return fail(ctx, MP_EINVAL, "mp_decode_step: n_new_coarse must be in [0, n_new_fine]");
+    const size_t row = kHeadDimHost * sizeof(uint16_t), pitch = (size_t)ctx->Tcap * row;
+    MP_HIP(ctx, hipMemcpy2DAsync(ctx->Kts, L * row, (char*)ctx->Kt + ns * row, pitch, L * row, ctx->U, hipMemcpyDeviceToDevice, s));
+    MP_HIP(ctx, hipMemcpy2DAsync(ctx->Vts, L * row, (char*)ctx->Vt + ns * row, pitch, L * row, ctx->U, hipMemcpyDeviceToDevice, s));
+    const mp_status st = update_clusters_impl(ctx, ctx->Kts, ctx->Vts, L, n_new_fine, ctx->cfg.levels == 2 ? n_new_coarse : 0,
+                                              refine_iters, split_iters, seed, seeds, s);
+    if (st != MP_OK) return st;
+    MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Kt + ns * row, pitch, (char*)ctx->Kt + (ns + L) * row, pitch, L * row, ctx->U, hipMemcpyDeviceToDevice, s));
+    MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Vt + ns * row, pitch, (char*)ctx->Vt + (ns + L) * row, pitch, L * row, ctx->U, hipMemcpyDeviceToDevice, s));
+    ctx->lb_recent = L;
+    return MP_OK;
+}
+}  // namespace
+
+mp_status mp_decode_step(mp_ctx* ctx, const void* q, const void* k_new, const void* v_new, int32_t key_budget,
+                         int32_t coarse_budget, uint32_t flags, int32_t n_new_fine, int32_t n_new_coarse,
+                         int32_t refine_iters, int32_t split_iters, uint64_t seed, const int32_t* seeds, void* out,
+                         float* lse, void* stream)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_decode_step: null context");
+    if (!ctx->has_index) return fail(ctx, MP_ESTATE, "mp_decode_step: no index yet (call mp_cluster_kv first)");
+    if (ctx->lb_window == 0) return fail(ctx, MP_ESTATE, "mp_decode_step: no local buffer (call mp_local_buffer_init first)");
+    if (!q || !k_new || !v_new || !out) return fail(ctx, MP_EINVAL, "mp_decode_step: null q/k_new/v_new/out");
+    hipStream_t s = (hipStream_t)stream;
+    const int L = ctx->lb_window, ns = ctx->lb_sink;
+    if (ctx->lb_recent >= 2 * L) {      // a refresh that failed in an earlier call (e.g. capacity) is due first
+        const mp_status st = refresh_local_buffer(ctx, n_new_fine, n_new_coarse, refine_iters, split_iters, seed, seeds, s);
+        if (st != MP_OK) return st;
+    }
+    const size_t row = kHeadDimHost * sizeof(uint16_t), pitch = (size_t)ctx->Tcap * row;
+    const size_t at = (size_t)(ns + ctx->lb_recent) * row;
+    // the new token joins the buffer first: a decoding step attends to its own key and value
+    MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Kt + at, pitch, k_new, row, row, ctx->U, hipMemcpyDeviceToDevice, s));
+    MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Vt + at, pitch, v_new, row, row, ctx->U, hipMemcpyDeviceToDevice, s));
+    ctx->lb_recent += 1;
+    const mp_status st = mp_decode_attention(ctx, q, ctx->Kt, ctx->Vt, ns + ctx->lb_recent, ctx->Tcap, key_budget,
+                                             coarse_budget, flags, out, lse, stream);
+    if (st != MP_OK) {
+        ctx->lb_recent -= 1;
+        return st;
+    }
+    if (ctx->lb_recent == 2 * L)
+        return refresh_local_buffer(ctx, n_new_fine, n_new_coarse, refine_iters, split_iters, seed, seeds, s);
     return MP_OK;
 }
 

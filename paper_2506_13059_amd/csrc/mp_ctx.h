@@ -121,6 +121,14 @@ struct mp_ctx {
     float* partials = nullptr;     // [U, Pcap, G, 132]
     int32_t Pcap = 0;
 
+    // library-managed local buffer (mp_local_buffer_init / mp_decode_step): rows [0, lb_sink) are sink
+    // tokens, rows [lb_sink, lb_sink + lb_recent) the newest tokens in sequence order
+    uint16_t* Kt = nullptr;        // bf16 [U, Tcap, 128]
+    uint16_t* Vt = nullptr;
+    uint16_t* Kts = nullptr;       // bf16 [U, Tcap, 128] staging: the rows handed to the cluster update, packed
+    uint16_t* Vts = nullptr;
+    int32_t lb_window = 0, lb_sink = 0, lb_recent = 0;
+
     // ---- current index (host copies of sizes) ----
     bool has_index = false;
     bool decoded = false;
