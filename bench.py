@@ -201,54 +201,68 @@ def main():
 
 
 def online_generation(mp, inputs, dev):
-    """cfg4_online: an 8K-token index grows by 16384 generated tokens.  Every token is one decode step
-    over the index plus the tail of tokens appended since the last refresh; every 128 tokens the
-    tail goes into the index with mp_update_clusters (Sec. 3.3).  Reports GPU time per token."""
+    """cfg4_online: an 8K-token index grows by 16384 generated tokens through mp_decode_step: every
+    token is one decode step over the index plus the library's local buffer (10 sink tokens and the
+    newest 128 .. 255 tokens, attended exactly); whenever the buffer holds 256 recent tokens the
+    oldest 128 go into the index with the online cluster update (Sec. 3.3, Sec. 4, Sec. 5.1).
+    Reports GPU time per token."""
     import torch
     w = inputs.WORKLOADS["cfg4_online"]
-    every, rounds = w.update_every, w.gen_tokens // w.update_every
+    L, n_sink = w.update_every, 10
+    rounds = w.gen_tokens // L
     n_max = w.context + w.gen_tokens
     max_fine = w.n_fine + rounds * w.new_fine_per_update
     max_coarse = w.n_coarse + rounds * w.new_coarse_per_update
     seed = 1000 * list(inputs.WORKLOADS).index(w.name)
     data = inputs.make_workload(w, dev, seed=seed, n_query_sets=16)
     ctx = mp.MpContext(w.batch, w.n_q_heads, w.n_kv_heads, max_tokens=n_max, levels=w.levels, max_fine=max_fine,
-                       max_coarse=max_coarse, block_w=w.block_w, block_alpha=w.block_alpha, max_tail=every)
+                       max_coarse=max_coarse, block_w=w.block_w, block_alpha=w.block_alpha, max_tail=n_sink + 2 * L)
     ctx.mp_cluster_kv(data["K"], data["V"], w.n_fine, w.n_coarse, iters=w.kmeans_iters, init_fine=data["init_fine"],
                       init_coarse=data["init_coarse"])
     Q, centers = data["q"], data["centers"]
+    shape = (w.batch, w.n_kv_heads, -1, 128)
+    ks, vs = (t.view(shape) for t in inputs.draw_tokens(centers, n_sink, seed + 50))
+    kr, vr = (t.view(shape) for t in inputs.draw_tokens(centers, L, seed + 51))
+    ctx.mp_local_buffer_init(L, ks.contiguous(), vs.contiguous(), kr.contiguous(), vr.contiguous())
     out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.bfloat16, device=dev)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    dec_ms = upd_ms = 0.0
+    plain_ms = refresh_ms = 0.0
     n = w.context
     torch.cuda.synchronize()
     t0 = time.time()
     for r in range(rounds):
         centers = inputs.drift_modes(centers, seed + 100 + r)
-        Kn, Vn = inputs.draw_tokens(centers, every, seed + 200 + r)
-        Kn, Vn = Kn.view(w.batch, w.n_kv_heads, every, 128), Vn.view(w.batch, w.n_kv_heads, every, 128)
+        Kn, Vn = inputs.draw_tokens(centers, L, seed + 200 + r)
+        Kn, Vn = Kn.view(shape), Vn.view(shape)
+        rows = [(Kn[:, :, i:i + 1].contiguous(), Vn[:, :, i:i + 1].contiguous()) for i in range(L)]
         kb = n // 8
+        args = dict(n_new_fine=w.new_fine_per_update, n_new_coarse=w.new_coarse_per_update, refine_iters=w.refine_iters,
+                    split_iters=w.kmeans_iters, seed=seed + 300 + r, out=out)
         ev[0].record()
-        for i in range(every):      # token i sees the i tokens generated since the last refresh as tail
-            ctx.mp_decode_attention(Q[i % 16], kb, 2 * kb, k_tail=Kn, v_tail=Vn, n_tail=i, out=out)
+        for i in range(L - 1):      # the buffer grows from 128 to 255 recent tokens
+            ctx.mp_decode_step(Q[i % 16], rows[i][0], rows[i][1], kb, 2 * kb, **args)
         ev[1].record()
-        ctx.mp_update_clusters(Kn, Vn, w.new_fine_per_update, w.new_coarse_per_update, refine_iters=w.refine_iters,
-                               split_iters=w.kmeans_iters, seed=seed + 300 + r)
+        ctx.mp_decode_step(Q[(L - 1) % 16], rows[L - 1][0], rows[L - 1][1], kb, 2 * kb, **args)   # decode + refresh
         ev[2].record()
         torch.cuda.synchronize()
-        dec_ms += ev[0].elapsed_time(ev[1])
-        upd_ms += ev[1].elapsed_time(ev[2])
-        n += every
+        plain_ms += ev[0].elapsed_time(ev[1])
+        refresh_ms += ev[1].elapsed_time(ev[2])
+        n += L
     wall = time.time() - t0
     sizes = ctx.mp_get_sizes()
+    assert sizes["n_tokens"] == n and ctx.mp_local_buffer_size()["n_recent"] == L
     ctx.close()
+    decode_us = plain_ms * 1e3 / (rounds * (L - 1))                 # per step without refresh
+    update_us = refresh_ms * 1e3 / rounds - decode_us               # the refresh inside the 128th step
+    total_us = (plain_ms + refresh_ms) * 1e3 / w.gen_tokens
     return {"workload": w.name, "batch": w.batch, "tokens_generated": w.gen_tokens, "context": [w.context, n],
-            "refresh_every": every, "key_budget": "context/8", "final_sizes": sizes,
-            "decode_us_per_token": round(dec_ms * 1e3 / w.gen_tokens, 2),
-            "update_us_per_refresh": round(upd_ms * 1e3 / rounds, 1),
-            "update_us_per_token": round(upd_ms * 1e3 / w.gen_tokens, 2),
-            "total_us_per_token": round((dec_ms + upd_ms) * 1e3 / w.gen_tokens, 2),
-            "update_share": round(upd_ms / (dec_ms + upd_ms), 4),
+            "local_buffer": f"{n_sink} sink + {L}..{2 * L - 1} recent tokens", "refresh_every": L,
+            "key_budget": "context/8", "final_sizes": sizes,
+            "decode_us_per_token": round(decode_us, 2),
+            "update_us_per_refresh": round(update_us, 1),
+            "update_us_per_token": round(update_us / L, 2),
+            "total_us_per_token": round(total_us, 2),
+            "update_share": round(update_us / L / total_us, 4),
             "wall_us_per_token_incl_input_generation": round(wall * 1e6 / w.gen_tokens, 1)}
 
 

@@ -456,11 +456,8 @@ mp_status mp_decode_step(mp_ctx* ctx, const void* q, const void* k_new, const vo
         const mp_status st = refresh_local_buffer(ctx, n_new_fine, n_new_coarse, refine_iters, split_iters, seed, seeds, s);
         if (st != MP_OK) return st;
     }
-    const size_t row = kHeadDimHost * sizeof(uint16_t), pitch = (size_t)ctx->Tcap * row;
-    const size_t at = (size_t)(ns + ctx->lb_recent) * row;
     // the new token joins the buffer first: a decoding step attends to its own key and value
-    MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Kt + at, pitch, k_new, row, row, ctx->U, hipMemcpyDeviceToDevice, s));
-    MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Vt + at, pitch, v_new, row, row, ctx->U, hipMemcpyDeviceToDevice, s));
+    MP_HIP(ctx, mp::launch_append_row(k_new, v_new, ctx->U, ctx->Kt, ctx->Vt, ctx->Tcap, ns + ctx->lb_recent, s));
     ctx->lb_recent += 1;
     const mp_status st = mp_decode_attention(ctx, q, ctx->Kt, ctx->Vt, ns + ctx->lb_recent, ctx->Tcap, key_budget,
                                              coarse_budget, flags, out, lse, stream);

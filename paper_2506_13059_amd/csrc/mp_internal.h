@@ -104,6 +104,9 @@ size_t score_smem_bytes(int G, int cap);
 // Index construction helpers (member lists, gathers, per-cluster means)
 // ------------------------------------------------------------------------------------------------
 hipError_t launch_fill_i32(int32_t* p, long long n, int32_t v, hipStream_t s);
+// dstK[u][row] = srcK[u], dstV[u][row] = srcV[u] for bf16 rows of 128 (src: [U, 128])
+hipError_t launch_append_row(const void* srcK, const void* srcV, int U, void* dstK, void* dstV, long long dst_unit_rows,
+                             int row, hipStream_t s);
 // Nearest-centroid assignment (fp64 definition, lowest index among equal distances) of the points of
 // nb blocks per unit.  blocks_dev: int32 [nb][4] = {first point, end point, first centroid, end
 // centroid}; assign[u][t] receives the centroid row of point t.  amb_list [U, list_stride] (at least
