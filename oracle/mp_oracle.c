@@ -136,8 +136,14 @@ static double lse_weighted(const double *x, const double *w, int m)
  *   mp_terms == 0 drops the Eq. 2 terms (sparse attention over the retrieved keys only, the
  *   comparison method of Sec. 5.1).
  *
+ * Lookup query (Sec. 3.1, last paragraph, and Sec. 4): when the clusters were formed on keys
+ * rotated to a fixed relative position, the centroid comparison uses a query rotated to the
+ * matching fixed position.  ql takes the place of q in every centroid logit l[h,.] (steps 1, 3 and
+ * the Eq. 2 terms of step 5, which reuse the logits of the lookup); the exact part of step 5 uses
+ * q and the stored keys.  ql == q gives the plain method.
+ *
  * Inputs (fp64, row-major):
- *   q [G,d]; K,V [n,d] clustered tokens in sequence order; fine_of_token [n];
+ *   q, ql [G,d]; K,V [n,d] clustered tokens in sequence order; fine_of_token [n];
  *   Kc_f,Vc_f [Cf,d], N_f [Cf]; coarse_of_fine [Cf], Kc_c,Vc_c [Cc,d], N_c [Cc] (levels==2);
  *   Kx,Vx [nx,d] tokens that are always attended exactly (local buffer, sink tokens).
  * Outputs:
@@ -145,7 +151,7 @@ static double lse_weighted(const double *x, const double *w, int m)
  *   r_c [Cc], r_f [Cf] (NaN where the cluster did not take part), n_sel_keys (may be NULL).
  * Returns 0, or -1 if N_f / N_c disagree with fine_of_token / coarse_of_fine.
  * ------------------------------------------------------------------------------------------- */
-int mpo_decode_unit(const double *q, int G, int d, double scale,
+int mpo_decode_unit(const double *q, const double *ql, int G, int d, double scale,
                     const double *K, const double *V, int n, const int32_t *fine_of_token,
                     int Cf, const double *Kc_f, const double *Vc_f, const int32_t *N_f,
                     int levels, int Cc, const int32_t *coarse_of_fine,
@@ -202,7 +208,7 @@ int mpo_decode_unit(const double *q, int G, int d, double scale,
         for (int h = 0; h < G; ++h) {
             for (int i = 0; i < m; ++i) {
                 int c = ids[i];
-                lc[(size_t)h * Cc + c] = scale * dot(q + (size_t)h * d, Kc_c + (size_t)c * d, d);
+                lc[(size_t)h * Cc + c] = scale * dot(ql + (size_t)h * d, Kc_c + (size_t)c * d, d);
                 tx[i] = lc[(size_t)h * Cc + c];
                 tw[i] = (double)N_c[c];
             }
@@ -229,7 +235,7 @@ int mpo_decode_unit(const double *q, int G, int d, double scale,
         int m = 0;
         for (int i = 0; i < mF; ++i) {
             int f = ids[i];
-            lf[(size_t)h * Cf + f] = scale * dot(q + (size_t)h * d, Kc_f + (size_t)f * d, d);
+            lf[(size_t)h * Cf + f] = scale * dot(ql + (size_t)h * d, Kc_f + (size_t)f * d, d);
             tx[m] = lf[(size_t)h * Cf + f];
             tw[m] = (double)N_f[f];
             ++m;
@@ -329,7 +335,7 @@ int mpo_decode_batch(int U, const double *q, int G, int d, double scale,
     for (int u = 0; u < U; ++u) {
         size_t cf = (size_t)Cf, cc = (size_t)(Cc > 0 ? Cc : 0), dd = (size_t)d;
         int rc = mpo_decode_unit(
-            q + u * (size_t)G * dd, G, d, scale, K + u * (size_t)n * dd, V + u * (size_t)n * dd, n,
+            q + u * (size_t)G * dd, q + u * (size_t)G * dd, G, d, scale, K + u * (size_t)n * dd, V + u * (size_t)n * dd, n,
             fine_of_token + u * (size_t)n, Cf, Kc_f + u * cf * dd, Vc_f + u * cf * dd, N_f + u * cf,
             levels, Cc, levels == 2 ? coarse_of_fine + u * cf : NULL,
             levels == 2 ? Kc_c + u * cc * dd : NULL, levels == 2 ? Vc_c + u * cc * dd : NULL,

@@ -95,14 +95,17 @@ def full_attention(q, K, V, scale):
     return out, lse
 
 
-def decode_unit(q, cl, key_budget, coarse_budget=0, Kx=None, Vx=None, scale=None, mp_terms=True):
+def decode_unit(q, cl, key_budget, coarse_budget=0, Kx=None, Vx=None, scale=None, mp_terms=True, q_lookup=None):
     """One Multipole Attention decode step for one unit (Eq. 1, Eq. 2, Sec. 3.4).
 
     ``cl`` is a clustering dict as produced by :func:`cluster_unit` or
-    :func:`clustering_from_assignment`.  Returns a dict with out, lse, promising, selected, r_c,
-    r_f, n_sel_keys.
+    :func:`clustering_from_assignment`.  ``q_lookup`` (default: q) is the query used against the
+    centroids when the clusters were formed on lookup keys (Sec. 3.1, last paragraph).  Returns a
+    dict with out, lse, promising, selected, r_c, r_f, n_sel_keys.
     """
     q = _f64(q)
+    ql = q if q_lookup is None else _f64(q_lookup)
+    assert ql.shape == q.shape
     G, d = q.shape
     if scale is None:
         scale = 1.0 / np.sqrt(d)
@@ -129,7 +132,7 @@ def decode_unit(q, cl, key_budget, coarse_budget=0, Kx=None, Vx=None, scale=None
     r_f = np.full(max(Cf, 1), np.nan)
     nsel = C.c_int64(0)
     rc = lib().mpo_decode_unit(
-        _d(q), C.c_int(G), C.c_int(d), C.c_double(scale), _d(K), _d(V), C.c_int(n), _i(fot),
+        _d(q), _d(ql), C.c_int(G), C.c_int(d), C.c_double(scale), _d(K), _d(V), C.c_int(n), _i(fot),
         C.c_int(Cf), _d(Kc_f), _d(Vc_f), _i(N_f), C.c_int(levels), C.c_int(Cc), _i(cof), _d(Kc_c), _d(Vc_c),
         _i(N_c), _d(Kx), _d(Vx), C.c_int(nx), C.c_int64(int(key_budget)), C.c_int64(int(coarse_budget)),
         C.c_int(1 if mp_terms else 0), _d(out), _d(lse), _b(promising), _b(selected), _d(r_c), _d(r_f),
@@ -269,29 +272,37 @@ def _concat_blocks(K, V, levels, blocks, parts):
     return cl
 
 
-def cluster_unit(K, V, blocks, init_fine, init_coarse, iters, levels):
+def cluster_unit(K, V, blocks, init_fine, init_coarse, iters, levels, K_lookup=None):
     """Build the clustered index of one unit.
 
     blocks: from :func:`plan_blocks`.  init_fine: int32 [n_fine], block-local token indices of the
     seeds, laid out block after block; init_coarse: int32 [n_coarse], block-local fine-cluster
-    indices of the coarse seeds (ignored for one level).
+    indices of the coarse seeds (ignored for one level).  K_lookup: the keys the clusters are
+    formed on and the key centroids are means of (Sec. 3.1, last paragraph: keys rotated to a
+    fixed relative position); K itself is then only attended exactly.  Default: K.
     """
     K, V = _f64(K), _f64(V)
+    KL = K if K_lookup is None else _f64(K_lookup)
+    assert KL.shape == K.shape
     parts = []
     for b in blocks:
-        Kb, Vb = K[b["t0"]:b["t1"]], V[b["t0"]:b["t1"]]
+        Kb, Vb = KL[b["t0"]:b["t1"]], V[b["t0"]:b["t1"]]
         fi = _i32(init_fine[b["f0"]:b["f1"]])
         ci = _i32(init_coarse[b["c0"]:b["c1"]]) if levels == 2 else None
         parts.append(cluster_block(Kb, Vb, fi, ci, iters, levels))
-    return _concat_blocks(K, V, levels, blocks, parts)
+    cl = _concat_blocks(K, V, levels, blocks, parts)
+    if K_lookup is not None:
+        cl["KL"] = KL
+    return cl
 
 
-def clustering_from_assignment(K, V, fine_of_token, n_fine, coarse_of_fine=None, n_coarse=0):
+def clustering_from_assignment(K, V, fine_of_token, n_fine, coarse_of_fine=None, n_coarse=0, K_lookup=None):
     """Stored tables for a given assignment (single block, ids used as given): centroid = bf16(mean
-    of members); empty clusters get zero centroids and N = 0."""
+    of members); empty clusters get zero centroids and N = 0.  K_lookup as in :func:`cluster_unit`."""
     K, V = _f64(K), _f64(V)
+    KL = K if K_lookup is None else _f64(K_lookup)
     fot = _i32(fine_of_token)
-    Sk, N_f = member_sums(K, fot, n_fine)
+    Sk, N_f = member_sums(KL, fot, n_fine)
     Sv, _ = member_sums(V, fot, n_fine)
     cl = dict(K=K, V=V, levels=1 if coarse_of_fine is None else 2, fine_of_token=fot,
               Kc_f=_mean_bf16(Sk, N_f), Vc_f=_mean_bf16(Sv, N_f), N_f=N_f,
@@ -299,9 +310,11 @@ def clustering_from_assignment(K, V, fine_of_token, n_fine, coarse_of_fine=None,
     if coarse_of_fine is not None:
         cof = _i32(coarse_of_fine)
         ac = cof[fot]
-        Skc, N_c = member_sums(K, ac, n_coarse)
+        Skc, N_c = member_sums(KL, ac, n_coarse)
         Svc, _ = member_sums(V, ac, n_coarse)
         cl.update(coarse_of_fine=cof, Kc_c=_mean_bf16(Skc, N_c), Vc_c=_mean_bf16(Svc, N_c), N_c=N_c)
+    if K_lookup is not None:
+        cl["KL"] = KL
     return cl
 
 
@@ -332,13 +345,15 @@ def update_seed_counts(blocks, n_new, n_new_fine, n_new_coarse, block_w, block_a
     return counts
 
 
-def _replace_last_block(cl, K, V, blocks, parts):
+def _replace_last_block(cl, K, V, blocks, parts, KL=None):
     """New clustering dict: all blocks but the last as they are, the last one replaced by `parts`
     (one or two finalized blocks whose ranges are blocks[-len(parts):])."""
     levels = int(cl["levels"])
     old_last = cl["blocks"][-1]
     t0, f0, c0 = old_last["t0"], old_last["f0"], old_last["c0"]
     out = dict(K=K, V=V, levels=levels, blocks=[dict(b) for b in blocks])
+    if KL is not None:
+        out["KL"] = KL
     fot = np.concatenate([cl["fine_of_token"][:t0]] +
                          [p["fine_of_token"] + b["f0"] for b, p in zip(blocks[-len(parts):], parts)]).astype(np.int32)
     out["fine_of_token"] = fot
@@ -354,10 +369,15 @@ def _replace_last_block(cl, K, V, blocks, parts):
 
 
 def update_unit(cl, K_new, V_new, n_new_fine, n_new_coarse, seeds, refine_iters, block_w, block_alpha,
-                split_iters=10):
+                split_iters=10, K_new_lookup=None):
     """Apply one online update to the clustering dict `cl` of a unit; returns the new dict.
-    seeds: int32 list laid out as described by :func:`update_seed_counts`."""
+    seeds: int32 list laid out as described by :func:`update_seed_counts`.  K_new_lookup: lookup
+    keys of the appended tokens, required iff the index was built on lookup keys; all clustering
+    arithmetic below then runs on lookup keys, K_new is only stored."""
     K_new, V_new = _f64(K_new), _f64(V_new)
+    has_lookup = "KL" in cl
+    assert has_lookup == (K_new_lookup is not None)
+    X_new = _f64(K_new_lookup) if has_lookup else K_new
     levels = int(cl["levels"])
     blocks = [dict(b) for b in cl["blocks"]]
     b = blocks[-1]
@@ -370,23 +390,24 @@ def update_unit(cl, K_new, V_new, n_new_fine, n_new_coarse, seeds, refine_iters,
     sd = [seeds[cuts[i]:cuts[i + 1]] for i in range(6)]
     K = np.concatenate([cl["K"], K_new])
     V = np.concatenate([cl["V"], V_new])
-    Kb, Vb = K[t0:], V[t0:]
+    X = np.concatenate([cl["KL"], X_new]) if has_lookup else K     # the keys the clusters are formed on
+    Kb, Vb = X[t0:], V[t0:]
     nb = Kb.shape[0]
     kf_old, kf = f1 - f0, f1 - f0 + n_new_fine
     kc_old, kc = c1 - c0, c1 - c0 + (n_new_coarse if levels == 2 else 0)
 
     # working centroids of the block: the stored fine key centroids, plus the new seeds
-    Cw = np.concatenate([cl["Kc_f"][f0:f1], K_new[sd[0]]]) if n_new_fine else cl["Kc_f"][f0:f1].copy()
+    Cw = np.concatenate([cl["Kc_f"][f0:f1], X_new[sd[0]]]) if n_new_fine else cl["Kc_f"][f0:f1].copy()
     Nw = np.concatenate([cl["N_f"][f0:f1], np.zeros(n_new_fine, dtype=np.int32)]).astype(np.int64)
     # one-shot assignment of the appended tokens against frozen centroids
-    a_new = assign(K_new, Cw)
+    a_new = assign(X_new, Cw)
     # running mean of the touched centroids: c <- bf16((N c + sum of newly assigned keys) / (N + n))
     Cw = Cw.copy()
     for j in np.unique(a_new):
         s = Nw[j] * Cw[j]
         members = np.flatnonzero(a_new == j)
         for t in members:
-            s = s + K_new[t]
+            s = s + X_new[t]
         Cw[j] = round_bf16(s / float(Nw[j] + members.size))
     a = np.concatenate([cl["fine_of_token"][t0:t1] - f0, a_new]).astype(np.int32)
     # refinement: full Lloyd iterations over the last block
@@ -400,7 +421,8 @@ def update_unit(cl, K_new, V_new, n_new_fine, n_new_coarse, seeds, refine_iters,
         Ccw, parent, _ = lloyd_from(Cw, Ccw, max(1, refine_iters))
     part = finalize_block(Kb, Vb, a, Cw, parent, kc, Ccw)
     b.update(t1=t0 + nb, f1=f0 + kf, c1=c0 + kc)
-    out = _replace_last_block(cl, K, V, blocks, [part])
+    KL = X if has_lookup else None
+    out = _replace_last_block(cl, K, V, blocks, [part], KL)
 
     if counts[2] > 0:   # the last block reached W + alpha tokens: split it
         W = block_w
@@ -408,5 +430,5 @@ def update_unit(cl, K_new, V_new, n_new_fine, n_new_coarse, seeds, refine_iters,
         b2 = dict(t0=t0 + W, t1=t0 + nb, f0=b1["f1"], f1=f0 + kf, c0=b1["c1"], c1=c0 + kc)
         p1 = cluster_block(Kb[:W], Vb[:W], _i32(sd[2]), _i32(sd[4]) if levels == 2 else None, split_iters, levels)
         p2 = cluster_block(Kb[W:], Vb[W:], _i32(sd[3]), _i32(sd[5]) if levels == 2 else None, split_iters, levels)
-        out = _replace_last_block(cl, K, V, blocks[:-1] + [b1, b2], [p1, p2])
+        out = _replace_last_block(cl, K, V, blocks[:-1] + [b1, b2], [p1, p2], KL)
     return out
