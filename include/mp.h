@@ -54,6 +54,7 @@ typedef struct {
     int32_t block_w;       /* W of Sec. 3.3: clustering block length; 0 = one block             */
     int32_t block_alpha;   /* alpha of Sec. 3.3: the last block holds alpha .. W+alpha-1 tokens */
     int32_t max_tail;      /* capacity: unclustered newest tokens per unit passed to decode     */
+    int32_t lookup_keys;   /* 1: clusters are formed on separate lookup keys (see mp_cluster_kv) */
     float softmax_scale;   /* multiplies every q.k and q.centroid product; 0 => 1/sqrt(head_dim) */
 } mp_config;
 
@@ -113,11 +114,19 @@ int32_t mp_plan_blocks(int32_t n_tokens, int32_t block_w, int32_t block_alpha, i
  * cluster), and the stored tables hold, per cluster, N, bf16(mean key), bf16(mean value) (an empty
  * cluster keeps its k-means centroid as key centroid and a zero value centroid).
  *
+ * Lookup keys (Sec. 3.1, last paragraph: keys rotated to a fixed relative position before
+ * clustering, so that position-dependent rotation does not scatter similar keys).  A context
+ * created with lookup_keys = 1 takes, wherever keys are handed over, a second array k_lookup of
+ * the same shape: the clusters are formed on k_lookup and the key centroids are means of
+ * k_lookup rows, while k is what is stored and attended exactly.  The rotation itself is the
+ * caller's business.  k_lookup must be NULL for any other context (MP_EINVAL otherwise, and when
+ * it is missing for a lookup context).
+ *
  * Errors: MP_EINVAL, MP_ECAPACITY (n_tokens > max_tokens, n_fine > max_fine, ...), MP_EHIP.
  * Replaces any previous index of the context.
  * ------------------------------------------------------------------------------------------- */
-mp_status mp_cluster_kv(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, int32_t n_fine,
-                        int32_t n_coarse, int32_t iters, uint64_t seed, const int32_t* init_fine,
+mp_status mp_cluster_kv(mp_ctx* ctx, const void* k, const void* k_lookup, const void* v, int32_t n_tokens,
+                        int32_t n_fine, int32_t n_coarse, int32_t iters, uint64_t seed, const int32_t* init_fine,
                         const int32_t* init_coarse, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
@@ -130,7 +139,7 @@ mp_status mp_cluster_kv(mp_ctx* ctx, const void* k, const void* v, int32_t n_tok
  * Empty clusters get zero centroids and N = 0.  Out-of-range ids are undefined behaviour on the
  * device side (they are not read back to be checked).
  * ------------------------------------------------------------------------------------------- */
-mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens,
+mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* k_lookup, const void* v, int32_t n_tokens,
                             const int32_t* fine_of_token, int32_t n_fine,
                             const int32_t* coarse_of_fine, int32_t n_coarse, void* stream);
 
@@ -158,6 +167,8 @@ mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* v, int32_t n
  *      the remainder to the second, nb = tokens in the block.
  *
  *   k_new, v_new   device bf16 [B, Hkv, n_new, 128]
+ *   k_new_lookup   lookup keys of the appended tokens (same shape; contexts with lookup_keys only,
+ *                  else NULL): every step above then works on lookup keys, k_new is only stored
  *   n_new_fine     0 <= n_new_fine <= n_new;  n_new_coarse: 0 <= n_new_coarse <= n_new_fine
  *   seeds          host int32 [B*Hkv, total], total and the six list lengths from
  *                  mp_update_seed_counts(): {n_new_fine indices into the appended tokens,
@@ -170,14 +181,19 @@ mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* v, int32_t n
  * ------------------------------------------------------------------------------------------- */
 int32_t mp_update_seed_counts(const mp_ctx* ctx, int32_t n_new, int32_t n_new_fine, int32_t n_new_coarse,
                               int32_t* counts /* host int32 [6] */);   /* returns total, -1 on bad arguments */
-mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* v_new, int32_t n_new,
-                             int32_t n_new_fine, int32_t n_new_coarse, int32_t refine_iters,
+mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* k_new_lookup, const void* v_new,
+                             int32_t n_new, int32_t n_new_fine, int32_t n_new_coarse, int32_t refine_iters,
                              int32_t split_iters, uint64_t seed, const int32_t* seeds, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * mp_decode_attention -- one decode step for every unit (Eq. 1, Eq. 2, Sec. 3.4, Sec. 4).
  *
  *   q               device bf16 [B, Hq, 128]
+ *   q_lookup        device bf16 [B, Hq, 128] or NULL (= q): the query compared with the centroids
+ *                   (Sec. 3.1, last paragraph: a query rotated to the fixed position that matches
+ *                   the lookup keys).  It gives every centroid logit, including those of the Eq. 2
+ *                   terms (Sec. 4: the replacement stage reuses the lookup's products); q itself
+ *                   meets the stored keys and the tail.
  *   k_tail, v_tail  device bf16 [B, Hkv, tail_stride, 128], of which the first n_tail rows of every
  *                   unit are used: newest tokens that are not clustered yet (the local buffer of
  *                   Sec. 4); always attended exactly; NULL with n_tail == 0.
@@ -208,9 +224,9 @@ mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* v_new, 
  * MP_ECAPACITY (n_tail > max_tail).
  * ------------------------------------------------------------------------------------------- */
 #define MP_DECODE_NO_MULTIPOLE 1u
-mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, const void* v_tail,
-                              int32_t n_tail, int32_t tail_stride, int32_t key_budget, int32_t coarse_budget,
-                              uint32_t flags, void* out, float* lse, void* stream);
+mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* q_lookup, const void* k_tail,
+                              const void* v_tail, int32_t n_tail, int32_t tail_stride, int32_t key_budget,
+                              int32_t coarse_budget, uint32_t flags, void* out, float* lse, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Library-managed local buffer (Sec. 4 and Sec. 5.1: the newest L to 2L tokens are kept out of the
@@ -221,12 +237,14 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
  * mp_local_buffer_init sets the window L, copies n_sink sink tokens and the n_recent newest tokens
  * (0 <= n_recent < 2L, in sequence order) into the context's buffer.  k_* / v_*: device bf16
  * [B, Hkv, n, 128], read on the stream, may be NULL when n == 0.  Needs n_sink + 2L <= max_tail.
- * May be called again to reset the buffer.
+ * May be called again to reset the buffer.  Contexts with lookup_keys also take the lookup keys of
+ * the recent tokens (they are needed when those tokens are clustered); sinks never are.
  *
  * mp_decode_step is one decoding step of a generation loop:
- *   1. the new token's key and value (device bf16 [B, Hkv, 1, 128]) join the buffer;
- *   2. mp_decode_attention with the buffer (sinks, then the recent tokens including the new one) as
- *      the tail;
+ *   1. the new token's key and value (device bf16 [B, Hkv, 1, 128]; k_new_lookup likewise for
+ *      contexts with lookup_keys, else NULL) join the buffer;
+ *   2. mp_decode_attention (q, q_lookup) with the buffer (sinks, then the recent tokens including
+ *      the new one) as the tail;
  *   3. when the buffer holds 2L recent tokens, mp_update_clusters with the oldest L of them
  *      (n_new_fine, n_new_coarse, refine_iters, split_iters, seed, seeds as for that call; `seeds`
  *      is read only in such a step), and the newer L move to the front.
@@ -236,12 +254,13 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
  * next call retries the update before anything else.
  * ------------------------------------------------------------------------------------------- */
 mp_status mp_local_buffer_init(mp_ctx* ctx, int32_t window, const void* k_sink, const void* v_sink, int32_t n_sink,
-                               const void* k_recent, const void* v_recent, int32_t n_recent, void* stream);
+                               const void* k_recent, const void* k_recent_lookup, const void* v_recent,
+                               int32_t n_recent, void* stream);
 mp_status mp_local_buffer_size(const mp_ctx* ctx, int32_t* window, int32_t* n_sink, int32_t* n_recent);
-mp_status mp_decode_step(mp_ctx* ctx, const void* q, const void* k_new, const void* v_new, int32_t key_budget,
-                         int32_t coarse_budget, uint32_t flags, int32_t n_new_fine, int32_t n_new_coarse,
-                         int32_t refine_iters, int32_t split_iters, uint64_t seed, const int32_t* seeds, void* out,
-                         float* lse, void* stream);
+mp_status mp_decode_step(mp_ctx* ctx, const void* q, const void* q_lookup, const void* k_new, const void* k_new_lookup,
+                         const void* v_new, int32_t key_budget, int32_t coarse_budget, uint32_t flags, int32_t n_new_fine,
+                         int32_t n_new_coarse, int32_t refine_iters, int32_t split_iters, uint64_t seed,
+                         const int32_t* seeds, void* out, float* lse, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Stage timing (for benchmarks).  While enabled, mp_decode_attention records HIP events on the

@@ -34,7 +34,7 @@ class MpError(RuntimeError):
 class MpConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "max_tokens", "levels", "max_fine", "max_coarse",
-        "block_w", "block_alpha", "max_tail")] + [("softmax_scale", C.c_float)]
+        "block_w", "block_alpha", "max_tail", "lookup_keys")] + [("softmax_scale", C.c_float)]
 
 
 _lib = None
@@ -59,14 +59,14 @@ def lib():
         L.mp_device_bytes.restype = sz
         L.mp_plan_blocks.argtypes = [i32, i32, i32, i32, i32, vp, i32]
         L.mp_plan_blocks.restype = i32
-        L.mp_cluster_kv.argtypes = [vp, vp, vp, i32, i32, i32, i32, u64, vp, vp, vp]
-        L.mp_set_clustering.argtypes = [vp, vp, vp, i32, vp, i32, vp, i32, vp]
-        L.mp_update_clusters.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, u64, vp, vp]
-        L.mp_decode_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, u32, vp, vp, vp]
+        L.mp_cluster_kv.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, u64, vp, vp, vp]
+        L.mp_set_clustering.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, i32, vp]
+        L.mp_update_clusters.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, u64, vp, vp]
+        L.mp_decode_attention.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, u32, vp, vp, vp]
         L.mp_update_seed_counts.argtypes = [vp, i32, i32, i32, vp]
-        L.mp_local_buffer_init.argtypes = [vp, i32, vp, vp, i32, vp, vp, i32, vp]
+        L.mp_local_buffer_init.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, i32, vp]
         L.mp_local_buffer_size.argtypes = [vp, vp, vp, vp]
-        L.mp_decode_step.argtypes = [vp, vp, vp, vp, i32, i32, u32, i32, i32, i32, i32, u64, vp, vp, vp, vp]
+        L.mp_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, u32, i32, i32, i32, i32, u64, vp, vp, vp, vp]
         L.mp_update_seed_counts.restype = i32
         L.mp_enable_stage_timing.argtypes = [vp, i32]
         L.mp_get_stage_timing.argtypes = [vp, vp]
@@ -141,9 +141,9 @@ class MpContext:
     """Owns an mp_ctx handle.  Method names and arguments mirror the C entry points."""
 
     def __init__(self, batch, n_q_heads, n_kv_heads, max_tokens, levels, max_fine, max_coarse=0, block_w=0,
-                 block_alpha=0, max_tail=0, softmax_scale=0.0, head_dim=128):
+                 block_alpha=0, max_tail=0, softmax_scale=0.0, head_dim=128, lookup_keys=False):
         self.cfg = MpConfig(batch, n_q_heads, n_kv_heads, head_dim, max_tokens, levels, max_fine, max_coarse,
-                            block_w, block_alpha, max_tail, softmax_scale)
+                            block_w, block_alpha, max_tail, 1 if lookup_keys else 0, softmax_scale)
         self.h = C.c_void_p()
         st = lib().mp_create(C.byref(self.cfg), C.byref(self.h))
         _check(st)
@@ -164,33 +164,35 @@ class MpContext:
     def device_bytes(self):
         return int(lib().mp_device_bytes(self.h))
 
-    def mp_cluster_kv(self, k, v, n_fine, n_coarse=0, iters=10, seed=0, init_fine=None, init_coarse=None):
+    def mp_cluster_kv(self, k, v, n_fine, n_coarse=0, iters=10, seed=0, init_fine=None, init_coarse=None,
+                      k_lookup=None):
         n_tokens = k.shape[2]
         f_keep, f_ptr = _host_i32(init_fine)
         c_keep, c_ptr = _host_i32(init_coarse)
-        st = lib().mp_cluster_kv(self.h, _ptr(k), _ptr(v), n_tokens, n_fine, n_coarse, iters, seed, f_ptr, c_ptr,
-                                 _stream())
+        st = lib().mp_cluster_kv(self.h, _ptr(k), _ptr(k_lookup), _ptr(v), n_tokens, n_fine, n_coarse, iters, seed,
+                                 f_ptr, c_ptr, _stream())
         _check(st, self.h)
 
-    def mp_set_clustering(self, k, v, fine_of_token, n_fine, coarse_of_fine=None, n_coarse=0):
+    def mp_set_clustering(self, k, v, fine_of_token, n_fine, coarse_of_fine=None, n_coarse=0, k_lookup=None):
         n_tokens = k.shape[2]
-        st = lib().mp_set_clustering(self.h, _ptr(k), _ptr(v), n_tokens, _ptr(fine_of_token), n_fine,
+        st = lib().mp_set_clustering(self.h, _ptr(k), _ptr(k_lookup), _ptr(v), n_tokens, _ptr(fine_of_token), n_fine,
                                      _ptr(coarse_of_fine), n_coarse, _stream())
         _check(st, self.h)
 
     def mp_update_clusters(self, k_new, v_new, n_new_fine, n_new_coarse=0, refine_iters=3, split_iters=10, seed=0,
-                           seeds=None):
+                           seeds=None, k_new_lookup=None):
         n_new = k_new.shape[2]
         s_keep, s_ptr = _host_i32(seeds)
-        st = lib().mp_update_clusters(self.h, _ptr(k_new), _ptr(v_new), n_new, n_new_fine, n_new_coarse,
+        st = lib().mp_update_clusters(self.h, _ptr(k_new), _ptr(k_new_lookup), _ptr(v_new), n_new, n_new_fine, n_new_coarse,
                                       refine_iters, split_iters, seed, s_ptr, _stream())
         _check(st, self.h)
 
-    def mp_local_buffer_init(self, window, k_sink=None, v_sink=None, k_recent=None, v_recent=None):
+    def mp_local_buffer_init(self, window, k_sink=None, v_sink=None, k_recent=None, v_recent=None,
+                             k_recent_lookup=None):
         n_sink = 0 if k_sink is None else k_sink.shape[2]
         n_recent = 0 if k_recent is None else k_recent.shape[2]
         st = lib().mp_local_buffer_init(self.h, window, _ptr(k_sink), _ptr(v_sink), n_sink, _ptr(k_recent),
-                                        _ptr(v_recent), n_recent, _stream())
+                                        _ptr(k_recent_lookup), _ptr(v_recent), n_recent, _stream())
         _check(st, self.h)
 
     def mp_local_buffer_size(self):
@@ -201,11 +203,13 @@ class MpContext:
         return dict(window=buf[0], n_sink=buf[1], n_recent=buf[2])
 
     def mp_decode_step(self, q, k_new, v_new, key_budget, coarse_budget=0, n_new_fine=0, n_new_coarse=0,
-                       refine_iters=3, split_iters=10, seed=0, seeds=None, out=None, lse=None, flags=0):
+                       refine_iters=3, split_iters=10, seed=0, seeds=None, out=None, lse=None, flags=0,
+                       q_lookup=None, k_new_lookup=None):
         if out is None:
             out = torch.empty_like(q)
         s_keep, s_ptr = _host_i32(seeds)
-        st = lib().mp_decode_step(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), key_budget, coarse_budget, flags,
+        st = lib().mp_decode_step(self.h, _ptr(q), _ptr(q_lookup), _ptr(k_new), _ptr(k_new_lookup), _ptr(v_new),
+                                  key_budget, coarse_budget, flags,
                                   n_new_fine, n_new_coarse, refine_iters, split_iters, seed, s_ptr, _ptr(out),
                                   _ptr(lse), _stream())
         _check(st, self.h)
@@ -219,14 +223,14 @@ class MpContext:
         return list(buf)
 
     def mp_decode_attention(self, q, key_budget, coarse_budget=0, k_tail=None, v_tail=None, out=None, lse=None,
-                            flags=0, n_tail=None):
+                            flags=0, n_tail=None, q_lookup=None):
         """k_tail / v_tail [B, Hkv, rows, 128]; n_tail (default: all rows) = rows of every unit in use."""
         tail_stride = 0 if k_tail is None else k_tail.shape[2]
         if n_tail is None:
             n_tail = tail_stride
         if out is None:
             out = torch.empty_like(q)
-        st = lib().mp_decode_attention(self.h, _ptr(q), _ptr(k_tail), _ptr(v_tail), n_tail, tail_stride, key_budget,
+        st = lib().mp_decode_attention(self.h, _ptr(q), _ptr(q_lookup), _ptr(k_tail), _ptr(v_tail), n_tail, tail_stride, key_budget,
                                        coarse_budget, flags, _ptr(out), _ptr(lse), _stream())
         _check(st, self.h)
         return out

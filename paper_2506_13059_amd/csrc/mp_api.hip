@@ -19,14 +19,15 @@ using namespace mp;
 
 namespace mp {
 // implemented in mp_cluster.hip
-mp_status cluster_kv_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, int32_t n_fine,
+mp_status cluster_kv_impl(mp_ctx* ctx, const void* k, const void* k_lookup, const void* v, int32_t n_tokens, int32_t n_fine,
                           int32_t n_coarse, int32_t iters, uint64_t seed, const int32_t* init_fine,
                           const int32_t* init_coarse, hipStream_t s);
-mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* v_new, int32_t n_new, int32_t n_new_fine,
-                               int32_t n_new_coarse, int32_t refine_iters, int32_t split_iters, uint64_t seed,
-                               const int32_t* seeds, hipStream_t s);
-mp_status set_clustering_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, const int32_t* fine_of_token,
-                              int32_t n_fine, const int32_t* coarse_of_fine, int32_t n_coarse, hipStream_t s);
+mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* k_new_lookup, const void* v_new, int32_t n_new,
+                               int32_t n_new_fine, int32_t n_new_coarse, int32_t refine_iters, int32_t split_iters,
+                               uint64_t seed, const int32_t* seeds, hipStream_t s);
+mp_status set_clustering_impl(mp_ctx* ctx, const void* k, const void* k_lookup, const void* v, int32_t n_tokens,
+                              const int32_t* fine_of_token, int32_t n_fine, const int32_t* coarse_of_fine, int32_t n_coarse,
+                              hipStream_t s);
 void update_seed_counts(const mp_ctx* ctx, int n_new, int n_new_fine, int n_new_coarse, int32_t counts[6]);
 
 thread_local std::string g_err;   // errors of context-free calls
@@ -97,6 +98,9 @@ void free_all(mp_ctx* ctx)
 }
 
 }  // namespace
+
+// A context created with lookup_keys expects lookup keys wherever keys are handed over, any other none.
+static bool lookup_arg_ok(const mp_ctx* ctx, const void* k_lookup) { return (ctx->cfg.lookup_keys != 0) == (k_lookup != nullptr); }
 
 extern "C" {
 
@@ -169,6 +173,7 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     A(fstart, U * (F + 1)); A(cof, U * F); A(cstart, U * (Cc + 1)); A(crow, U * (Cc + 1));
     A(Kc, U * T * D); A(Vc, U * T * D); A(Ncl, U * T);
     A(Kfb, U * (size_t)ctx->FBcap * D); A(Vfb, U * (size_t)ctx->FBcap * D);
+    if (c.lookup_keys) A(Kfs, U * (size_t)ctx->FBcap * D);
     A(km_assign, U * N); A(km_list, U * N); A(km_cnt, U * T); A(km_start, U * (T + 2));
     A(km_Cf, U * F * D); A(km_Cc, U * Cc * D); A(km_parent, U * F); A(km_plist, U * F); A(km_newid, U * F);
     A(km_seed_f, U * F); A(km_seed_c, U * Cc); A(blocks_dev, 3 * (size_t)ctx->max_blocks * 4);
@@ -183,6 +188,7 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     if (ctx->Tcap > 0) {
         const size_t Tc = ctx->Tcap;
         A(Kt, U * Tc * D); A(Vt, U * Tc * D); A(Kts, U * Tc * D); A(Vts, U * Tc * D);
+        if (c.lookup_keys) { A(Ktl, U * Tc * D); A(Ktls, U * Tc * D); }
     }
 #undef A
     if (e == hipSuccess) {
@@ -218,7 +224,7 @@ void mp_destroy(mp_ctx* ctx)
     delete ctx;
 }
 
-mp_status mp_cluster_kv(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, int32_t n_fine, int32_t n_coarse,
+mp_status mp_cluster_kv(mp_ctx* ctx, const void* k, const void* k_lookup, const void* v, int32_t n_tokens, int32_t n_fine, int32_t n_coarse,
                         int32_t iters, uint64_t seed, const int32_t* init_fine, const int32_t* init_coarse,
                         void* stream)
 {
@@ -256,11 +262,13 @@ mp_status mp_cluster_kv(mp_ctx* ctx, const void* k, const void* v, int32_t n_tok
                     const int32_t f = init_coarse[(size_t)u * n_coarse + c];
                     if (f < 0 || f >= b.f1 - b.f0) return fail(ctx, MP_EINVAL, "mp_cluster_kv: init_coarse[%d][%d] = %d out of its block", u, c, f);
                 }
-    return cluster_kv_impl(ctx, k, v, n_tokens, n_fine, n_coarse, iters, seed, init_fine, init_coarse, (hipStream_t)stream);
+    if (!lookup_arg_ok(ctx, k_lookup)) return fail(ctx, MP_EINVAL, "mp_cluster_kv: k_lookup must be given exactly when the context was created with lookup_keys");
+    return cluster_kv_impl(ctx, k, k_lookup, v, n_tokens, n_fine, n_coarse, iters, seed, init_fine, init_coarse, (hipStream_t)stream);
 }
 
-mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, const int32_t* fine_of_token,
-                            int32_t n_fine, const int32_t* coarse_of_fine, int32_t n_coarse, void* stream)
+mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* k_lookup, const void* v, int32_t n_tokens,
+                            const int32_t* fine_of_token, int32_t n_fine, const int32_t* coarse_of_fine, int32_t n_coarse,
+                            void* stream)
 {
     if (!ctx) return fail(nullptr, MP_EINVAL, "mp_set_clustering: null context");
     if (!k || !v || !fine_of_token) return fail(ctx, MP_EINVAL, "mp_set_clustering: null pointer");
@@ -273,7 +281,8 @@ mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* v, int32_t n
     } else {
         n_coarse = 0;
     }
-    return set_clustering_impl(ctx, k, v, n_tokens, fine_of_token, n_fine, coarse_of_fine, n_coarse, (hipStream_t)stream);
+    if (!lookup_arg_ok(ctx, k_lookup)) return fail(ctx, MP_EINVAL, "mp_set_clustering: k_lookup must be given exactly when the context was created with lookup_keys");
+    return set_clustering_impl(ctx, k, k_lookup, v, n_tokens, fine_of_token, n_fine, coarse_of_fine, n_coarse, (hipStream_t)stream);
 }
 
 int32_t mp_update_seed_counts(const mp_ctx* ctx, int32_t n_new, int32_t n_new_fine, int32_t n_new_coarse, int32_t* counts)
@@ -285,9 +294,9 @@ int32_t mp_update_seed_counts(const mp_ctx* ctx, int32_t n_new, int32_t n_new_fi
     return t;
 }
 
-mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* v_new, int32_t n_new, int32_t n_new_fine,
-                             int32_t n_new_coarse, int32_t refine_iters, int32_t split_iters, uint64_t seed,
-                             const int32_t* seeds, void* stream)
+mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* k_new_lookup, const void* v_new, int32_t n_new,
+                             int32_t n_new_fine, int32_t n_new_coarse, int32_t refine_iters, int32_t split_iters,
+                             uint64_t seed, const int32_t* seeds, void* stream)
 {
     if (!ctx) return fail(nullptr, MP_EINVAL, "mp_update_clusters: null context");
     if (!ctx->has_index) return fail(ctx, MP_ESTATE, "mp_update_clusters: no index yet (call mp_cluster_kv first)");
@@ -297,12 +306,13 @@ mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* v_new, 
                     refine_iters, split_iters);
     if (ctx->cfg.levels == 2 && (n_new_coarse < 0 || n_new_coarse > n_new_fine))
         return fail(ctx, MP_EINVAL, "mp_update_clusters: n_new_coarse must be in [0, n_new_fine]");
-    return update_clusters_impl(ctx, k_new, v_new, n_new, n_new_fine, ctx->cfg.levels == 2 ? n_new_coarse : 0, refine_iters,
-                                split_iters, seed, seeds, (hipStream_t)stream);
+    if (!lookup_arg_ok(ctx, k_new_lookup)) return fail(ctx, MP_EINVAL, "mp_update_clusters: k_new_lookup must be given exactly when the context was created with lookup_keys");
+    return update_clusters_impl(ctx, k_new, k_new_lookup, v_new, n_new, n_new_fine, ctx->cfg.levels == 2 ? n_new_coarse : 0,
+                                refine_iters, split_iters, seed, seeds, (hipStream_t)stream);
 }
 
-mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, const void* v_tail, int32_t n_tail,
-                              int32_t tail_stride,
+mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* q_lookup, const void* k_tail, const void* v_tail,
+                              int32_t n_tail, int32_t tail_stride,
                               int32_t key_budget, int32_t coarse_budget, uint32_t flags, void* out, float* lse, void* stream)
 {
     if (!ctx) return fail(nullptr, MP_EINVAL, "mp_decode_attention: null context");
@@ -319,7 +329,7 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
     const int use_mp = (flags & MP_DECODE_NO_MULTIPOLE) ? 0 : 1;
 
     ScoreParams sp{};
-    sp.q = (const uint16_t*)q; sp.Kc = ctx->Kc; sp.N = ctx->Ncl; sp.tab_rows = ctx->tab_rows; sp.fcap = ctx->Fcap;
+    sp.q = (const uint16_t*)(q_lookup ? q_lookup : q); sp.Kc = ctx->Kc; sp.N = ctx->Ncl; sp.tab_rows = ctx->tab_rows; sp.fcap = ctx->Fcap;
     sp.levels = ctx->cfg.levels; sp.n_fine = ctx->n_fine; sp.n_coarse = ctx->n_coarse;
     sp.key_budget = key_budget; sp.coarse_budget = coarse_budget; sp.scale = ctx->scale_d;
     sp.cstart = ctx->cstart; sp.cstart_stride = ctx->Ccap + 1; sp.fstart = ctx->fstart; sp.fstart_stride = ctx->Fcap + 1;
@@ -383,13 +393,16 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* k_tail, co
 // exactly; every L steps the oldest L of them go into the clusters) and sink tokens
 // ------------------------------------------------------------------------------------------------
 mp_status mp_local_buffer_init(mp_ctx* ctx, int32_t window, const void* k_sink, const void* v_sink, int32_t n_sink,
-                               const void* k_recent, const void* v_recent, int32_t n_recent, void* stream)
+                               const void* k_recent, const void* k_recent_lookup, const void* v_recent, int32_t n_recent,
+                               void* stream)
 {
     if (!ctx) return fail(nullptr, MP_EINVAL, "mp_local_buffer_init: null context");
     if (window < 1 || n_sink < 0 || n_recent < 0 || n_recent >= 2 * window)
         return fail(ctx, MP_EINVAL, "mp_local_buffer_init: need window >= 1, n_sink >= 0, 0 <= n_recent < 2 * window");
     if ((n_sink > 0 && (!k_sink || !v_sink)) || (n_recent > 0 && (!k_recent || !v_recent)))
         return fail(ctx, MP_EINVAL, "mp_local_buffer_init: null rows with a positive count");
+    if (n_recent > 0 && !lookup_arg_ok(ctx, k_recent_lookup))
+        return fail(ctx, MP_EINVAL, "mp_local_buffer_init: k_recent_lookup must be given exactly when the context was created with lookup_keys");
     if ((long long)n_sink + 2ll * window > ctx->Tcap)
         return fail(ctx, MP_ECAPACITY, "mp_local_buffer_init: n_sink + 2 * window = %lld > max_tail %d", (long long)n_sink + 2ll * window, ctx->Tcap);
     hipStream_t s = (hipStream_t)stream;
@@ -401,6 +414,8 @@ mp_status mp_local_buffer_init(mp_ctx* ctx, int32_t window, const void* k_sink, 
     if (n_recent > 0) {
         MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Kt + n_sink * row, pitch, k_recent, n_recent * row, n_recent * row, ctx->U, hipMemcpyDeviceToDevice, s));
         MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Vt + n_sink * row, pitch, v_recent, n_recent * row, n_recent * row, ctx->U, hipMemcpyDeviceToDevice, s));
+        if (k_recent_lookup)
+            MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Ktl + n_sink * row, pitch, k_recent_lookup, n_recent * row, n_recent * row, ctx->U, hipMemcpyDeviceToDevice, s));
     }
     ctx->lb_window = window;
     ctx->lb_sink = n_sink;
@@ -431,9 +446,14 @@ mp_status refresh_local_buffer(mp_ctx* ctx, int32_t n_new_fine, int32_t n_new_co
     const size_t row = kHeadDimHost * sizeof(uint16_t), pitch = (size_t)ctx->Tcap * row;
     MP_HIP(ctx, hipMemcpy2DAsync(ctx->Kts, L * row, (char*)ctx->Kt + ns * row, pitch, L * row, ctx->U, hipMemcpyDeviceToDevice, s));
     MP_HIP(ctx, hipMemcpy2DAsync(ctx->Vts, L * row, (char*)ctx->Vt + ns * row, pitch, L * row, ctx->U, hipMemcpyDeviceToDevice, s));
-    const mp_status st = update_clusters_impl(ctx, ctx->Kts, ctx->Vts, L, n_new_fine, ctx->cfg.levels == 2 ? n_new_coarse : 0,
-                                              refine_iters, split_iters, seed, seeds, s);
+    const bool lookup = ctx->cfg.lookup_keys != 0;
+    if (lookup)
+        MP_HIP(ctx, hipMemcpy2DAsync(ctx->Ktls, L * row, (char*)ctx->Ktl + ns * row, pitch, L * row, ctx->U, hipMemcpyDeviceToDevice, s));
+    const mp_status st = update_clusters_impl(ctx, ctx->Kts, lookup ? ctx->Ktls : nullptr, ctx->Vts, L, n_new_fine,
+                                              ctx->cfg.levels == 2 ? n_new_coarse : 0, refine_iters, split_iters, seed, seeds, s);
     if (st != MP_OK) return st;
+    if (lookup)
+        MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Ktl + ns * row, pitch, (char*)ctx->Ktl + (ns + L) * row, pitch, L * row, ctx->U, hipMemcpyDeviceToDevice, s));
     MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Kt + ns * row, pitch, (char*)ctx->Kt + (ns + L) * row, pitch, L * row, ctx->U, hipMemcpyDeviceToDevice, s));
     MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Vt + ns * row, pitch, (char*)ctx->Vt + (ns + L) * row, pitch, L * row, ctx->U, hipMemcpyDeviceToDevice, s));
     ctx->lb_recent = L;
@@ -441,15 +461,16 @@ mp_status refresh_local_buffer(mp_ctx* ctx, int32_t n_new_fine, int32_t n_new_co
 }
 }  // namespace
 
-mp_status mp_decode_step(mp_ctx* ctx, const void* q, const void* k_new, const void* v_new, int32_t key_budget,
-                         int32_t coarse_budget, uint32_t flags, int32_t n_new_fine, int32_t n_new_coarse,
-                         int32_t refine_iters, int32_t split_iters, uint64_t seed, const int32_t* seeds, void* out,
-                         float* lse, void* stream)
+mp_status mp_decode_step(mp_ctx* ctx, const void* q, const void* q_lookup, const void* k_new, const void* k_new_lookup,
+                         const void* v_new, int32_t key_budget, int32_t coarse_budget, uint32_t flags, int32_t n_new_fine,
+                         int32_t n_new_coarse, int32_t refine_iters, int32_t split_iters, uint64_t seed,
+                         const int32_t* seeds, void* out, float* lse, void* stream)
 {
     if (!ctx) return fail(nullptr, MP_EINVAL, "mp_decode_step: null context");
     if (!ctx->has_index) return fail(ctx, MP_ESTATE, "mp_decode_step: no index yet (call mp_cluster_kv first)");
     if (ctx->lb_window == 0) return fail(ctx, MP_ESTATE, "mp_decode_step: no local buffer (call mp_local_buffer_init first)");
     if (!q || !k_new || !v_new || !out) return fail(ctx, MP_EINVAL, "mp_decode_step: null q/k_new/v_new/out");
+    if (!lookup_arg_ok(ctx, k_new_lookup)) return fail(ctx, MP_EINVAL, "mp_decode_step: k_new_lookup must be given exactly when the context was created with lookup_keys");
     hipStream_t s = (hipStream_t)stream;
     const int L = ctx->lb_window, ns = ctx->lb_sink;
     if (ctx->lb_recent >= 2 * L) {      // a refresh that failed in an earlier call (e.g. capacity) is due first
@@ -458,8 +479,12 @@ mp_status mp_decode_step(mp_ctx* ctx, const void* q, const void* k_new, const vo
     }
     // the new token joins the buffer first: a decoding step attends to its own key and value
     MP_HIP(ctx, mp::launch_append_row(k_new, v_new, ctx->U, ctx->Kt, ctx->Vt, ctx->Tcap, ns + ctx->lb_recent, s));
+    if (k_new_lookup)
+        MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Ktl + (size_t)(ns + ctx->lb_recent) * kHeadDimHost * sizeof(uint16_t),
+                                     (size_t)ctx->Tcap * kHeadDimHost * sizeof(uint16_t), k_new_lookup, kHeadDimHost * sizeof(uint16_t),
+                                     kHeadDimHost * sizeof(uint16_t), ctx->U, hipMemcpyDeviceToDevice, s));
     ctx->lb_recent += 1;
-    const mp_status st = mp_decode_attention(ctx, q, ctx->Kt, ctx->Vt, ns + ctx->lb_recent, ctx->Tcap, key_budget,
+    const mp_status st = mp_decode_attention(ctx, q, q_lookup, ctx->Kt, ctx->Vt, ns + ctx->lb_recent, ctx->Tcap, key_budget,
                                              coarse_budget, flags, out, lse, stream);
     if (st != MP_OK) {
         ctx->lb_recent -= 1;

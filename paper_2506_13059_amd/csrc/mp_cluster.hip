@@ -237,7 +237,8 @@ bool distinct_in_range(const int32_t* v, int k, int n)
 
 // A contiguous run of clustering blocks whose points live in X at local indices [0, n_pts).
 struct Range {
-    const uint16_t* Xk;
+    const uint16_t* Xk;             // keys the clusters are formed on (lookup keys when the context uses them)
+    const uint16_t* Xs;             // keys to store and attend exactly (== Xk without lookup keys)
     const uint16_t* Xv;
     long long x_unit_rows;
     int pt0;                        // token / stored-row index of local point 0
@@ -267,9 +268,9 @@ void upload_descs(const Range& r, int max_blocks, std::vector<int32_t>& bd, int&
 // Stored layout and tables of a range from: ids (final fine id of each local point), ctx->cof for
 // [f0,f1) (non-decreasing per block), and -- for empty clusters -- the key centroids already sitting
 // in ctx->Kc when key_fallback is set.  Block descriptors of the range must be in blocks_dev slot 1.
-mp_status finalize_range(mp_ctx* ctx, const void* Xk, const void* Xv, long long x_unit_rows, int pt0, int n_pts,
-                         const int32_t* ids, long long ids_stride, int f0, int f1, int c0, int c1, int nb, int max_kf,
-                         bool key_fallback, hipStream_t s)
+mp_status finalize_range(mp_ctx* ctx, const void* Xk, const void* Xs, const void* Xv, long long x_unit_rows, int pt0,
+                         int n_pts, const int32_t* ids, long long ids_stride, int f0, int f1, int c0, int c1, int nb,
+                         int max_kf, bool key_fallback, hipStream_t s)
 {
     const int U = ctx->U;
     const long long Ncap = ctx->Ncap, tab = ctx->tab_rows;
@@ -280,7 +281,7 @@ mp_status finalize_range(mp_ctx* ctx, const void* Xk, const void* Xv, long long 
     MP_HIPC(launch_block_lists(ids, ids_stride, bdev, nb, max_kf, 0, U, ctx->km_start, tab + 1, ctx->km_list, Ncap, s));
     MP_HIPC(launch_offset_lists(ctx->km_start, tab + 1, f0, f1, ctx->km_list, Ncap, n_pts, pt0, U, ctx->fstart,
                                 ctx->Fcap + 1, ctx->perm, Ncap, s));
-    MP_HIPC(launch_gather_rows(Xk, Xv, x_unit_rows, ctx->km_list, Ncap, n_pts, U, ctx->Kp, ctx->Vp, Ncap, pt0, s));
+    MP_HIPC(launch_gather_rows(Xs, Xv, x_unit_rows, ctx->km_list, Ncap, n_pts, U, ctx->Kp, ctx->Vp, Ncap, pt0, s));
     MP_HIPC(launch_cluster_means((const uint16_t*)Xk, x_unit_rows, ctx->km_list, Ncap, ctx->km_start, tab + 1, f0, f1, U,
                                  ctx->Kc, tab, 0, key_fallback ? ctx->Kc : nullptr, tab, nullptr, 0, 0, s));
     MP_HIPC(launch_cluster_means((const uint16_t*)Xv, x_unit_rows, ctx->km_list, Ncap, ctx->km_start, tab + 1, f0, f1, U,
@@ -289,9 +290,13 @@ mp_status finalize_range(mp_ctx* ctx, const void* Xk, const void* Xv, long long 
         MP_HIPC(launch_coarse_start(ctx->cof, ctx->Fcap, f0, f1, c0, c1, U, ctx->cstart, ctx->Ccap + 1, s));
         MP_HIPC(launch_coarse_row_start(ctx->cstart, ctx->Ccap + 1, ctx->fstart, ctx->Fcap + 1, c0, c1, U, ctx->crow,
                                         ctx->Ccap + 1, s));
-        MP_HIPC(launch_cluster_means(ctx->Kp, Ncap, nullptr, 0, ctx->crow, ctx->Ccap + 1, c0, c1, U, ctx->Kc, tab,
-                                     ctx->Fcap, key_fallback ? ctx->Kc + (long long)ctx->Fcap * kHeadDim : nullptr, tab,
-                                     nullptr, 0, 0, s));
+        const uint16_t* kfb = key_fallback ? ctx->Kc + (long long)ctx->Fcap * kHeadDim : nullptr;
+        if (Xs == Xk)       // the stored rows of a coarse cluster are contiguous: sum them where they lie
+            MP_HIPC(launch_cluster_means(ctx->Kp, Ncap, nullptr, 0, ctx->crow, ctx->Ccap + 1, c0, c1, U, ctx->Kc, tab, ctx->Fcap,
+                                         kfb, tab, nullptr, 0, 0, s));
+        else                // lookup keys are not stored: the same rows, in the same order, through the member list
+            MP_HIPC(launch_cluster_means((const uint16_t*)Xk, x_unit_rows, ctx->km_list - pt0, Ncap, ctx->crow, ctx->Ccap + 1,
+                                         c0, c1, U, ctx->Kc, tab, ctx->Fcap, kfb, tab, nullptr, 0, 0, s));
         MP_HIPC(launch_cluster_means(ctx->Vp, Ncap, nullptr, 0, ctx->crow, ctx->Ccap + 1, c0, c1, U, ctx->Vc, tab,
                                      ctx->Fcap, nullptr, 0, ctx->Ncl, tab, ctx->Fcap, s));
     }
@@ -350,7 +355,7 @@ mp_status coarse_and_finalize(mp_ctx* ctx, const Range& r, int coarse_iters, boo
                            (const uint4*)ctx->km_Cf, Fcap, r.f0, nullptr, 0, 0, kf, (uint4*)ctx->Kc, ctx->tab_rows, r.f0);
         MP_HIPC(hipGetLastError());
     }
-    return finalize_range(ctx, r.Xk, r.Xv, r.x_unit_rows, r.pt0, r.n_pts, ctx->km_assign, ctx->Ncap, r.f0, r.f1, r.c0,
+    return finalize_range(ctx, r.Xk, r.Xs, r.Xv, r.x_unit_rows, r.pt0, r.n_pts, ctx->km_assign, ctx->Ncap, r.f0, r.f1, r.c0,
                           r.c1, nb, max_kf, true, s);
 }
 
@@ -380,7 +385,7 @@ mp_status cluster_range(mp_ctx* ctx, const Range& r, int iters, hipStream_t s)
 
 }  // namespace
 
-mp_status cluster_kv_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, int32_t n_fine,
+mp_status cluster_kv_impl(mp_ctx* ctx, const void* k, const void* k_lookup, const void* v, int32_t n_tokens, int32_t n_fine,
                           int32_t n_coarse, int32_t iters, uint64_t seed, const int32_t* init_fine,
                           const int32_t* init_coarse, hipStream_t s)
 {
@@ -416,7 +421,8 @@ mp_status cluster_kv_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_t
                          (size_t)n_coarse * 4, U, s));
 
     Range r;
-    r.Xk = (const uint16_t*)k; r.Xv = (const uint16_t*)v; r.x_unit_rows = n_tokens; r.pt0 = 0; r.n_pts = n_tokens;
+    r.Xk = (const uint16_t*)(k_lookup ? k_lookup : k); r.Xs = (const uint16_t*)k; r.Xv = (const uint16_t*)v;
+    r.x_unit_rows = n_tokens; r.pt0 = 0; r.n_pts = n_tokens;
     r.blocks = blocks; r.f0 = 0; r.f1 = n_fine; r.c0 = 0; r.c1 = n_coarse;
     const mp_status st = cluster_range(ctx, r, iters, s);
     if (st != MP_OK) return st;
@@ -426,8 +432,11 @@ mp_status cluster_kv_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_t
     const int nlast = lb.t1 - lb.t0;
     if (nlast <= ctx->FBcap) {
         const size_t row = kHeadDim * sizeof(uint16_t);
-        MP_HIPC(hipMemcpy2DAsync(ctx->Kfb, (size_t)ctx->FBcap * row, (const char*)k + (size_t)lb.t0 * row,
+        MP_HIPC(hipMemcpy2DAsync(ctx->Kfb, (size_t)ctx->FBcap * row, (const char*)r.Xk + (size_t)lb.t0 * row,
                                  (size_t)n_tokens * row, (size_t)nlast * row, U, hipMemcpyDeviceToDevice, s));
+        if (k_lookup)
+            MP_HIPC(hipMemcpy2DAsync(ctx->Kfs, (size_t)ctx->FBcap * row, (const char*)k + (size_t)lb.t0 * row,
+                                     (size_t)n_tokens * row, (size_t)nlast * row, U, hipMemcpyDeviceToDevice, s));
         MP_HIPC(hipMemcpy2DAsync(ctx->Vfb, (size_t)ctx->FBcap * row, (const char*)v + (size_t)lb.t0 * row,
                                  (size_t)n_tokens * row, (size_t)nlast * row, U, hipMemcpyDeviceToDevice, s));
     }
@@ -441,7 +450,7 @@ mp_status cluster_kv_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_t
     return MP_OK;
 }
 
-mp_status set_clustering_impl(mp_ctx* ctx, const void* k, const void* v, int32_t n_tokens, const int32_t* fine_of_token,
+mp_status set_clustering_impl(mp_ctx* ctx, const void* k, const void* k_lookup, const void* v, int32_t n_tokens, const int32_t* fine_of_token,
                               int32_t n_fine, const int32_t* coarse_of_fine, int32_t n_coarse, hipStream_t s)
 {
     MP_TRY(stage_open(ctx));
@@ -458,13 +467,17 @@ mp_status set_clustering_impl(mp_ctx* ctx, const void* k, const void* v, int32_t
     upload_descs(r, ctx->max_blocks, ctx->stage_blocks2, max_pts, max_kf, max_kc);
     MP_TRY(upload(ctx, ctx->blocks_dev + 4 * (size_t)ctx->max_blocks, ctx->stage_blocks2.data(),
                   ctx->stage_blocks2.size() * sizeof(int32_t), s));
-    const mp_status st = finalize_range(ctx, k, v, n_tokens, 0, n_tokens, ctx->fot, ctx->Ncap, 0, n_fine, 0, n_coarse, 1,
+    const void* xk = k_lookup ? k_lookup : k;
+    const mp_status st = finalize_range(ctx, xk, k, v, n_tokens, 0, n_tokens, ctx->fot, ctx->Ncap, 0, n_fine, 0, n_coarse, 1,
                                         max_kf, false, s);
     if (st != MP_OK) return st;
     if (n_tokens <= ctx->FBcap) {
         const size_t row = kHeadDim * sizeof(uint16_t);
-        MP_HIPC(hipMemcpy2DAsync(ctx->Kfb, (size_t)ctx->FBcap * row, k, (size_t)n_tokens * row, (size_t)n_tokens * row, U,
+        MP_HIPC(hipMemcpy2DAsync(ctx->Kfb, (size_t)ctx->FBcap * row, xk, (size_t)n_tokens * row, (size_t)n_tokens * row, U,
                                  hipMemcpyDeviceToDevice, s));
+        if (k_lookup)
+            MP_HIPC(hipMemcpy2DAsync(ctx->Kfs, (size_t)ctx->FBcap * row, k, (size_t)n_tokens * row, (size_t)n_tokens * row, U,
+                                     hipMemcpyDeviceToDevice, s));
         MP_HIPC(hipMemcpy2DAsync(ctx->Vfb, (size_t)ctx->FBcap * row, v, (size_t)n_tokens * row, (size_t)n_tokens * row, U,
                                  hipMemcpyDeviceToDevice, s));
     }
@@ -497,7 +510,7 @@ void update_seed_counts(const mp_ctx* ctx, int n_new, int n_new_fine, int n_new_
     }
 }
 
-mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* v_new, int32_t n_new, int32_t n_new_fine,
+mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* k_new_lookup, const void* v_new, int32_t n_new, int32_t n_new_fine,
                                int32_t n_new_coarse, int32_t refine_iters, int32_t split_iters, uint64_t seed,
                                const int32_t* seeds, hipStream_t s)
 {
@@ -550,8 +563,12 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* v_new
     const long long Fcap = ctx->Fcap, Ccap1 = std::max(ctx->Ccap, 1), Ncap = ctx->Ncap;
 
     // ---- append the new tokens to the sequence-ordered copy of the last block ----
-    MP_HIPC(hipMemcpy2DAsync((char*)ctx->Kfb + (size_t)nb_old * row, (size_t)ctx->FBcap * row, k_new, (size_t)n_new * row,
-                             (size_t)n_new * row, U, hipMemcpyDeviceToDevice, s));
+    MP_HIPC(hipMemcpy2DAsync((char*)ctx->Kfb + (size_t)nb_old * row, (size_t)ctx->FBcap * row,
+                             k_new_lookup ? k_new_lookup : k_new, (size_t)n_new * row, (size_t)n_new * row, U,
+                             hipMemcpyDeviceToDevice, s));
+    if (k_new_lookup)
+        MP_HIPC(hipMemcpy2DAsync((char*)ctx->Kfs + (size_t)nb_old * row, (size_t)ctx->FBcap * row, k_new, (size_t)n_new * row,
+                                 (size_t)n_new * row, U, hipMemcpyDeviceToDevice, s));
     MP_HIPC(hipMemcpy2DAsync((char*)ctx->Vfb + (size_t)nb_old * row, (size_t)ctx->FBcap * row, v_new, (size_t)n_new * row,
                              (size_t)n_new * row, U, hipMemcpyDeviceToDevice, s));
     // seeds of the new clusters, at their global ids
@@ -564,7 +581,7 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* v_new
 
     // block descriptors: slot 1 = [fine: all points of the last block | coarse], slot 0 (scratch) = appended points / new clusters
     Range r;
-    r.Xk = ctx->Kfb; r.Xv = ctx->Vfb; r.x_unit_rows = ctx->FBcap; r.pt0 = t0; r.n_pts = nb;
+    r.Xk = ctx->Kfb; r.Xs = k_new_lookup ? ctx->Kfs : ctx->Kfb; r.Xv = ctx->Vfb; r.x_unit_rows = ctx->FBcap; r.pt0 = t0; r.n_pts = nb;
     r.blocks.assign(1, BlockPlan{0, nb, f0, f1, c0, c1});
     r.f0 = f0; r.f1 = f1; r.c0 = c0; r.c1 = c1;
     int max_pts, max_kf, max_kc;
@@ -639,11 +656,18 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* v_new
         r2.blocks.push_back(BlockPlan{W, nb, f0 + cnts[2], f1, c0 + cnts[4], c1});
         st = cluster_range(ctx, r2, split_iters, s);
         if (st != MP_OK) return st;
-        // the remaining tokens become the new last block: move them to the front of Kfb / Vfb
-        MP_HIPC(hipMemcpy2DAsync(ctx->Kfb, (size_t)ctx->FBcap * row, (const char*)ctx->Kfb + (size_t)W * row,
-                                 (size_t)ctx->FBcap * row, (size_t)(nb - W) * row, U, hipMemcpyDeviceToDevice, s));
-        MP_HIPC(hipMemcpy2DAsync(ctx->Vfb, (size_t)ctx->FBcap * row, (const char*)ctx->Vfb + (size_t)W * row,
-                                 (size_t)ctx->FBcap * row, (size_t)(nb - W) * row, U, hipMemcpyDeviceToDevice, s));
+        // the remaining tokens become the new last block: move them to the front of the sequence-ordered
+        // copies, W rows at a time (a piece never overlaps its destination, W rows further down)
+        uint16_t* bufs[3] = {ctx->Kfb, ctx->Vfb, k_new_lookup ? ctx->Kfs : nullptr};
+        for (uint16_t* b : bufs) {
+            if (!b) continue;
+            for (int done = 0; done < nb - W; done += W) {
+                const int rows_now = std::min(W, nb - W - done);
+                MP_HIPC(hipMemcpy2DAsync((char*)b + (size_t)done * row, (size_t)ctx->FBcap * row,
+                                         (const char*)b + (size_t)(W + done) * row, (size_t)ctx->FBcap * row,
+                                         (size_t)rows_now * row, U, hipMemcpyDeviceToDevice, s));
+            }
+        }
         ctx->blocks.back() = BlockPlan{t0, t0 + W, f0, f0 + cnts[2], c0, c0 + cnts[4]};
         ctx->blocks.push_back(BlockPlan{t0 + W, t0 + nb, f0 + cnts[2], f1, c0 + cnts[4], c1});
     }

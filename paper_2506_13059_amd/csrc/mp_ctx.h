@@ -77,7 +77,8 @@ struct mp_ctx {
     int32_t* Ncl = nullptr;        // [U, tab_rows] member counts
 
     // ---- last block in sequence order (working set of the online update) ----
-    uint16_t* Kfb = nullptr;       // bf16 [U, FBcap, 128]
+    uint16_t* Kfb = nullptr;       // bf16 [U, FBcap, 128] keys the clusters are formed on (lookup keys if in use)
+    uint16_t* Kfs = nullptr;       // bf16 [U, FBcap, 128] the stored keys of the same tokens (only with lookup keys)
     uint16_t* Vfb = nullptr;
 
     // ---- k-means workspace ----
@@ -127,6 +128,8 @@ struct mp_ctx {
     uint16_t* Vt = nullptr;
     uint16_t* Kts = nullptr;       // bf16 [U, Tcap, 128] staging: the rows handed to the cluster update, packed
     uint16_t* Vts = nullptr;
+    uint16_t* Ktl = nullptr;       // lookup keys of the buffered tokens and their staging (only with lookup keys)
+    uint16_t* Ktls = nullptr;
     int32_t lb_window = 0, lb_sink = 0, lb_recent = 0;
 
     // ---- current index (host copies of sizes) ----

@@ -74,20 +74,43 @@ def check_output(out, ref, label=""):
     return err.max(), rel
 
 
+def rope(x, pos, base=10000.0):
+    """Rotary position embedding of x [..., n, d] at the integer positions pos [n] (channel j pairs
+    with channel j + d/2), rounded to bf16.  Input generation for the lookup-key tests: the stored
+    keys carry their own position, the lookup keys one fixed position."""
+    d = x.shape[-1]
+    inv = base ** (-torch.arange(0, d // 2, device=x.device, dtype=torch.float64) * 2 / d)
+    ang = pos.to(device=x.device, dtype=torch.float64)[:, None] * inv[None, :]
+    c, s = torch.cos(ang), torch.sin(ang)
+    x = x.to(torch.float64)
+    a, b = x[..., : d // 2], x[..., d // 2:]
+    return torch.cat([a * c - b * s, a * s + b * c], -1).to(torch.bfloat16)
+
+
+def signed_permutation(d, seed, device):
+    """x -> x[..., perm] * sign: exact in bf16, keeps every dot product and distance."""
+    g = torch.Generator().manual_seed(seed)
+    perm = torch.randperm(d, generator=g).to(device)
+    sign = (torch.randint(0, 2, (d,), generator=g) * 2 - 1).to(device=device, dtype=torch.bfloat16)
+    return lambda x: (x[..., perm] * sign).contiguous()
+
+
 def compare_decode(ctx, q, K, V, key_budget, coarse_budget=0, k_tail=None, v_tail=None, units=None, flags=0,
-                   label=""):
+                   label="", q_lookup=None):
     """Run mp_decode_attention and the oracle on the same inputs; assert the parity bar.
-    q [B,Hq,128], K/V [B,Hkv,n,128] (sequence order), tails [B,Hkv,nt,128]."""
+    q [B,Hq,128], K/V [B,Hkv,n,128] (sequence order, the stored keys), tails [B,Hkv,nt,128];
+    q_lookup [B,Hq,128]: the query the centroids are compared with (contexts with lookup keys)."""
     B, Hq, d = q.shape
     U, G = ctx.U, ctx.G
     lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device)
-    out = ctx.mp_decode_attention(q, key_budget, coarse_budget, k_tail, v_tail, lse=lse, flags=flags)
+    out = ctx.mp_decode_attention(q, key_budget, coarse_budget, k_tail, v_tail, lse=lse, flags=flags, q_lookup=q_lookup)
     sel = ctx.mp_get_selection()
     cnt = ctx.mp_get_counters()
     torch.cuda.synchronize()
     out64 = f64(out).reshape(U, G, d)
     lse64 = f64(lse).reshape(U, G)
     q64 = f64(q).reshape(U, G, d)
+    ql64 = f64(q_lookup).reshape(U, G, d) if q_lookup is not None else None
     Ku, Vu = K.reshape(U, -1, d), V.reshape(U, -1, d)
     fs, rf = sel["fine_selected"].cpu().numpy(), sel["r_fine"].cpu().numpy()
     two = ctx.cfg.levels == 2
@@ -101,7 +124,7 @@ def compare_decode(ctx, q, K, V, key_budget, coarse_budget=0, k_tail=None, v_tai
         Kx = f64(k_tail.reshape(U, -1, d)[u]) if k_tail is not None else None
         Vx = f64(v_tail.reshape(U, -1, d)[u]) if v_tail is not None else None
         res = O.decode_unit(q64[u], cl, key_budget, coarse_budget, Kx, Vx, scale=1 / math.sqrt(d),
-                            mp_terms=not (flags & 1))
+                            mp_terms=not (flags & 1), q_lookup=None if ql64 is None else ql64[u])
         exact = True
         if two:
             exact &= sets_match(cp[u], res["promising"], res["r_c"], f"{label} unit {u} coarse")

@@ -199,7 +199,7 @@ def test_tail_in_a_buffer_of_fixed_capacity():
         assert torch.equal(a, b), f"n_tail={n_tail}"
     with pytest.raises(mp.MpError):
         lib_call = mp.lib().mp_decode_attention      # 0 < tail_stride < n_tail is refused
-        st = lib_call(ctx.h, q[0].contiguous().data_ptr(), kt.data_ptr(), vt.data_ptr(), 8, 4, 100, 0, 0,
+        st = lib_call(ctx.h, q[0].contiguous().data_ptr(), None, kt.data_ptr(), vt.data_ptr(), 8, 4, 100, 0, 0,
                       torch.empty_like(q[0]).data_ptr(), None, None)
         mp._check(st, ctx.h)
     ctx.close()

@@ -9,38 +9,50 @@ import torch
 pytestmark = pytest.mark.gpu
 
 
-def _loop(levels, steps, L, n_sink, n_recent0):
+def _loop(levels, steps, L, n_sink, n_recent0, lookup=False):
+    """lookup: the stored keys carry a rotary embedding of their own position, the lookup keys and
+    the lookup query one of a fixed position (Sec. 3.1, last paragraph)."""
     from paper_2506_13059_amd import binding as mp, inputs
     from oracle import mp_oracle as O
-    from tests.gpu_util import f64, check_output, sets_match
+    from tests.gpu_util import f64, check_output, sets_match, rope
+
+    def stored_and_lookup(X, pos0):
+        if not lookup:
+            return X, None
+        return rope(X, pos0 + torch.arange(X.shape[-2])), rope(X, torch.full((X.shape[-2],), 4096))
     B, Hq, Hkv, n0, W, alpha = 1, 4, 2, 700, 512, 256
     nf, nc = 44, 6
     U, G = B * Hkv, Hq // Hkv
     seed = 41
     centers = inputs.make_modes(U, 40, "cuda", seed)
     K, V = inputs.draw_tokens(centers, n0, seed + 1)
+    K, KL = stored_and_lookup(K, 0)
     blocks = mp.mp_plan_blocks(n0, W, alpha, nf, nc if levels == 2 else 0)
     init_f, init_c = inputs.draw_seeds(U, blocks, levels, seed + 3)
     cap = n0 + steps + 2 * L
     ctx = mp.MpContext(B, Hq, Hkv, max_tokens=cap, levels=levels, max_fine=nf + 8 * (steps // L + 2),
                        max_coarse=(nc + 2 * (steps // L + 2)) if levels == 2 else 0, block_w=W, block_alpha=alpha,
-                       max_tail=n_sink + 2 * L)
+                       max_tail=n_sink + 2 * L, lookup_keys=lookup)
     ctx.mp_cluster_kv(K.view(B, Hkv, n0, 128), V.view(B, Hkv, n0, 128), nf, nc, iters=4, init_fine=init_f,
-                      init_coarse=init_c if levels == 2 else None)
+                      init_coarse=init_c if levels == 2 else None, k_lookup=KL.view(B, Hkv, n0, 128) if lookup else None)
     K64, V64 = f64(K), f64(V)
-    cls = [O.cluster_unit(K64[u], V64[u], blocks, init_f[u].numpy(), init_c[u].numpy() if levels == 2 else None, 4, levels)
-           for u in range(U)]
+    KL64 = f64(KL) if lookup else [None] * U
+    cls = [O.cluster_unit(K64[u], V64[u], blocks, init_f[u].numpy(), init_c[u].numpy() if levels == 2 else None, 4, levels,
+                          K_lookup=KL64[u]) for u in range(U)]
     g = torch.Generator(device="cuda").manual_seed(seed + 5)
     ks = torch.randn(B, Hkv, n_sink, 128, generator=g, device="cuda").to(torch.bfloat16)
     vs = torch.randn(B, Hkv, n_sink, 128, generator=g, device="cuda").to(torch.bfloat16)
     kr, vr = inputs.draw_tokens(centers, max(n_recent0, 1), seed + 6)
-    kr, vr = kr[:, :n_recent0].reshape(B, Hkv, n_recent0, 128), vr[:, :n_recent0].reshape(B, Hkv, n_recent0, 128)
+    kr, krl = stored_and_lookup(kr[:, :n_recent0], n0)
+    kr, vr = kr.reshape(B, Hkv, n_recent0, 128), vr[:, :n_recent0].reshape(B, Hkv, n_recent0, 128)
     ctx.mp_local_buffer_init(L, ks if n_sink else None, vs if n_sink else None, kr.contiguous() if n_recent0 else None,
-                             vr.contiguous() if n_recent0 else None)
+                             vr.contiguous() if n_recent0 else None,
+                             k_recent_lookup=krl.reshape(B, Hkv, n_recent0, 128).contiguous() if lookup and n_recent0 else None)
     # the oracle's view of the buffer: per unit lists of rows (fp64)
     sink_k, sink_v = f64(ks).reshape(U, n_sink, 128), f64(vs).reshape(U, n_sink, 128)
     rec_k = [list(f64(kr).reshape(U, n_recent0, 128)[u]) for u in range(U)]
     rec_v = [list(f64(vr).reshape(U, n_recent0, 128)[u]) for u in range(U)]
+    rec_kl = [list(f64(krl).reshape(U, n_recent0, 128)[u]) if lookup else [] for u in range(U)]
     rng = np.random.default_rng(seed)
     kb, cb = 96, 260
     refreshes = 0
@@ -48,6 +60,9 @@ def _loop(levels, steps, L, n_sink, n_recent0):
         centers = inputs.drift_modes(centers, seed + 100 + t)
         kn, vn = inputs.draw_tokens(centers, 1, seed + 200 + t)
         q = inputs.draw_queries(centers, G, 1, seed + 300 + t, softness=0.4).view(B, Hq, 128)
+        pos = n0 + n_recent0 + t
+        kn, knl = stored_and_lookup(kn, pos)
+        q, ql = (rope(q, torch.full((Hq,), pos)), rope(q, torch.full((Hq,), 4100))) if lookup else (q, None)
         size = ctx.mp_local_buffer_size()
         assert size == dict(window=L, n_sink=n_sink, n_recent=len(rec_k[0]))
         will_refresh = size["n_recent"] + 1 == 2 * L
@@ -62,24 +77,29 @@ def _loop(levels, steps, L, n_sink, n_recent0):
         lse = torch.empty(B, Hq, dtype=torch.float32, device="cuda")
         out = ctx.mp_decode_step(q, kn.view(B, Hkv, 1, 128), vn.view(B, Hkv, 1, 128), kb, cb, n_new_fine=3,
                                  n_new_coarse=1 if levels == 2 else 0, refine_iters=2, split_iters=4,
-                                 seeds=None if seeds is None else torch.tensor(seeds), lse=lse)
+                                 seeds=None if seeds is None else torch.tensor(seeds), lse=lse, q_lookup=ql,
+                                 k_new_lookup=knl.view(B, Hkv, 1, 128) if lookup else None)
         sel = ctx.mp_get_selection() if not will_refresh else None      # (the refresh re-numbers clusters)
         torch.cuda.synchronize()
         kn64, vn64, q64 = f64(kn).reshape(U, 128), f64(vn).reshape(U, 128), f64(q).reshape(U, G, 128)
+        knl64, ql64 = (f64(knl).reshape(U, 128), f64(ql).reshape(U, G, 128)) if lookup else (None, [None] * U)
         for u in range(U):
             rec_k[u].append(kn64[u])
             rec_v[u].append(vn64[u])
+            if lookup:
+                rec_kl[u].append(knl64[u])
             Kx = np.concatenate([sink_k[u], np.stack(rec_k[u])]) if n_sink else np.stack(rec_k[u])
             Vx = np.concatenate([sink_v[u], np.stack(rec_v[u])]) if n_sink else np.stack(rec_v[u])
-            res = O.decode_unit(q64[u], cls[u], kb, cb, Kx, Vx)
+            res = O.decode_unit(q64[u], cls[u], kb, cb, Kx, Vx, q_lookup=ql64[u])
             check_output(f64(out).reshape(U, G, 128)[u], res["out"], f"step {t} unit {u}")
             np.testing.assert_allclose(lse.view(U, G)[u].cpu().numpy(), res["lse"], rtol=3e-5, atol=3e-4)
             if sel is not None:
                 assert sets_match(sel["fine_selected"][u].cpu().numpy(), res["selected"], res["r_f"], f"step {t} unit {u}")
             if will_refresh:
                 cls[u] = O.update_unit(cls[u], np.stack(rec_k[u][:L]), np.stack(rec_v[u][:L]), 3, 1 if levels == 2 else 0,
-                                       seeds[u], 2, W, alpha, split_iters=4)
-                rec_k[u], rec_v[u] = rec_k[u][L:], rec_v[u][L:]
+                                       seeds[u], 2, W, alpha, split_iters=4,
+                                       K_new_lookup=np.stack(rec_kl[u][:L]) if lookup else None)
+                rec_k[u], rec_v[u], rec_kl[u] = rec_k[u][L:], rec_v[u][L:], rec_kl[u][L:]
         refreshes += will_refresh
     sizes = ctx.mp_get_sizes()
     assert sizes["n_tokens"] == n0 + refreshes * L == cls[0]["K"].shape[0]
@@ -122,3 +142,8 @@ def test_local_buffer_argument_errors():
         ctx.mp_decode_step(q, z[:, :, :1].contiguous(), z[:, :, :1].contiguous(), 8)   # no index yet
     assert e.value.status == mp.MP_ESTATE
     ctx.close()
+
+
+def test_generation_with_lookup_keys_and_a_lookup_query():
+    refreshes, sizes = _loop(levels=2, steps=80, L=16, n_sink=3, n_recent0=20, lookup=True)
+    assert refreshes == 5 and sizes["n_blocks"] == 2

@@ -40,29 +40,45 @@ def _compare_index(ctx, cls, levels, label):
             np.testing.assert_allclose(kcc[u][live], cl["Kc_c"][live], rtol=2.0 ** -7, atol=1e-30)
 
 
-def _chain(B, Hq, Hkv, n0, modes, levels, nf, nc, W, alpha, iters, updates, seed, max_tokens, max_fine, max_coarse):
-    """updates: list of (n_new, n_new_fine, n_new_coarse, refine_iters)."""
+def _chain(B, Hq, Hkv, n0, modes, levels, nf, nc, W, alpha, iters, updates, seed, max_tokens, max_fine, max_coarse,
+           lookup=None):
+    """updates: list of (n_new, n_new_fine, n_new_coarse, refine_iters).  lookup: None, or how the
+    lookup keys relate to the stored keys: "rope" (stored keys rotated to their own position, lookup
+    keys to one fixed position, Sec. 3.1 last paragraph) or "perm" (a signed permutation)."""
     from paper_2506_13059_amd import binding as mp, inputs
     from oracle import mp_oracle as O
-    from tests.gpu_util import f64
+    from tests.gpu_util import f64, rope, signed_permutation
     U = B * Hkv
     centers = inputs.make_modes(U, modes, "cuda", seed)
     K, V = inputs.draw_tokens(centers, n0, seed + 1)
+    A = signed_permutation(128, seed, "cuda")
+
+    def stored_and_lookup(X, pos0):
+        if lookup == "rope":
+            return rope(X, pos0 + torch.arange(X.shape[1])), rope(X, torch.full((X.shape[1],), 4096))
+        if lookup == "perm":
+            return X, A(X)
+        return X, None
+
+    K, KL = stored_and_lookup(K, 0)
+    lk = (lambda t, n: None) if lookup is None else (lambda t, n: t.view(B, Hkv, n, 128))
     blocks = mp.mp_plan_blocks(n0, W, alpha, nf, nc if levels == 2 else 0)
     init_f, init_c = inputs.draw_seeds(U, blocks, levels, seed + 3)
     ctx = mp.MpContext(B, Hq, Hkv, max_tokens=max_tokens, levels=levels, max_fine=max_fine, max_coarse=max_coarse,
-                       block_w=W, block_alpha=alpha, max_tail=0)
+                       block_w=W, block_alpha=alpha, max_tail=0, lookup_keys=lookup is not None)
     ctx.mp_cluster_kv(K.view(B, Hkv, n0, 128), V.view(B, Hkv, n0, 128), nf, nc, iters=iters, init_fine=init_f,
-                      init_coarse=init_c if levels == 2 else None)
+                      init_coarse=init_c if levels == 2 else None, k_lookup=lk(KL, n0))
     K64, V64 = f64(K), f64(V)
+    KL64 = f64(KL) if lookup else [None] * U
     cls = [O.cluster_unit(K64[u], V64[u], blocks, init_f[u].numpy(), init_c[u].numpy() if levels == 2 else None,
-                          iters, levels) for u in range(U)]
+                          iters, levels, K_lookup=KL64[u]) for u in range(U)]
     _compare_index(ctx, cls, levels, "after build")
     rng = np.random.default_rng(seed)
     for step, (n_new, nnf, nnc, refine) in enumerate(updates):
         print(f"update {step}: +{n_new} tokens, +{nnf} fine, +{nnc} coarse, refine {refine}", flush=True)
         centers = inputs.drift_modes(centers, seed + 100 + step)
         Kn, Vn = inputs.draw_tokens(centers, n_new, seed + 200 + step)
+        Kn, KLn = stored_and_lookup(Kn, cls[0]["K"].shape[0])
         counts = ctx.mp_update_seed_counts(n_new, nnf, nnc)
         assert counts == O.update_seed_counts(cls[0]["blocks"], n_new, nnf, nnc, W, alpha, levels)
         nb = cls[0]["blocks"][-1]["t1"] - cls[0]["blocks"][-1]["t0"] + n_new
@@ -70,10 +86,11 @@ def _chain(B, Hq, Hkv, n0, modes, levels, nf, nc, W, alpha, iters, updates, seed
         seeds = np.stack([np.concatenate([rng.choice(max(l, 1), c, replace=False) for l, c in zip(lims, counts)])
                           for _ in range(U)]).astype(np.int32)
         ctx.mp_update_clusters(Kn.view(B, Hkv, n_new, 128), Vn.view(B, Hkv, n_new, 128), nnf, nnc, refine_iters=refine,
-                               split_iters=iters, seeds=torch.tensor(seeds))
+                               split_iters=iters, seeds=torch.tensor(seeds), k_new_lookup=lk(KLn, n_new))
         Kn64, Vn64 = f64(Kn), f64(Vn)
-        cls = [O.update_unit(cls[u], Kn64[u], Vn64[u], nnf, nnc, seeds[u], refine, W, alpha, split_iters=iters)
-               for u in range(U)]
+        KLn64 = f64(KLn) if lookup else [None] * U
+        cls = [O.update_unit(cls[u], Kn64[u], Vn64[u], nnf, nnc, seeds[u], refine, W, alpha, split_iters=iters,
+                             K_new_lookup=KLn64[u]) for u in range(U)]
         _compare_index(ctx, cls, levels, f"after update {step}")
     return ctx, cls, centers
 

@@ -62,9 +62,9 @@ def test_create_rejects_bad_configs_without_a_gpu(lib):
 
 def test_null_context_calls_fail_cleanly(lib):
     from paper_2506_13059_amd import binding as mp
-    assert lib.mp_decode_attention(None, None, None, None, 0, 0, 0, 0, 0, None, None, None) == mp.MP_EINVAL
-    assert lib.mp_cluster_kv(None, None, None, 1, 1, 0, 1, 0, None, None, None) == mp.MP_EINVAL
-    assert lib.mp_update_clusters(None, None, None, 1, 0, 0, 0, 1, 0, None, None) == mp.MP_EINVAL
+    assert lib.mp_decode_attention(None, None, None, None, None, 0, 0, 0, 0, 0, None, None, None) == mp.MP_EINVAL
+    assert lib.mp_cluster_kv(None, None, None, None, 1, 1, 0, 1, 0, None, None, None) == mp.MP_EINVAL
+    assert lib.mp_update_clusters(None, None, None, None, 1, 0, 0, 0, 1, 0, None, None) == mp.MP_EINVAL
     assert lib.mp_dense_attention(None, None, None, 1, 1, 1, 1, 0.0, None, None, None, 0, None) == mp.MP_EINVAL
     assert b"null" in lib.mp_last_error(None)
     lib.mp_destroy(None)
