@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--no-online", action="store_true", help="skip the online-generation (cfg4_online) extra")
     ap.add_argument("--only-online", action="store_true",
                     help="run only the online-generation workload and print its record (for profiling)")
+    ap.add_argument("--error-study", action="store_true",
+                    help="instead of timing: output error against dense attention over key budgets, with and without "
+                         "the centroid terms of Eq. 2, one and two levels, on inputs with two scales of structure")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
     args = ap.parse_args()
@@ -71,6 +74,9 @@ def main():
     dev = "cuda"
     if args.only_online:
         print(json.dumps(online_generation(mp, inputs, dev)))
+        return
+    if args.error_study:
+        print(json.dumps(error_study(mp, inputs, dev)))
         return
     w = inputs.WORKLOADS[args.workload]
     n_sets = 16
@@ -134,6 +140,25 @@ def main():
                            vp_bytes=vp_bytes, gbps=step_bytes / us / 1e3,
                            vp_gbps=vp_bytes / (stage["value_ms"] * 1e3) / 1e3 if stage["value_ms"] > 0 else 0.0)
 
+    # the same step replayed from a HIP graph (16 steps, one per query set, captured once): what a
+    # multi-layer decode loop that captures its launches would see
+    kb0 = w.key_budgets[0]
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(n_sets):
+            ctx.mp_decode_attention(Q[i], kb0, args.coarse_mult * kb0, out=out)
+    n_rep = max(2, args.steps // n_sets)
+    graph.replay()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(n_rep):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    graph_us = e0.elapsed_time(e1) / (n_rep * n_sets) * 1e3
+    del graph
+
     # dense comparison kernel, same tensors
     ws = torch.empty(max(mp.mp_dense_workspace_bytes(w.batch, w.n_q_heads, w.n_kv_heads, w.context), 16),
                      dtype=torch.uint8, device=dev)
@@ -150,7 +175,6 @@ def main():
     dense_bytes = 2 * K.numel() * 2
     dense_gbps = dense_bytes / dense_us / 1e3
 
-    kb0 = w.key_budgets[0]
     r0 = results[kb0]
 
     cpu = None
@@ -178,6 +202,7 @@ def main():
         "achieved_hbm_frac_of_peak": round(r0["gbps"] / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": int(r0["step_bytes"]),
         "stage_us": {k_: round(v, 2) for k_, v in r0["stage_us"].items()},
+        "graph_replay_us_per_step": round(graph_us, 2),
         "dense_us_per_step": round(dense_us, 2),
         "dense_hbm_gbps": round(dense_gbps, 1),
         "speedup_vs_dense": round(dense_us / r0["us"], 3),
@@ -264,6 +289,57 @@ def online_generation(mp, inputs, dev):
             "total_us_per_token": round(total_us, 2),
             "update_share": round(update_us / L / total_us, 4),
             "wall_us_per_token_incl_input_generation": round(wall * 1e6 / w.gen_tokens, 1)}
+
+
+def error_study(mp, inputs, dev, context=32768, n_fine=4096, n_coarse=512, modes=2048, fan=16, n_sets=16,
+                softness=(0.2, 0.35), seed=77):
+    """Output error of the decode step against dense attention (the library's own dense kernel, on the
+    same tensors), as the key budget grows: with the centroid terms of Eq. 2 and with the flag that
+    drops them (retrieval only, the comparison of the paper's ablation), for a one-level and a
+    two-level index.  1 sequence, 32 query / 8 KV heads, 32K tokens; one fine centroid per 8 tokens
+    and one coarse centroid per 64 tokens (the ratios of Sec. 5.1), clustered in blocks of 8192
+    tokens; keys and values come from 2048 modes in 128 families, two scales of structure
+    (inputs.make_tree_modes), because on modes drawn independently a coarse centroid says nothing
+    about a query's mode.  A query is softness x (a mode center + noise): the smaller, the flatter its
+    attention and the more mass sits outside the retrieved keys.  error = mean over heads and query
+    sets of |out - dense|_2 / |dense|_2; keys_read / centroids_scored = exactly attended keys /
+    centroids compared with the query, per unit, averaged."""
+    import torch
+    B, Hq, Hkv = 1, 32, 8
+    U, G = B * Hkv, Hq // Hkv
+    kc, vc = inputs.make_tree_modes(U, modes, fan, dev, seed)
+    K, V = inputs.draw_tokens(kc, context, seed + 1, value_centers=vc)
+    K, V = K.view(B, Hkv, context, 128), V.view(B, Hkv, context, 128)
+    Qs = [inputs.draw_queries(kc, G, n_sets, seed + 2, softness=sf).view(n_sets, B, Hq, 128) for sf in softness]
+    blocks = inputs.plan_blocks(context, 8192, 4096, n_fine, n_coarse)
+    denses = [[mp.mp_dense_attention(Q[i], K, V).float() for i in range(n_sets)] for Q in Qs]
+    rows = []
+    budgets = [context // f for f in (128, 64, 32, 16, 8, 4)]
+    for levels in (1, 2):
+        init_f, init_c = inputs.draw_seeds(U, blocks, levels, seed + 3)
+        ctx = mp.MpContext(B, Hq, Hkv, max_tokens=context, levels=levels, max_fine=n_fine,
+                           max_coarse=n_coarse if levels == 2 else 0, block_w=8192, block_alpha=4096)
+        ctx.mp_cluster_kv(K, V, n_fine, n_coarse if levels == 2 else 0, iters=10, init_fine=init_f,
+                          init_coarse=init_c if levels == 2 else None)
+        for sf, Q, dense in zip(softness, Qs, denses):
+            for kb in budgets:
+                rec = dict(levels=levels, softness=sf, key_budget=kb)
+                for name, flags in (("multipole", 0), ("retrieval_only", 1)):
+                    err, keys, scored = 0.0, 0.0, 0.0
+                    for i in range(n_sets):
+                        out = ctx.mp_decode_attention(Q[i], kb, 4 * kb if levels == 2 else 0, flags=flags).float()
+                        err += float(((out - dense[i]).norm(dim=-1) / dense[i].norm(dim=-1)).mean())
+                        cnt = ctx.mp_get_counters().float().mean(dim=0)
+                        keys += float(cnt[0])
+                        scored += float(cnt[1] + cnt[2])
+                    rec[name + "_rel_err"] = round(err / n_sets, 5)
+                    rec["keys_read"] = round(keys / n_sets, 1)
+                    rec["centroids_scored"] = round(scored / n_sets, 1)
+                rows.append(rec)
+        ctx.close()
+    return dict(study="output error against dense attention", data="synthetic, modes with two scales of structure",
+                context=context, n_fine=n_fine, n_coarse=n_coarse, modes=modes, modes_per_family=fan, query_sets=n_sets,
+                coarse_budget="4 x key budget", rows=rows)
 
 
 def measured_traffic(workload, key_budget):

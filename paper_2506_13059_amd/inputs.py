@@ -76,8 +76,27 @@ def make_modes(units: int, modes: int, device, seed: int):
     return centers
 
 
-def draw_tokens(centers: torch.Tensor, n_tokens: int, seed: int, noise: float = 0.3, chunk_units: int = 8):
-    """Keys and values for every unit: K, V bf16 [units, n_tokens, 128]."""
+def make_tree_modes(units: int, modes: int, fan: int, device, seed: int, spread: float = 0.6):
+    """Mode centers with two scales of structure, for accuracy studies: modes / fan parent centers
+    2*N(0,1)*sqrt(1 - spread^2), every mode = its parent + 2*N(0,1)*spread (same overall variance as
+    :func:`make_modes`, no outlier channels).  Returns key centers and, drawn the same way from other
+    random numbers, value centers (both [units, modes, 128] fp32), so that tokens of one mode, and
+    to a lesser degree of sibling modes, carry similar values."""
+    g = _gen(device, seed)
+    parents = modes // fan
+    out = []
+    for _ in range(2):
+        top = 2.0 * (1.0 - spread * spread) ** 0.5 * torch.randn(units, parents, 1, HEAD_DIM, generator=g, device=device)
+        sub = 2.0 * spread * torch.randn(units, parents, fan, HEAD_DIM, generator=g, device=device)
+        out.append((top + sub).reshape(units, parents * fan, HEAD_DIM))
+    return out[0], out[1]
+
+
+def draw_tokens(centers: torch.Tensor, n_tokens: int, seed: int, noise: float = 0.3, chunk_units: int = 8,
+                value_centers: torch.Tensor = None, value_scale: float = 0.5):
+    """Keys and values for every unit: K, V bf16 [units, n_tokens, 128].  With value_centers
+    ([units, modes, 128]) a token's value is value_scale * (the value center of its mode + N(0,1))
+    instead of plain N(0,1)."""
     units, modes, d = centers.shape
     device = centers.device
     g = _gen(device, seed)
@@ -90,8 +109,11 @@ def draw_tokens(centers: torch.Tensor, n_tokens: int, seed: int, noise: float = 
         k = torch.gather(centers[u0:u1], 1, idx)
         k += noise * torch.randn(u1 - u0, n_tokens, d, generator=g, device=device)
         K[u0:u1] = k.to(torch.bfloat16)
+        v = torch.randn(u1 - u0, n_tokens, d, generator=g, device=device)
+        if value_centers is not None:
+            v = value_scale * (v + torch.gather(value_centers[u0:u1], 1, idx))
         del k, idx, mode
-        V[u0:u1] = torch.randn(u1 - u0, n_tokens, d, generator=g, device=device).to(torch.bfloat16)
+        V[u0:u1] = v.to(torch.bfloat16)
     return K, V
 
 
