@@ -21,6 +21,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# mp_assign.hip: keep the MFMA accumulators in ordinary vector registers; the comparison code reads
+# every one of them, and copying them out of accumulation registers costs an instruction each
+EXTRA_FLAGS = {"mp_assign.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def _headers():
     hs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     hs.append(os.path.join(os.path.dirname(HERE), "include", "mp.h"))
@@ -32,7 +37,7 @@ def _compile(src, force):
     o = os.path.join(OBJ, src + ".o")
     newest = max([os.path.getmtime(s)] + [os.path.getmtime(h) for h in _headers()])
     if force or not os.path.exists(o) or os.path.getmtime(o) < newest:
-        cmd = ["hipcc", *FLAGS, "-c", s, "-o", o]
+        cmd = ["hipcc", *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", s, "-o", o]
         r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
         out = "\n".join(l for l in r.stdout.splitlines() if "not a recognized feature" not in l)
         if r.returncode != 0:

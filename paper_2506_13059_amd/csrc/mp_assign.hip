@@ -7,9 +7,12 @@
 // can change the answer:
 //
 //   1. assign_mfma_kernel: s[t,j] = x_t.c_j - |c_j|^2/2 (argmax = nearest centroid) with
-//      v_mfma_f32_32x32x16_bf16, fp32 accumulation.  Per point it keeps the best and the second
-//      best score.  The products are exact and every one of the 128 accumulation steps loses at
-//      most one unit in the last place of a partial sum bounded by |x||c|, so each score is within
+//      v_mfma_f32_32x32x16_bf16, fp32 accumulation.  The offset -|c_j|^2/2 is part of the
+//      contraction: split exactly into three bf16 values, it sits in three extra slots of the
+//      reduction dimension against ones on the point side, so the scores leave the matrix cores
+//      complete.  Per point the kernel keeps the best and the second best score.  The products
+//      are exact and every one of the 131 accumulation steps loses at most one unit in the last
+//      place of a partial sum bounded by max(|x||c|, |c|^2/2), so each score is within
 //      2^-16 max(|x|^2, max_j |c_j|^2) of its exact value (2^-19 more for four mantissa bits that
 //      carry an index during the comparison).  A point whose two best scores are
 //      further apart than 2^-13 of that scale has a unique nearest centroid in exact arithmetic
@@ -31,7 +34,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kTile = 32;                 // centroids per tile = rows of the MFMA A operand
-constexpr int kRowBytes = 256 + 16;       // padded LDS row of one centroid
+constexpr int kRowBytes = 256 + 16;       // LDS row of one centroid: 128 dims, then -|c|^2/2 as three bf16 and five zeros
 constexpr float kMarginScale = 1.0f / 8192.0f;   // 2^-13
 constexpr float kNoCentroid = -3.0e38f;          // score of a padded row (finite: index bits are packed into scores)
 
@@ -50,7 +53,7 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
                                                           int32_t* __restrict__ amb_cnt, int cnt_stride)
 {
     __shared__ __align__(16) unsigned char tile[2][kTile * kRowBytes];
-    __shared__ __align__(16) float tile_c2[2][kTile];    // -|c|^2 / 2, kNoCentroid past the last centroid
+    __shared__ float wave_c2max[4];
     const int u = blockIdx.z, b = blockIdx.y;
     const int x0 = blocks[4 * b + 0], x1 = blocks[4 * b + 1], k0 = blocks[4 * b + 2], k1 = blocks[4 * b + 3];
     const int p0 = x0 + (int)blockIdx.x * kPtsPerWg;
@@ -72,18 +75,21 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
         for (int ks = 0; ks < 8; ++ks) {
             const uint4 w = xp[2 * ks + half];
             xb[c][ks] = __builtin_bit_cast(bf16x8_t, w);
-            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float lo = bf16lo_to_f32(ww[e]), hi = bf16hi_to_f32(ww[e]);
-                x2[c] = fmaf(lo, lo, x2[c]);
-                x2[c] = fmaf(hi, hi, x2[c]);
-            }
+            x2[c] = dot2_bf16(w.x, w.x, x2[c]);      // |x|^2 only scales the margin
+            x2[c] = dot2_bf16(w.y, w.y, x2[c]);
+            x2[c] = dot2_bf16(w.z, w.z, x2[c]);
+            x2[c] = dot2_bf16(w.w, w.w, x2[c]);
         }
     }
+    // point side of the three offset slots: ones in the slots of the lower half-wave, zeros elsewhere
+    const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, half == 0 ? make_uint4(0x3f803f80u, 0x00003f80u, 0u, 0u)
+                                                                  : make_uint4(0u, 0u, 0u, 0u));
+    bf16x8_t ones_too = ones;      // a second copy the compiler cannot see through: two multiplications
+    asm volatile("" : "+v"(ones_too));   // on the otherwise idle matrix pipe instead of sixteen register moves
     // this thread's share of a centroid tile: two 16-byte pieces, 16 threads per row
     const uint16_t* Cu = C + (long long)u * c_unit_rows * kHeadDim;
     uint4 pre[2];
+    float c2max = 0.f;
     auto request = [&](int j0) {
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
@@ -100,20 +106,27 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
             const int row = e >> 4, seg = e & 15;
             const uint4 w = pre[pass];
             *reinterpret_cast<uint4*>(tile[buf] + row * kRowBytes + seg * 16) = w;
-            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-            float s = 0.f;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float lo = bf16lo_to_f32(ww[q]), hi = bf16hi_to_f32(ww[q]);
-                s = fmaf(lo, lo, s);
-                s = fmaf(hi, hi, s);
-            }
+            // |c|^2 from exact products, a dozen fp32 roundings: at most 2^-20 of its value, far below
+            // the bound on a score
+            float s = dot2_bf16(w.x, w.x, 0.f);
+            s = dot2_bf16(w.y, w.y, s);
+            s = dot2_bf16(w.z, w.z, s);
+            s = dot2_bf16(w.w, w.w, s);
             s = sum8(s);
             s += dpp_f32<kDppMirror>(s);      // the other 8 lanes of the row of 16
-            if (seg == 0) tile_c2[buf][row] = (j0 + row < k1) ? -0.5f * s : kNoCentroid;
+            c2max = fmaxf(c2max, s);          // (rows past the last centroid are zeros)
+            if (seg == 0) {
+                // v = hi + mid + lo exactly: 24 significant bits in three pieces of 8
+                const float v = (j0 + row < k1) ? -0.5f * s : kNoCentroid;
+                const uint32_t hi = __float_as_uint(v) & 0xffff0000u;
+                const float r1 = v - __uint_as_float(hi);
+                const uint32_t mid = __float_as_uint(r1) & 0xffff0000u;
+                const uint32_t lo = __float_as_uint(r1 - __uint_as_float(mid)) & 0xffff0000u;
+                *reinterpret_cast<uint4*>(tile[buf] + row * kRowBytes + 256) = make_uint4((hi >> 16) | mid, lo >> 16, 0u, 0u);
+            }
         }
     };
-    float best[2] = {-INFINITY, -INFINITY}, second[2] = {-INFINITY, -INFINITY}, c2max = 0.f;
+    float best[2] = {-INFINITY, -INFINITY}, second[2] = {-INFINITY, -INFINITY};
     int btile[2] = {k0, k0};
     request(k0);
     deposit(k0, 0);
@@ -123,21 +136,37 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
         const bool more = j0 + kTile < k1;
         if (more) request(j0 + kTile);
         // accumulator rows of this lane: m(i) = 8 (i / 4) + 4 half + i % 4
+        // (fragments are read a batch ahead of the multiplications that use them)
         f32x16_t acc[2];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const float4 c = *reinterpret_cast<const float4*>(&tile_c2[buf][8 * g + 4 * half]);
-            acc[0][4 * g + 0] = c.x; acc[0][4 * g + 1] = c.y; acc[0][4 * g + 2] = c.z; acc[0][4 * g + 3] = c.w;
-        }
-        acc[1] = acc[0];
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-            if (acc[0][i] > kNoCentroid) c2max = fmaxf(c2max, -2.f * acc[0][i]);
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(tile[buf] + col * kRowBytes + 32 * ks + 16 * half);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[0][ks], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[1][ks], acc[1], 0, 0, 0);
+        const unsigned char* arow = tile[buf] + col * kRowBytes + 16 * half;
+        auto frag = [&](int ks) { return *reinterpret_cast<const bf16x8_t*>(arow + 32 * ks); };
+        {
+            const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            const bf16x8_t a_off = *reinterpret_cast<const bf16x8_t*>(tile[buf] + col * kRowBytes + 256);
+            const bf16x8_t a0 = frag(0), a1 = frag(1), a2 = frag(2), a3 = frag(3), a4 = frag(4);
+            __builtin_amdgcn_sched_barrier(0);      // (keeps the compiler from pairing every read with its use again)
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_off, ones, zero, 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_off, ones_too, zero, 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, xb[0][0], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, xb[1][0], acc[1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            const bf16x8_t a5 = frag(5), a6 = frag(6), a7 = frag(7);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xb[0][1], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xb[1][1], acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, xb[0][2], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, xb[1][2], acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, xb[0][3], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, xb[1][3], acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a4, xb[0][4], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a4, xb[1][4], acc[1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a5, xb[0][5], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a5, xb[1][5], acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a6, xb[0][6], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a6, xb[1][6], acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a7, xb[0][7], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a7, xb[1][7], acc[1], 0, 0, 0);
         }
         // best and second best per point.  The slot i of a score inside the tile rides in its four
         // lowest mantissa bits (a change of at most 2^-19 of its magnitude), so that a pair of scores
@@ -157,8 +186,12 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
         if (more) deposit(j0 + kTile, buf ^ 1);
         __syncthreads();
     }
+    // largest |c|^2 of the block: every thread saw the rows it deposited
+    c2max = wave_max_f32(c2max);
+    if (lane == 0) wave_c2max[wave] = c2max;
+    __syncthreads();
+    c2max = fmaxf(fmaxf(wave_c2max[0], wave_c2max[1]), fmaxf(wave_c2max[2], wave_c2max[3]));
     // the two halves of the wave hold the other rows of the same points
-    c2max = fmaxf(c2max, __shfl_xor(c2max, 32, 64));
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
         const int slot = (int)(__float_as_uint(best[c]) & 15u);
