@@ -39,8 +39,8 @@ constexpr float kMarginScale = 1.0f / 8192.0f;   // 2^-13
 constexpr float kNoCentroid = -3.0e38f;          // score of a padded row (finite: index bits are packed into scores)
 
 // grid = (ceil(max points per block / 256), nb, U); 256 threads = 4 waves of 64 points (two MFMA
-// column tiles that share every centroid fragment).  Centroid tiles are double-buffered in LDS: the
-// rows of the next tile are requested before the current tile is multiplied and stored after it.
+// column tiles that share every centroid fragment).  Centroid tiles are double-buffered in LDS; their
+// rows are requested two tiles ahead and wait in registers until the buffer they go to is free.
 // blocks: int32 [nb][4] = {first point, end point, first centroid, end centroid}.
 // assign[u][t] receives the best centroid of stage 1; amb_list[u][first point + i], i < amb_cnt[u][b],
 // the points of block b that stage 2 has to decide.
@@ -88,23 +88,26 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
     asm volatile("" : "+v"(ones_too));   // on the otherwise idle matrix pipe instead of sixteen register moves
     // this thread's share of a centroid tile: two 16-byte pieces, 16 threads per row
     const uint16_t* Cu = C + (long long)u * c_unit_rows * kHeadDim;
-    uint4 pre[2];
+    uint4 pre_a[2], pre_b[2];     // rows on their way to LDS: the next tile and the one after it
     float c2max = 0.f;
-    auto request = [&](int j0) {
+    auto request = [&](int j0, uint4 (&pre)[2]) {
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
             const int e = pass * 256 + tid;
             const int row = e >> 4, seg = e & 15;
-            pre[pass] = make_uint4(0, 0, 0, 0);
-            if (j0 + row < k1) pre[pass] = reinterpret_cast<const uint4*>(Cu + (long long)(j0 + row) * kHeadDim)[seg];
+            // always a load (of the last centroid when the row does not exist; deposit stores zeros for
+            // it): the count of loads in flight is then the same on every path, which is what lets
+            // the compiler wait for the older request only
+            const int j = j0 + row < k1 ? j0 + row : k1 - 1;
+            pre[pass] = reinterpret_cast<const uint4*>(Cu + (long long)j * kHeadDim)[seg];
         }
     };
-    auto deposit = [&](int j0, int buf) {
+    auto deposit = [&](int j0, int buf, const uint4 (&pre)[2]) {
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
             const int e = pass * 256 + tid;
             const int row = e >> 4, seg = e & 15;
-            const uint4 w = pre[pass];
+            const uint4 w = (j0 + row < k1) ? pre[pass] : make_uint4(0, 0, 0, 0);
             *reinterpret_cast<uint4*>(tile[buf] + row * kRowBytes + seg * 16) = w;
             // |c|^2 from exact products, a dozen fp32 roundings: at most 2^-20 of its value, far below
             // the bound on a score
@@ -128,45 +131,30 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
     };
     float best[2] = {-INFINITY, -INFINITY}, second[2] = {-INFINITY, -INFINITY};
     int btile[2] = {k0, k0};
-    request(k0);
-    deposit(k0, 0);
+    // Rows are requested two tiles ahead: a tile's multiplications take less time than a load from
+    // L2 under the traffic of the other workgroups' point loads.
+    request(k0, pre_a);
+    request(k0 + kTile, pre_b);
+    deposit(k0, 0, pre_a);
     __syncthreads();
-    int buf = 0;
-    for (int j0 = k0; j0 < k1; j0 += kTile, buf ^= 1) {
+    // one tile: `next` holds the rows of the following tile, `after` receives those of the one after it
+    auto step = [&](int j0, int buf, uint4 (&after)[2], const uint4 (&next)[2]) {
         const bool more = j0 + kTile < k1;
-        if (more) request(j0 + kTile);
+        request(j0 + 2 * kTile, after);
+        __builtin_amdgcn_sched_barrier(0);      // (the compiler would sink the loads below the multiplications)
         // accumulator rows of this lane: m(i) = 8 (i / 4) + 4 half + i % 4
-        // (fragments are read a batch ahead of the multiplications that use them)
         f32x16_t acc[2];
-        const unsigned char* arow = tile[buf] + col * kRowBytes + 16 * half;
-        auto frag = [&](int ks) { return *reinterpret_cast<const bf16x8_t*>(arow + 32 * ks); };
         {
             const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            const bf16x8_t a_off = *reinterpret_cast<const bf16x8_t*>(tile[buf] + col * kRowBytes + 256);
-            const bf16x8_t a0 = frag(0), a1 = frag(1), a2 = frag(2), a3 = frag(3), a4 = frag(4);
-            __builtin_amdgcn_sched_barrier(0);      // (keeps the compiler from pairing every read with its use again)
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_off, ones, zero, 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_off, ones_too, zero, 0, 0, 0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, xb[0][0], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, xb[1][0], acc[1], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            const bf16x8_t a5 = frag(5), a6 = frag(6), a7 = frag(7);
-            __builtin_amdgcn_sched_barrier(0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xb[0][1], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xb[1][1], acc[1], 0, 0, 0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, xb[0][2], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, xb[1][2], acc[1], 0, 0, 0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, xb[0][3], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, xb[1][3], acc[1], 0, 0, 0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a4, xb[0][4], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a4, xb[1][4], acc[1], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a5, xb[0][5], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a5, xb[1][5], acc[1], 0, 0, 0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a6, xb[0][6], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a6, xb[1][6], acc[1], 0, 0, 0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a7, xb[0][7], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a7, xb[1][7], acc[1], 0, 0, 0);
+            const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(tile[buf] + col * kRowBytes + 256);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, ones, zero, 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, ones_too, zero, 0, 0, 0);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(tile[buf] + col * kRowBytes + 32 * ks + 16 * half);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[0][ks], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[1][ks], acc[1], 0, 0, 0);
         }
         // best and second best per point.  The slot i of a score inside the tile rides in its four
         // lowest mantissa bits (a change of at most 2^-19 of its magnitude), so that a pair of scores
@@ -183,8 +171,14 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
             }
             btile[c] = best[c] != before ? j0 : btile[c];
         }
-        if (more) deposit(j0 + kTile, buf ^ 1);
+        if (more) deposit(j0 + kTile, buf ^ 1, next);
         __syncthreads();
+    };
+    // (two tiles per trip, so that the two register sets swap roles without being copied: a copy
+    // would have to wait for the load)
+    for (int j0 = k0; j0 < k1; j0 += 2 * kTile) {
+        step(j0, 0, pre_a, pre_b);
+        if (j0 + kTile < k1) step(j0 + kTile, 1, pre_b, pre_a);
     }
     // largest |c|^2 of the block: every thread saw the rows it deposited
     c2max = wave_max_f32(c2max);
