@@ -86,7 +86,10 @@ def test_byte_model_reproduces_the_papers_memory_operation_column():
     # accounting, fed with the counters such a step would produce, must give the same fractions.
     import numpy as np
     import bench
-    for n, budget, want in [(8192, 128, 0.11), (16384, 128, 0.09), (8192, 512, 0.16), (16384, 512, 0.11)]:
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "table2_memory_operations.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 4
+    for n, budget, want in [(int(a), int(b), float(c)) for a, b, c in rows]:
         cents = n // 16
         counters = np.array([[budget + 256 + 10, cents, 0, cents]])
         step_bytes, value_pass_bytes = bench.algorithmic_bytes(counters, G=4)
