@@ -189,8 +189,10 @@ int mpo_decode_unit(const double *q, const double *ql, int G, int d, double scal
     double *lc = (double *)malloc(sizeof(double) * GCc);   /* l[h,c] */
     double *lf = (double *)malloc(sizeof(double) * GCf);   /* l[h,f] */
     int32_t *ids = (int32_t *)malloc(sizeof(int32_t) * (size_t)((Cc > Cf ? Cc : Cf) + 1));
-    double *tx = (double *)malloc(sizeof(double) * (size_t)((Cc + Cf) + 1));
-    double *tw = (double *)malloc(sizeof(double) * (size_t)((Cc + Cf) + 1));
+    /* scratch for one weighted log-sum-exp: over the entries of both levels, or over the G heads */
+    const size_t nscr = (size_t)((Cc + Cf) + 1) > (size_t)G ? (size_t)((Cc + Cf) + 1) : (size_t)G;
+    double *tx = (double *)malloc(sizeof(double) * nscr);
+    double *tw = (double *)malloc(sizeof(double) * nscr);
     double *lseh = (double *)malloc(sizeof(double) * (size_t)G);
 
     if (promising) memset(promising, 0, (size_t)(Cc > 0 ? Cc : 0));

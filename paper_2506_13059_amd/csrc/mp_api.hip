@@ -204,6 +204,8 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     if (e != hipSuccess) {
         const mp_status st = (e == hipErrorOutOfMemory) ? MP_ENOMEM : MP_EHIP;
         fail(nullptr, st, "mp_create: %s (after %zu bytes)", hipGetErrorString(e), ctx->device_bytes);
+        if (ctx->pin_ev) (void)hipEventDestroy(ctx->pin_ev);
+        if (ctx->pin) (void)hipHostFree(ctx->pin);
         free_all(ctx);
         delete ctx;
         return st;

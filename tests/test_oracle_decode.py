@@ -336,3 +336,18 @@ def test_inconsistent_clustering_is_rejected():
     bad = dict(cl, N_f=cl["N_f"] + 1)
     with pytest.raises(ValueError):
         O.decode_unit(q, bad, key_budget=10, coarse_budget=10)
+
+
+def test_more_heads_than_clusters():
+    # one token, one fine and one coarse cluster, seven heads: every head attends to the only token
+    # whatever the budgets, with or without centroid terms (the centroid IS the token)
+    rng = np.random.default_rng(77)
+    K, V, q = _bf16(rng.normal(size=(1, 16))), _bf16(rng.normal(size=(1, 16))), _bf16(rng.normal(size=(7, 16)))
+    cl = dict(K=K, V=V, levels=2, fine_of_token=np.zeros(1, np.int32), Kc_f=K.copy(), Vc_f=V.copy(), N_f=np.ones(1, np.int32),
+              coarse_of_fine=np.zeros(1, np.int32), Kc_c=K.copy(), Vc_c=V.copy(), N_c=np.ones(1, np.int32))
+    for kb, cb in [(0, 0), (1, 1), (5, 0), (0, 5)]:
+        r = O.decode_unit(q, cl, kb, cb)
+        np.testing.assert_allclose(r["out"], np.repeat(V, 7, axis=0), rtol=1e-14)
+        np.testing.assert_allclose(r["lse"], (q @ K[0]) / np.sqrt(16), rtol=1e-13, atol=1e-13)
+    r = O.decode_unit(q, cl, 1, 1, mp_terms=False)
+    np.testing.assert_allclose(r["out"], np.repeat(V, 7, axis=0), rtol=1e-14)
