@@ -145,3 +145,31 @@ def test_update_argument_errors():
     ctx.mp_update_clusters(kn, kn, 2, 1, seed=5)
     assert ctx.mp_get_sizes()["n_tokens"] == 166
     ctx.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_update_chains(seed):
+    # seeded random shapes: block sizes (or no blocks), cluster ratios, iteration counts, update sizes
+    # down to a single token, updates without new clusters, with and without lookup keys
+    rng = np.random.default_rng(300 + seed)
+    W = int(rng.choice([0, 128, 256]))
+    alpha = 0 if W == 0 else int(rng.choice([W // 2, W]))
+    n0 = int(rng.integers(200, 600)) if W == 0 else int(rng.integers(W + alpha, 3 * W))
+    levels = int(rng.integers(1, 3))
+    nf = max(2, n0 // int(rng.choice([8, 16, 32])))
+    nc = max(1, nf // 6) if levels == 2 else 0
+    iters = int(rng.integers(1, 4))
+    updates = []
+    for _ in range(3):
+        n_new = int(rng.choice([1, 8, 16, 40]))
+        nnf = int(rng.integers(0, min(n_new, 6) + 1))
+        nnc = int(rng.integers(0, min(nnf, 2) + 1)) if levels == 2 else 0
+        updates.append((n_new, nnf, nnc, int(rng.integers(0, 3))))
+    lookup = [None, "rope", "perm"][int(rng.integers(0, 3))]
+    B, Hkv = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+    print(f"seed {seed}: B={B} Hkv={Hkv} n0={n0} W={W} alpha={alpha} levels={levels} nf={nf} nc={nc} iters={iters} "
+          f"updates={updates} lookup={lookup}", flush=True)
+    ctx, cls, _ = _chain(B, 2 * Hkv, Hkv, n0, 12, levels, nf, nc, W, alpha, iters, updates, seed=400 + seed,
+                         max_tokens=n0 + sum(u[0] for u in updates), max_fine=nf + sum(u[1] for u in updates) + 8,
+                         max_coarse=(nc + sum(u[2] for u in updates) + 4) if levels == 2 else 0, lookup=lookup)
+    ctx.close()
