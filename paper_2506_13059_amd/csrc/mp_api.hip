@@ -313,9 +313,22 @@ mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* k_new_l
                                 refine_iters, split_iters, seed, seeds, (hipStream_t)stream);
 }
 
-mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* q_lookup, const void* k_tail, const void* v_tail,
-                              int32_t n_tail, int32_t tail_stride,
-                              int32_t key_budget, int32_t coarse_budget, uint32_t flags, void* out, float* lse, void* stream)
+}  // extern "C"
+
+namespace {
+// Rows that join the tail buffers at the start of a step (see ScoreParams::app_*).
+struct AppendRows {
+    int n = 0;
+    const void* src[3] = {nullptr, nullptr, nullptr};
+    void* dst[3] = {nullptr, nullptr, nullptr};
+    long long dst_rows = 0;
+    int row = 0;
+};
+}  // namespace
+
+static mp_status decode_impl(mp_ctx* ctx, const void* q, const void* q_lookup, const void* k_tail, const void* v_tail,
+                             int32_t n_tail, int32_t tail_stride, int32_t key_budget, int32_t coarse_budget, uint32_t flags,
+                             void* out, float* lse, void* stream, const AppendRows* app)
 {
     if (!ctx) return fail(nullptr, MP_EINVAL, "mp_decode_attention: null context");
     if (!ctx->has_index) return fail(ctx, MP_ESTATE, "mp_decode_attention: no index yet (call mp_cluster_kv first)");
@@ -344,6 +357,10 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* q_lookup, 
     sp.use_mp = use_mp; sp.counters = ctx->counters; sp.n_tail = n_tail;
     sp.lds_cap = std::min(1024, std::max(ctx->n_fine, std::max(ctx->n_coarse, 1)));
     sp.G = G; sp.U = U;
+    if (app) {
+        sp.app_n = app->n; sp.app_dst_rows = app->dst_rows; sp.app_row = app->row;
+        for (int a = 0; a < app->n; ++a) { sp.app_src[a] = app->src[a]; sp.app_dst[a] = app->dst[a]; }
+    }
     if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[0], s));
     if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[1], s));
     MP_HIP(ctx, launch_score_select(sp, s));
@@ -388,6 +405,16 @@ mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* q_lookup, 
     ctx->timed_levels = two ? 2 : 1;
     ctx->decoded = true;
     return MP_OK;
+}
+
+extern "C" {
+
+mp_status mp_decode_attention(mp_ctx* ctx, const void* q, const void* q_lookup, const void* k_tail, const void* v_tail,
+                              int32_t n_tail, int32_t tail_stride,
+                              int32_t key_budget, int32_t coarse_budget, uint32_t flags, void* out, float* lse, void* stream)
+{
+    return decode_impl(ctx, q, q_lookup, k_tail, v_tail, n_tail, tail_stride, key_budget, coarse_budget, flags, out, lse,
+                       stream, nullptr);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -479,15 +506,16 @@ mp_status mp_decode_step(mp_ctx* ctx, const void* q, const void* q_lookup, const
         const mp_status st = refresh_local_buffer(ctx, n_new_fine, n_new_coarse, refine_iters, split_iters, seed, seeds, s);
         if (st != MP_OK) return st;
     }
-    // the new token joins the buffer first: a decoding step attends to its own key and value
-    MP_HIP(ctx, mp::launch_append_row(k_new, v_new, ctx->U, ctx->Kt, ctx->Vt, ctx->Tcap, ns + ctx->lb_recent, s));
-    if (k_new_lookup)
-        MP_HIP(ctx, hipMemcpy2DAsync((char*)ctx->Ktl + (size_t)(ns + ctx->lb_recent) * kHeadDimHost * sizeof(uint16_t),
-                                     (size_t)ctx->Tcap * kHeadDimHost * sizeof(uint16_t), k_new_lookup, kHeadDimHost * sizeof(uint16_t),
-                                     kHeadDimHost * sizeof(uint16_t), ctx->U, hipMemcpyDeviceToDevice, s));
+    // the new token joins the buffer first (a decoding step attends to its own key and value): the
+    // scoring launch of the step copies its rows in, one launch less than a copy of its own
+    AppendRows app;
+    app.dst_rows = ctx->Tcap; app.row = ns + ctx->lb_recent;
+    app.src[app.n] = k_new; app.dst[app.n++] = ctx->Kt;
+    app.src[app.n] = v_new; app.dst[app.n++] = ctx->Vt;
+    if (k_new_lookup) { app.src[app.n] = k_new_lookup; app.dst[app.n++] = ctx->Ktl; }
     ctx->lb_recent += 1;
-    const mp_status st = mp_decode_attention(ctx, q, q_lookup, ctx->Kt, ctx->Vt, ns + ctx->lb_recent, ctx->Tcap, key_budget,
-                                             coarse_budget, flags, out, lse, stream);
+    const mp_status st = decode_impl(ctx, q, q_lookup, ctx->Kt, ctx->Vt, ns + ctx->lb_recent, ctx->Tcap, key_budget,
+                                     coarse_budget, flags, out, lse, stream, &app);
     if (st != MP_OK) {
         ctx->lb_recent -= 1;
         return st;

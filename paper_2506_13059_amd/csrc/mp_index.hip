@@ -414,27 +414,6 @@ hipError_t launch_block_lists(const int32_t* ids, long long ids_stride, const in
     return hipGetLastError();
 }
 
-// One new row per unit and array: dstK[u][row] = srcK[u], dstV[u][row] = srcV[u] (256-byte rows).
-__global__ void append_row_kernel(const uint4* __restrict__ srcK, const uint4* __restrict__ srcV, int U,
-                                  uint4* __restrict__ dstK, uint4* __restrict__ dstV, long long dst_unit_rows, int row)
-{
-    const int g = blockIdx.x * blockDim.x + threadIdx.x;      // 32 threads per unit: 16 for K, 16 for V
-    const int u = g >> 5, c = g & 15;
-    if (u >= U) return;
-    const bool isv = (g >> 4) & 1;
-    const uint4* src = isv ? srcV : srcK;
-    uint4* dst = isv ? dstV : dstK;
-    dst[((long long)u * dst_unit_rows + row) * 16 + c] = src[(long long)u * 16 + c];
-}
-
-hipError_t launch_append_row(const void* srcK, const void* srcV, int U, void* dstK, void* dstV, long long dst_unit_rows,
-                             int row, hipStream_t s)
-{
-    hipLaunchKernelGGL(append_row_kernel, dim3((U * 32 + 255) / 256), dim3(256), 0, s, (const uint4*)srcK,
-                       (const uint4*)srcV, U, (uint4*)dstK, (uint4*)dstV, dst_unit_rows, row);
-    return hipGetLastError();
-}
-
 hipError_t launch_gather_rows(const void* srcK, const void* srcV, long long src_unit_rows, const int32_t* list,
                               long long list_stride, int n, int U, void* dstK, void* dstV, long long dst_unit_rows,
                               int dst_row0, hipStream_t s)

@@ -93,6 +93,14 @@ struct ScoreParams {
     int use_mp;
     int32_t* counters;          // [U, 4]
     int n_tail;
+    // optional: rows the caller hands over with this step (a generation loop's new token) are copied
+    // into the tail buffers by the workgroup of their unit before anything else; the value pass,
+    // a later launch, then finds them there.  app_n arrays (0 = none), 256-byte rows.
+    int app_n;
+    const void* app_src[3];     // [U, 128] bf16 each
+    void* app_dst[3];           // [U, app_dst_rows, 128] bf16 each
+    long long app_dst_rows;
+    int app_row;
     int lds_cap;                // entries of a level that fit the LDS working arrays
     int G, U;
 };
@@ -104,9 +112,6 @@ size_t score_smem_bytes(int G, int cap);
 // Index construction helpers (member lists, gathers, per-cluster means)
 // ------------------------------------------------------------------------------------------------
 hipError_t launch_fill_i32(int32_t* p, long long n, int32_t v, hipStream_t s);
-// dstK[u][row] = srcK[u], dstV[u][row] = srcV[u] for bf16 rows of 128 (src: [U, 128])
-hipError_t launch_append_row(const void* srcK, const void* srcV, int U, void* dstK, void* dstV, long long dst_unit_rows,
-                             int row, hipStream_t s);
 // Nearest-centroid assignment (fp64 definition, lowest index among equal distances) of the points of
 // nb blocks per unit.  blocks_dev: int32 [nb][4] = {first point, end point, first centroid, end
 // centroid}; assign[u][t] receives the centroid row of point t.  amb_list [U, list_stride] (at least

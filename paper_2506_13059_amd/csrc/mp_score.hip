@@ -656,6 +656,12 @@ __global__ __launch_bounds__(kThreads) void score_select_kernel(const ScoreParam
     unsigned char* lds = smem_raw + ((sizeof(Scratch) + 15) & ~size_t(15));
     const int u = blockIdx.x, tid = threadIdx.x;
 
+    if (tid < 16 * p.app_n) {       // the step's new rows go to their place in the tail buffers
+        const int a = tid >> 4, c = tid & 15;
+        const uint4 w = reinterpret_cast<const uint4*>(p.app_src[a])[(long long)u * 16 + c];
+        reinterpret_cast<uint4*>(p.app_dst[a])[((long long)u * p.app_dst_rows + p.app_row) * 16 + c] = w;
+    }
+
     // query slice of this lane: dims [DPL*sub, DPL*sub + DPL) of every head, as doubles
     double qreg[G][DPL];
     {
