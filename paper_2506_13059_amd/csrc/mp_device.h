@@ -56,6 +56,32 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
 }
 
+// e^x in fp64 for the arguments a shifted log-sum-exp produces: x <= 0 up to rounding of the shift
+// (any x below about 700 is fine), -inf allowed (gives 0).  x = k ln2 + r with |r| <= ln2 / 2, e^r by its
+// Taylor polynomial of degree 12 (remainder below 2e-16 of the value), scaled by 2^k with ldexp.
+// About a third of the instructions of the general-purpose routine; relative error below 1e-15.
+__device__ __forceinline__ double exp_shifted(double x)
+{
+    x = fmax(x, -800.0);                                   // e^-800 is zero in fp64; keeps k finite
+    const double kf = __builtin_rint(x * 1.4426950408889634074);
+    double r = fma(kf, -6.93147180369123816490e-01, x);    // ln2 in two parts
+    r = fma(kf, -1.90821492927058770002e-10, r);
+    double p = 2.08767569878680989792e-09;                 // 1/12!
+    p = fma(p, r, 2.50521083854417187751e-08);             // 1/11!
+    p = fma(p, r, 2.75573192239858906526e-07);             // 1/10!
+    p = fma(p, r, 2.75573192239858906526e-06);             // 1/9!
+    p = fma(p, r, 2.48015873015873015873e-05);             // 1/8!
+    p = fma(p, r, 1.98412698412698412698e-04);             // 1/7!
+    p = fma(p, r, 1.38888888888888888889e-03);             // 1/6!
+    p = fma(p, r, 8.33333333333333333333e-03);             // 1/5!
+    p = fma(p, r, 4.16666666666666666667e-02);             // 1/4!
+    p = fma(p, r, 1.66666666666666666667e-01);             // 1/3!
+    p = fma(p, r, 0.5);
+    p = fma(p, r, 1.0);
+    p = fma(p, r, 1.0);
+    return ldexp(p, (int)kf);
+}
+
 // ---- DPP cross-lane moves inside a row of 16 lanes ----------------------------------------------
 template <int kCtrl>
 __device__ __forceinline__ float dpp_f32(float v)

@@ -109,7 +109,7 @@ __device__ __forceinline__ void weighted_lse(const Arrays& A, Scratch& S, int n,
         if (pred(i)) {
             const double w = (double)A.wts[i];
 #pragma unroll
-            for (int h = 0; h < G; ++h) sm[h] += w * exp(A.lg[h * A.lg_stride + i] - mw[h]);
+            for (int h = 0; h < G; ++h) sm[h] += w * exp_shifted(A.lg[h * A.lg_stride + i] - mw[h]);
         }
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -132,7 +132,7 @@ __device__ __forceinline__ void weighted_lse(const Arrays& A, Scratch& S, int n,
         const double sv = live ? S.red_s[w * 8 + h] : 0.0;
         if (!(sv > 0.0)) m = -INFINITY;
         const double M = row_max_f64(m);
-        double t = (m == -INFINITY) ? 0.0 : sv * exp(m - M);
+        double t = (m == -INFINITY) ? 0.0 : sv * exp_shifted(m - M);
         t = row_sum_f64(t);
         const double r = (M == -INFINITY) ? -INFINITY : M + log(t);
 #pragma unroll
@@ -451,7 +451,7 @@ __device__ __forceinline__ void score_level(const ScoreParams& p, const Arrays& 
             if constexpr (G > 1) {
                 double ssum = 0.0;
 #pragma unroll
-                for (int h = 0; h < G; ++h) ssum += exp(t[h] - tm);
+                for (int h = 0; h < G; ++h) ssum += exp_shifted(t[h] - tm);
                 r += log(ssum);
             }
             key = descending_key(r);
