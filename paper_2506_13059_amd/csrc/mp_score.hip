@@ -51,10 +51,10 @@ struct Scratch {
     double red_s[(kWaves + 1) * 8];   // ... and sum
     double extra[8];                  // log-sum of the unpromising coarse clusters' N e^l, per head
     unsigned long long hist[3][256];  // radix digit histograms: entry count << 40 | token count
+    unsigned long long hkey[3][256];  // a key that fell into each bucket (THE key where the bucket holds one entry)
     unsigned long long rk_min[kWaves], rk_max[kWaves];  // per wave: smallest / largest key that takes part
     uint32_t rk_wt[kWaves], rk_cn[kWaves];              // ... their token total and their number
     uint32_t wsum[2][kWaves][2];      // per-wave totals of the two-value scan, double-buffered
-    unsigned long long sel_key;
 };
 
 struct Arrays {
@@ -213,7 +213,9 @@ __device__ __forceinline__ T wave_reduce(T v, Op op)
 // digit already spreads the entries over the histogram instead of piling them onto a few LDS
 // addresses.  One barrier per digit of up to 8 bits: the histogram (entry count and token count
 // packed in one 64-bit LDS atomic) is scanned by every wave for itself, which leaves the chosen
-// digit wave-uniform in registers.  Three histogram buffers rotate: pass p fills buffer p%3 and
+// digit wave-uniform in registers.  Next to each bucket's counts sits the key of an entry that fell
+// into it, so that the pass in which the boundary bucket is down to one entry ends the search
+// without another sweep.  Three histogram buffers rotate: pass p fills buffer p%3 and
 // clears buffer (p+1)%3, whose last readers (pass p-2) all finished before the barrier of pass p-1.
 template <bool kLds>
 __device__ __forceinline__ bool radix_select(const uint64_t* keys, const uint32_t* wts, int n, long long budget,
@@ -267,12 +269,17 @@ __device__ __forceinline__ bool radix_select(const uint64_t* keys, const uint32_
         const int bits = hi < 8 ? hi : 8, shift = hi - bits;
         const uint32_t dmask = (1u << bits) - 1u;
         unsigned long long* H = s.hist[pass % 3];
+        unsigned long long* HK = s.hkey[pass % 3];
         if (tid < 256) s.hist[(pass + 1) % 3][tid] = 0;
         for (int i = tid; i < n; i += kThreads) {
             const uint32_t w = wts[i];
             if (w == 0) continue;
             const uint64_t k = keys[i] - kmin;
-            if (hi >= 64 || (k >> hi) == prefix) atomicAdd(&H[(uint32_t)(k >> shift) & dmask], (1ull << 40) | w);
+            if (hi >= 64 || (k >> hi) == prefix) {
+                const uint32_t b = (uint32_t)(k >> shift) & dmask;
+                atomicAdd(&H[b], (1ull << 40) | w);
+                HK[b] = keys[i];        // plain store: only read back where this entry is alone in its bucket
+            }
         }
         phase_sync<kLds>();
         unsigned long long h4[4];
@@ -306,14 +313,9 @@ __device__ __forceinline__ bool radix_select(const uint64_t* keys, const uint32_
         prefix = (prefix << bits) | (uint32_t)__builtin_amdgcn_readlane((int)d, first);
         hi = shift;
         if (cnt == 1 && hi > 0) {
-            // a single entry carries the boundary: its full key is K*
-            for (int i = tid; i < n; i += kThreads) {
-                if (wts[i] == 0) continue;
-                const uint64_t k = keys[i];
-                if (((k - kmin) >> hi) == prefix) s.sel_key = k;
-            }
-            phase_sync<kLds>();
-            kstar = s.sel_key;
+            // a single entry carries the boundary: its full key is K*, and it left that key in the
+            // bucket's slot (nobody else wrote there in this pass)
+            kstar = HK[(uint32_t)prefix & dmask];
             acc_out = acc;
             ties_out = 1;
             return true;
