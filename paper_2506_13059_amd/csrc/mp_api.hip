@@ -56,14 +56,29 @@ int pick_chunk_rows(long long n_rows_per_unit, int n_units)
     return cr;
 }
 
-// Rows per workgroup for the stream of selected keys.  Long chunks (4 strips of 128 rows per wave)
-// spread the prologue and epilogue of a workgroup over more bytes, but only pay off while the launch
-// still has a workgroup for every resident slot; otherwise one strip per wave (measured on cfg3: 2048
-// at key budget 8192 = 512 workgroups, 512 at budget 4096 = 1024 workgroups).
-int pick_main_chunk_rows(int rows_max, int n_units)
+// Rows per workgroup for one stream of the value pass (selected keys: largest = 2048; centroid terms
+// and tail: largest = 512).  Long chunks spread the prologue and epilogue of a workgroup over more
+// bytes, but only pay off while the stream still has a workgroup for every resident slot; so: the
+// largest size that does, else the smallest (measured on cfg3: 2048 at key budget 8192 = 512
+// workgroups, 512 at budget 4096 = 1024 workgroups; on one sequence of 32K tokens, 8 units, 128-row
+// chunks instead of 512-row ones fill 4 times as many compute units).
+int pick_stream_chunk_rows(int rows_max, int n_units, int largest)
 {
-    const long long long_chunks = (long long)n_units * ((rows_max + 2047) / 2048);
-    return long_chunks >= kResidentWgs ? 2048 : kChunkRowsMin;
+    static const int kChoices[] = {2048, 512, 256, 128};
+    for (int c : kChoices)
+        if (c <= largest && (long long)n_units * ((rows_max + c - 1) / c) >= kResidentWgs) return c;
+    return 128;
+}
+
+// Most chunks a stream of up to rows_cap rows can be cut into under that rule.
+int max_stream_chunks(int rows_cap, int n_units, int largest)
+{
+    int m = 1;
+    for (int r = 1; r <= rows_cap; ++r) {
+        const int c = pick_stream_chunk_rows(r, n_units, largest);
+        m = std::max(m, (r + c - 1) / c);
+    }
+    return m;
 }
 
 }  // namespace mp
@@ -163,8 +178,8 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     ctx->tab_rows = (long long)ctx->Fcap + ctx->Ccap;
     ctx->FBcap = c.block_w > 0 ? (int32_t)std::min<long long>(c.max_tokens, 2ll * c.block_w) : c.max_tokens;
     ctx->max_blocks = std::max(4, c.block_w > 0 ? c.max_tokens / c.block_w + 2 : 2);
-    ctx->Pcap = ceil_div(ctx->Ncap, kChunkRowsMin) + 2 + ceil_div(ctx->Tcap, kChunkRowsMin) +
-                ceil_div(ctx->tab_rows, kChunkRowsMin) + 1;
+    ctx->Pcap = mp::max_stream_chunks(ctx->Ncap, ctx->U, 2048) + mp::max_stream_chunks(std::max(ctx->Tcap, 1), ctx->U, 512) +
+                mp::max_stream_chunks((int)ctx->tab_rows, ctx->U, 512);
 
     hipError_t e = hipGetDevice(&ctx->device);
     const size_t U = ctx->U, N = ctx->Ncap, F = ctx->Fcap, Cc = std::max(ctx->Ccap, 1), T = ctx->tab_rows, D = kHeadDimHost;
@@ -372,24 +387,25 @@ static mp_status decode_impl(mp_ctx* ctx, const void* q, const void* q_lookup, c
     vp.n_units = U;
     vp.scale_log2e = (float)(ctx->scale_d * 1.4426950408889634);
     const int main_max = std::min(key_budget, ctx->n_tokens);
-    const int cr = kChunkRowsMin;      // centroid terms and tail: short streams
     int ns = 0, chunk0 = 0;
     // order: centroid terms, tail, selected keys -- the longest stream goes last (see the kernel's block mapping)
     if (use_mp) {
         const int mp_max = ctx->n_fine + ctx->n_coarse;
+        const int cr = pick_stream_chunk_rows(mp_max, U, 512);
         RowSource& r = vp.src[ns++];
         r.K = nullptr; r.V = ctx->Vc; r.unit_rows = ctx->tab_rows; r.rows = ctx->mp_rows; r.rows_stride = ctx->tab_rows;
         r.count_dev = ctx->n_mp; r.count_max = mp_max; r.scores = ctx->mp_scores; r.chunk0 = chunk0;
         r.chunk_rows = cr; r.row0 = 0; r.n_chunks = ceil_div(mp_max, cr); chunk0 += r.n_chunks;
     }
     if (n_tail > 0) {
+        const int cr = pick_stream_chunk_rows(n_tail, U, 512);
         RowSource& r = vp.src[ns++];
         r.K = (const uint16_t*)k_tail; r.V = (const uint16_t*)v_tail; r.unit_rows = tail_stride ? tail_stride : n_tail; r.rows = nullptr; r.rows_stride = 0;
         r.count_dev = nullptr; r.count_max = n_tail; r.scores = nullptr; r.chunk0 = chunk0;
         r.chunk_rows = cr; r.row0 = 0; r.n_chunks = ceil_div(n_tail, cr); chunk0 += r.n_chunks;
     }
     if (main_max > 0) {
-        const int crm = pick_main_chunk_rows(main_max, U);
+        const int crm = pick_stream_chunk_rows(main_max, U, 2048);
         RowSource& r = vp.src[ns++];
         r.K = ctx->Kp; r.V = ctx->Vp; r.unit_rows = ctx->Ncap; r.rows = ctx->rows; r.rows_stride = ctx->Ncap;
         r.count_dev = ctx->n_rows; r.count_max = main_max; r.scores = nullptr; r.chunk0 = chunk0;

@@ -10,7 +10,7 @@ namespace mp {
 // one online-softmax partial (m, l, acc[128]) per (unit, chunk, head).  A stream may be cut into two
 // sources with different chunk sizes (large chunks first, small ones last) to shorten the drain.
 // ------------------------------------------------------------------------------------------------
-constexpr int kChunkRowsMin = 512;     // a workgroup is 4 waves, each taking strips of 128 rows
+constexpr int kChunkRowsMin = 512;     // smallest chunk of the dense kernel: 4 waves, one strip of 128 rows each
 constexpr int kPartStride = 132;       // floats per (unit, chunk, head): m, l, pad, pad, acc[128]
 constexpr int kMaxSources = 4;
 

@@ -263,3 +263,20 @@ def test_decode_argument_errors():
     torch.cuda.synchronize()
     assert torch.isfinite(out.float()).all()
     ctx.close()
+
+
+def test_many_units_long_chunks():
+    # 128 units x 2048 selected keys: the launch shape of the large workloads (512-row chunks of the
+    # selected-key stream, eight-iteration strips), at a size the oracle still checks unit by unit
+    from paper_2506_13059_amd import binding as mp
+    from tests.gpu_util import compare_decode
+    B, Hq, Hkv, n = 16, 16, 8, 4096
+    K, V, q = _mk(B, Hq, Hkv, n, 64, seed=91, softness=0.4)
+    g = torch.Generator(device="cuda").manual_seed(92)
+    fot = torch.randint(0, 128, (B * Hkv, n), generator=g, device="cuda").to(torch.int32)
+    cof = (torch.arange(128, device="cuda", dtype=torch.int32) // 8)[None].repeat(B * Hkv, 1).contiguous()
+    ctx = mp.MpContext(B, Hq, Hkv, max_tokens=n, levels=2, max_fine=128, max_coarse=16, max_tail=0)
+    ctx.mp_set_clustering(K, V, fot, 128, cof, 16)
+    r = compare_decode(ctx, q[0], K, V, 2048, 4096, label="many units")
+    assert r["exempt"] == 0
+    ctx.close()
