@@ -52,6 +52,7 @@ def main():
     ap.add_argument("--coarse-mult", type=int, default=2, help="coarse budget = mult * key budget")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-online", action="store_true", help="skip the online-generation (cfg4_online) extra")
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the smaller workloads (cfg0 - cfg2)")
     ap.add_argument("--only-online", action="store_true",
                     help="run only the online-generation workload and print its record (for profiling)")
     ap.add_argument("--error-study", action="store_true",
@@ -213,6 +214,11 @@ def main():
         "cluster_build_ms": round(cluster_ms, 2),
         "cluster_build_mtokens_per_s": round(w.units * w.context / cluster_ms / 1e3, 1),
         "online_generation": None if args.no_online else online_generation(mp, inputs, dev),
+        "other_workloads": None if args.no_others else {
+            name: quick_workload(mp, inputs, dev, name, args.coarse_mult)
+            for name in ("cfg0_tiny", "cfg1_qwen3_8b_32k", "cfg2_14b_64k") if name != w.name},
+        "input_checksums": {"K": checksum(K), "V": checksum(V), "q": checksum(Q)},
+        "kv_cache_mib": round(2 * K.numel() * 2 / 2 ** 20, 1),
         "input_generation_s": round(t_gen, 2),
         "paper_context": "paper reports up to 4.5x attention speedup vs FlashDecoding on an NVIDIA A6000 "
                          "(2.8x on A100), batch 16, 128K context",
@@ -223,6 +229,57 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
+
+
+def checksum(t):
+    """Sum of the tensor's 16-bit patterns (as a reproducibility fingerprint of the seeded inputs)."""
+    import torch
+    return int(t.contiguous().view(torch.int16).to(torch.int64).sum().item())
+
+
+def quick_workload(mp, inputs, dev, name, coarse_mult, steps=100, warmup=20):
+    """A short run of one of the smaller workloads: us per decode step at its key budget and the dense
+    kernel on the same tensors.  These steps are latency-bound (one step of one layer of a small
+    batch); caches whose keys and values fit the 256 MiB last-level cache are marked as such."""
+    import torch
+    w = inputs.WORKLOADS[name]
+    n_sets = 16
+    data = inputs.make_workload(w, dev, seed=1000 * list(inputs.WORKLOADS).index(name), n_query_sets=n_sets)
+    K, V, Q = data["K"], data["V"], data["q"]
+    ctx = mp.MpContext(w.batch, w.n_q_heads, w.n_kv_heads, max_tokens=w.context, levels=w.levels, max_fine=w.n_fine,
+                       max_coarse=w.n_coarse, block_w=w.block_w, block_alpha=w.block_alpha, max_tail=0)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    ctx.mp_cluster_kv(K, V, w.n_fine, w.n_coarse, iters=w.kmeans_iters, init_fine=data["init_fine"],
+                      init_coarse=data["init_coarse"] if w.levels == 2 else None)
+    e1.record()
+    torch.cuda.synchronize()
+    build_ms = e0.elapsed_time(e1)
+    out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.bfloat16, device=dev)
+    kb = w.key_budgets[0]
+    cb = coarse_mult * kb if w.levels == 2 else 0
+    ws = torch.empty(max(mp.mp_dense_workspace_bytes(w.batch, w.n_q_heads, w.n_kv_heads, w.context), 16),
+                     dtype=torch.uint8, device=dev)
+
+    def timed(fn):
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(steps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps * 1e3
+
+    us = timed(lambda i: ctx.mp_decode_attention(Q[i % n_sets], kb, cb, out=out))
+    dense_us = timed(lambda i: mp.mp_dense_attention(Q[i % n_sets], K, V, out=out, workspace=ws))
+    step_bytes, _ = algorithmic_bytes(ctx.mp_get_counters().cpu(), w.group)
+    kv_mib = 2 * K.numel() * 2 / 2 ** 20
+    ctx.close()
+    return {"us_per_step": round(us, 2), "dense_us_per_step": round(dense_us, 2), "speedup_vs_dense": round(dense_us / us, 3),
+            "key_budget": kb, "coarse_budget": cb, "achieved_hbm_gbps": round(step_bytes / us / 1e3, 1),
+            "kv_cache_mib": round(kv_mib, 1), "kv_fits_last_level_cache": kv_mib <= 256, "cluster_build_ms": round(build_ms, 2)}
 
 
 def online_generation(mp, inputs, dev):
@@ -414,9 +471,27 @@ def cpu_baseline(ctx, w, K, V, Q, kb, cb):
         if el >= 10.0 or reps >= 5000:
             break
     per_unit_us = el / reps / sample * 1e6
+    # beside it: the oracle's dense attention on one unit, and one Lloyd iteration (assignment + means) on
+    # one block of 8192 keys with 256 centroids, both scaled to the whole workload
+    t0 = time.time()
+    O.full_attention(args["q"][0], args["K"][0], args["V"][0], 1 / math.sqrt(d))
+    dense_unit_s = time.time() - t0
+    blk = args["K"][0][:min(8192, n)]
+    cent = blk[:: max(1, blk.shape[0] // 256)][:256].copy()
+    t0 = time.time()
+    a = O.assign(blk, cent)
+    O.member_sums(blk, a, cent.shape[0])
+    lloyd_block_s = time.time() - t0
+    n_blocks = max(1, n // 8192) * ctx.U
     return {"value": round(per_unit_us * ctx.U, 1), "unit": "us/step", "cores": O.num_threads(), "kind": "oracle",
             "sample": f"{sample} of {ctx.U} units of {w.name} (same clustering, query set 0, key budget {kb}), "
-                      f"{reps} repetitions in {el:.1f} s, scaled to {ctx.U} units"}
+                      f"{reps} repetitions in {el:.1f} s, scaled to {ctx.U} units",
+            "dense_us_per_step": round(dense_unit_s * ctx.U / max(1, O.num_threads()) * 1e6, 1),
+            "dense_sample": f"1 of {ctx.U} units on one thread, full attention over {n} keys, scaled to {ctx.U} units "
+                            f"spread over {O.num_threads()} threads",
+            "lloyd_iteration_ms": round(lloyd_block_s * n_blocks * 1e3, 1),
+            "lloyd_sample": f"1 block of {blk.shape[0]} keys x {cent.shape[0]} centroids (assignment + member sums), "
+                            f"scaled to {n_blocks} blocks"}
 
 
 if __name__ == "__main__":
