@@ -404,49 +404,50 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
     }
 }
 
-// One workgroup of 128 threads per (unit, head).  The chunk weights 2^(m_i - M) are computed
-// once (one chunk per thread, loads in flight together) and kept in LDS; thread d then combines
-// dimension d over the chunks with independent loads, in chunk order (bit-reproducible).
+// One workgroup of 128 threads per (unit, head); thread d combines dimension d over the chunks in
+// chunk order (bit-reproducible).  Every thread reads the (m, l) pairs of all chunks itself (the
+// same addresses across a wave: one transaction) and works out the weights 2^(m_i - M) on its own,
+// so nothing is exchanged and nothing waited for except memory: sixteen chunks are fetched at a
+// time, all loads of a batch in flight together, with an online rescale between batches.
 __global__ __launch_bounds__(128) void merge_kernel(const float* __restrict__ partials, int chunks_per_unit, int G,
                                                     uint16_t* __restrict__ out, float* __restrict__ lse)
 {
-    extern __shared__ float sw[];            // [chunks_per_unit] weights
-    __shared__ float red[4];
+    constexpr int kBatch = 16;
     const int uh = blockIdx.x;
     const int u = uh / G, h = uh - u * G;
-    const int d = threadIdx.x, lane = d & 63, wave = d >> 6;
+    const int d = threadIdx.x;
     const float* base = partials + ((long long)u * chunks_per_unit * G + h) * kPartStride;
     const long long cs = (long long)G * kPartStride;
-    float M = -INFINITY;
-    for (int i = d; i < chunks_per_unit; i += 128) {
-        const float mi = base[i * cs];
-        sw[i] = mi;
-        M = fmaxf(M, mi);
-    }
+    float M = -INFINITY, L = 0.f, a = 0.f;
+    for (int i0 = 0; i0 < chunks_per_unit; i0 += kBatch) {
+        float m[kBatch], l[kBatch], v[kBatch];
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
-    if (lane == 0) red[wave] = M;
-    __syncthreads();
-    M = fmaxf(red[0], red[1]);
-    const float Ms = (M == -INFINITY) ? 0.f : M;
-    float L = 0.f;
-    for (int i = d; i < chunks_per_unit; i += 128) {
-        const float mi = sw[i];
-        const float w = (mi == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mi - Ms);
-        sw[i] = w;
-        if (w > 0.f) L = fmaf(base[i * cs + 1], w, L);
-    }
+        for (int j = 0; j < kBatch; ++j) {
+            const int i = i0 + j < chunks_per_unit ? i0 + j : chunks_per_unit - 1;    // always a valid address
+            m[j] = base[i * cs];
+            l[j] = base[i * cs + 1];
+            v[j] = base[i * cs + 4 + d];
+        }
+        float bm = -INFINITY;
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off, 64);
-    if (lane == 0) red[2 + wave] = L;
-    __syncthreads();
-    L = red[2] + red[3];
-    float a = 0.f;
-#pragma unroll 8
-    for (int i = 0; i < chunks_per_unit; ++i) {
-        const float w = sw[i];
-        const float v = base[i * cs + 4 + d];      // always a valid address; ignored when w == 0
-        a = fmaf(w > 0.f ? v : 0.f, w, a);
+        for (int j = 0; j < kBatch; ++j) {
+            if (i0 + j >= chunks_per_unit) m[j] = -INFINITY;
+            bm = fmaxf(bm, m[j]);
+        }
+        const float Mn = fmaxf(M, bm);
+        if (Mn == -INFINITY) continue;                       // only empty chunks so far
+        const float keep = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mn);
+        a *= keep;
+        L *= keep;
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const float w = (m[j] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[j] - Mn);
+            if (w > 0.f) {                                   // (an empty chunk's row is never looked at)
+                a = fmaf(v[j], w, a);
+                L = fmaf(l[j], w, L);
+            }
+        }
+        M = Mn;
     }
     const float o = (L > 0.f) ? a / L : 0.f;
     out[(long long)uh * kHeadDim + d] = f32_to_bf16_rne(o);
@@ -486,8 +487,7 @@ hipError_t launch_merge(const float* partials, int n_units, int chunks_per_unit,
 {
     const long long blocks = (long long)n_units * G;
     if (blocks <= 0) return hipSuccess;
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)blocks), dim3(128), sizeof(float) * (size_t)(chunks_per_unit + 1),
-                       stream, partials, chunks_per_unit, G, out, lse);
+    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)blocks), dim3(128), 0, stream, partials, chunks_per_unit, G, out, lse);
     return hipGetLastError();
 }
 
