@@ -47,8 +47,8 @@ __device__ __forceinline__ double key_to_rank(uint64_t key)
 }
 
 struct Scratch {
-    double red_m[(kWaves + 1) * 8];   // per wave (and one extra slot), per head: shift
-    double red_s[(kWaves + 1) * 8];   // ... and sum
+    float gmax[kWaves * 8];           // per wave, per head: largest logit of an entry that takes part
+    double red_s[kWaves * 8];         // per wave, per head: sum of N e^{l - shift}
     double extra[8];                  // log-sum of the unpromising coarse clusters' N e^l, per head
     unsigned long long hist[3][256];  // radix digit histograms: entry count << 40 | token count
     unsigned long long hkey[3][256];  // a key that fell into each bucket (THE key where the bucket holds one entry)
@@ -83,58 +83,54 @@ __device__ __forceinline__ void phase_sync()
     }
 }
 
-// lse[h] = log( sum over the entries with pred(i) of N_i e^{l[h,i]}  [+ e^{extra_h}] ) for every head.
-// Each wave reduces its entries to a (shift, sum) pair per head; after one barrier every wave
-// combines the pairs of all waves by itself (one row of 16 lanes per head), so the result needs no
-// second barrier.  S.red_* are reused by the next call: callers have a barrier between two calls.
-template <int G, bool kLds, typename Pred>
-__device__ __forceinline__ void weighted_lse(const Arrays& A, Scratch& S, int n, bool with_extra, Pred pred,
-                                             double (&lse)[G])
+// What a level hands from its log-sum-exp to later sums over subsets of its entries: the shift per
+// head (the largest logit of an entry that takes part, rounded to float) and, for levels of up to
+// 2 * kThreads entries, this thread's terms N_i e^{l[h,i] - shift_h} of entries tid and tid + kThreads.
+template <int G>
+struct LevelTerms {
+    double shift[G];
+    double e[2][G];
+    bool kept;
+};
+
+// lse[h] = shift_h + log( sum over the workgroup of sm[h]  [+ e^{extra_h - shift_h}] ) for every head,
+// where sm[h] is this thread's sum of terms already divided by e^{shift_h}.  One barrier: per-wave sums
+// via DPP, then every wave adds the eight of them itself (one row of 16 lanes per head), so the
+// result needs no second barrier.  S.red_s is reused by the next call: callers have a barrier
+// between two calls.
+template <int G, bool kLds>
+__device__ __forceinline__ void combine_lse(Scratch& S, const double (&shift)[G], const double (&sm)[G], bool with_extra,
+                                            double (&lse)[G])
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    float mxf[G];
-#pragma unroll
-    for (int h = 0; h < G; ++h) mxf[h] = -INFINITY;
-    for (int i = tid; i < n; i += kThreads)
-        if (pred(i))
-#pragma unroll
-            for (int h = 0; h < G; ++h) mxf[h] = fmaxf(mxf[h], (float)A.lg[h * A.lg_stride + i]);
-    double mw[G], sm[G];
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-        mw[h] = (double)wave_max_f32(mxf[h]);     // a shift close to the wave's maximum is all that is needed
-        sm[h] = 0.0;
-    }
-    for (int i = tid; i < n; i += kThreads)
-        if (pred(i)) {
-            const double w = (double)A.wts[i];
-#pragma unroll
-            for (int h = 0; h < G; ++h) sm[h] += w * exp_shifted(A.lg[h * A.lg_stride + i] - mw[h]);
-        }
 #pragma unroll
     for (int h = 0; h < G; ++h) {
         const double t = wave_sum_f64(sm[h]);
-        if (lane == 0) {
-            S.red_m[wave * 8 + h] = mw[h];
-            S.red_s[wave * 8 + h] = t;
-        }
-    }
-    if (tid < G) {
-        S.red_m[kWaves * 8 + tid] = with_extra ? S.extra[tid] : -INFINITY;
-        S.red_s[kWaves * 8 + tid] = with_extra ? 1.0 : 0.0;
+        if (lane == 0) S.red_s[wave * 8 + h] = t;
     }
     phase_sync<kLds>();
 #pragma unroll
     for (int h0 = 0; h0 < G; h0 += 4) {
         const int h = h0 + (lane >> 4), w = lane & 15;
-        const bool live = h < G && w <= kWaves;
-        double m = live ? S.red_m[w * 8 + h] : -INFINITY;
-        const double sv = live ? S.red_s[w * 8 + h] : 0.0;
-        if (!(sv > 0.0)) m = -INFINITY;
-        const double M = row_max_f64(m);
-        double t = (m == -INFINITY) ? 0.0 : sv * exp_shifted(m - M);
-        t = row_sum_f64(t);
-        const double r = (M == -INFINITY) ? -INFINITY : M + log(t);
+        const bool live = h < G && w < kWaves;
+        double t = row_sum_f64(live ? S.red_s[w * 8 + h] : 0.0);
+        double sh = -INFINITY;
+#pragma unroll
+        for (int hh = 0; hh < 4; ++hh)
+            if (h0 + hh < G && (lane >> 4) == hh) sh = shift[h0 + hh];
+        double r;
+        if (with_extra && h < G) {
+            const double ex = S.extra[h];
+            const double M = fmax(sh, ex);
+            if (M == -INFINITY) {
+                r = -INFINITY;
+            } else {
+                const double a = (t > 0.0) ? t * exp_shifted(sh - M) : 0.0;
+                r = M + log(a + exp_shifted(ex - M));
+            }
+        } else {
+            r = (t > 0.0) ? sh + log(t) : -INFINITY;
+        }
 #pragma unroll
         for (int hh = 0; hh < 4; ++hh)
             if (h0 + hh < G) lse[h0 + hh] = readlane_f64(r, 16 * hh);
@@ -343,7 +339,7 @@ __device__ __forceinline__ double group_sum_f64(double v)
 template <int G, bool kLds, int LPE>
 __device__ __forceinline__ void score_level(const ScoreParams& p, const Arrays& A, Scratch& S, int u, int n,
                                             bool use_ids, bool coarse, const double (&qreg)[G][128 / LPE],
-                                            long long budget, bool with_extra)
+                                            long long budget, bool with_extra, LevelTerms<G>& T)
 {
     constexpr int DPL = 128 / LPE;           // dims per lane: 16 or 8
     constexpr int EPI = kThreads / LPE;      // entries per pass of the workgroup
@@ -370,27 +366,36 @@ __device__ __forceinline__ void score_level(const ScoreParams& p, const Arrays& 
     {
         const int sub = tid % LPE, grp = tid / LPE;
         uint4 nxt[2][DPL / 8];
+        int nxt_w[2];
+        float mxf[G];        // largest logit, per head, of the entries with members that this lane finishes
+#pragma unroll
+        for (int h = 0; h < G; ++h) mxf[h] = -INFINITY;
         auto request = [&](int i0) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int i = i0 + j * EPI + grp;
 #pragma unroll
                 for (int v = 0; v < DPL / 8; ++v) nxt[j][v] = make_uint4(0, 0, 0, 0);
+                nxt_w[j] = 0;
                 if (i < n) {
                     const int id = use_ids ? A.ids[i] : i;
                     const uint4* kp = reinterpret_cast<const uint4*>(Kcu + (long long)id * kHeadDim + DPL * sub);
 #pragma unroll
                     for (int v = 0; v < DPL / 8; ++v) nxt[j][v] = kp[v];
+                    nxt_w[j] = Nu[id];
                 }
             }
         };
         request(0);
         for (int i0 = 0; i0 < n; i0 += 2 * EPI) {
             uint4 kv[2][DPL / 8];
+            int kw[2];
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j) {
 #pragma unroll
                 for (int v = 0; v < DPL / 8; ++v) kv[j][v] = nxt[j][v];
+                kw[j] = nxt_w[j];
+            }
             if (i0 + 2 * EPI < n) request(i0 + 2 * EPI);
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -410,10 +415,19 @@ __device__ __forceinline__ void score_level(const ScoreParams& p, const Arrays& 
                     double a = 0.0;
 #pragma unroll
                     for (int e = 0; e < DPL; ++e) a = fma(qreg[h][e], kd[e], a);
-                    a = group_sum_f64<LPE>(a);
-                    if (sub == 0 && i < n) A.lg[h * A.lg_stride + i] = a * p.scale;
+                    a = group_sum_f64<LPE>(a) * p.scale;
+                    if (sub == 0 && i < n) {
+                        A.lg[h * A.lg_stride + i] = a;
+                        if (kw[j] > 0) mxf[h] = fmaxf(mxf[h], (float)a);
+                    }
                 }
             }
+        }
+        const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            const float m = wave_max_f32(mxf[h]);
+            if (lane == 0) S.gmax[wave * 8 + h] = m;
         }
     }
 #pragma unroll
@@ -435,8 +449,41 @@ __device__ __forceinline__ void score_level(const ScoreParams& p, const Arrays& 
     phase_sync<kLds>();
 
     // ---- per-head normaliser of Eq. 1: LSE_h = log( sum_i N_i e^{l[h,i]} + e^{extra_h} ) ----
+    // shift: the largest logit of the level (the waves left theirs in S.gmax before the barrier above)
     double lse[G];
-    weighted_lse<G, kLds>(A, S, n, with_extra, [&](int i) { return A.wts[i] != 0; }, lse);
+    {
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            float m = S.gmax[h];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) m = fmaxf(m, S.gmax[w * 8 + h]);
+            T.shift[h] = (double)m;
+        }
+        T.kept = (G <= 6) && n <= 2 * kThreads;     // (larger groups have no registers to spare for the kept terms)
+        double sm[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) sm[h] = T.e[0][h] = T.e[1][h] = 0.0;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int i = tid + k * kThreads;
+            if (i < n && A.wts[i] != 0) {
+                const double w = (double)A.wts[i];
+#pragma unroll
+                for (int h = 0; h < G; ++h) {
+                    const double e = w * exp_shifted(A.lg[h * A.lg_stride + i] - T.shift[h]);
+                    if constexpr (G <= 6) T.e[k][h] = e;
+                    sm[h] += e;
+                }
+            }
+        }
+        for (int i = tid + 2 * kThreads; i < n; i += kThreads)
+            if (A.wts[i] != 0) {
+                const double w = (double)A.wts[i];
+#pragma unroll
+                for (int h = 0; h < G; ++h) sm[h] += w * exp_shifted(A.lg[h * A.lg_stride + i] - T.shift[h]);
+            }
+        combine_lse<G, kLds>(S, T.shift, sm, with_extra, lse);
+    }
 
     // ---- rank keys ----
     const double logG = log((double)G);
@@ -546,9 +593,33 @@ __device__ __forceinline__ void coarse_phase(const ScoreParams& p, unsigned char
     const int tid = threadIdx.x;
     const int n_c = p.n_coarse;
     const Arrays C = make_arrays<G, kLds>(lds, p, u);
-    score_level<G, kLds, LPE>(p, C, S, u, n_c, false, true, qreg, p.coarse_budget, false);
+    LevelTerms<G> T;
+    score_level<G, kLds, LPE>(p, C, S, u, n_c, false, true, qreg, p.coarse_budget, false, T);
+    // log-sum of the unpromising clusters: the same terms as in the level's own normaliser, so the
+    // exponentials are not taken again where they were kept
     double ex[G];
-    weighted_lse<G, kLds>(C, S, n_c, false, [&](int i) { return C.wts[i] != 0 && !C.flags[i]; }, ex);
+    {
+        double sm[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) sm[h] = 0.0;
+        if (G <= 6 && T.kept) {
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int i = tid + k * kThreads;
+                if (i < n_c && C.wts[i] != 0 && !C.flags[i])
+#pragma unroll
+                    for (int h = 0; h < G; ++h) sm[h] += T.e[k][h];
+            }
+        } else {
+            for (int i = tid; i < n_c; i += kThreads)
+                if (C.wts[i] != 0 && !C.flags[i]) {
+                    const double w = (double)C.wts[i];
+#pragma unroll
+                    for (int h = 0; h < G; ++h) sm[h] += w * exp_shifted(C.lg[h * C.lg_stride + i] - T.shift[h]);
+                }
+        }
+        combine_lse<G, kLds>(S, T.shift, sm, false, ex);
+    }
 #pragma unroll
     for (int h = 0; h < G; ++h)
         if (tid == h) S.extra[h] = ex[h];
@@ -592,7 +663,8 @@ __device__ __forceinline__ void fine_phase(const ScoreParams& p, unsigned char* 
 {
     const int tid = threadIdx.x;
     const Arrays F = make_arrays<G, kLds>(lds, p, u);
-    score_level<G, kLds, LPE>(p, F, S, u, n_f, two, false, qreg, p.key_budget, two);
+    LevelTerms<G> T;
+    score_level<G, kLds, LPE>(p, F, S, u, n_f, two, false, qreg, p.key_budget, two, T);
     write_views(F, n_f, p.r_f + (long long)u * p.f_stride, p.flag_f + (long long)u * p.f_stride);
 
     // One scan gives every selected cluster (ascending fine id) its slot in a compact list and the
