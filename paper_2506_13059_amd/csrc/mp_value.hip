@@ -407,12 +407,13 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
 // One workgroup of 128 threads per (unit, head); thread d combines dimension d over the chunks in
 // chunk order (bit-reproducible).  Every thread reads the (m, l) pairs of all chunks itself (the
 // same addresses across a wave: one transaction) and works out the weights 2^(m_i - M) on its own,
-// so nothing is exchanged and nothing waited for except memory: sixteen chunks are fetched at a
-// time, all loads of a batch in flight together, with an online rescale between batches.
+// so nothing is exchanged and nothing waited for except memory: kBatch chunks are fetched at a
+// time, all loads of a batch in flight together, with an online rescale between batches (the
+// launch picks the batch that covers all chunks in one trip to memory where it can).
+template <int kBatch>
 __global__ __launch_bounds__(128) void merge_kernel(const float* __restrict__ partials, int chunks_per_unit, int G,
                                                     uint16_t* __restrict__ out, float* __restrict__ lse)
 {
-    constexpr int kBatch = 16;
     const int uh = blockIdx.x;
     const int u = uh / G, h = uh - u * G;
     const int d = threadIdx.x;
@@ -487,7 +488,12 @@ hipError_t launch_merge(const float* partials, int n_units, int chunks_per_unit,
 {
     const long long blocks = (long long)n_units * G;
     if (blocks <= 0) return hipSuccess;
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)blocks), dim3(128), 0, stream, partials, chunks_per_unit, G, out, lse);
+    if (chunks_per_unit <= 16)
+        hipLaunchKernelGGL(merge_kernel<16>, dim3((unsigned)blocks), dim3(128), 0, stream, partials, chunks_per_unit, G, out, lse);
+    else if (chunks_per_unit <= 32)
+        hipLaunchKernelGGL(merge_kernel<32>, dim3((unsigned)blocks), dim3(128), 0, stream, partials, chunks_per_unit, G, out, lse);
+    else
+        hipLaunchKernelGGL(merge_kernel<64>, dim3((unsigned)blocks), dim3(128), 0, stream, partials, chunks_per_unit, G, out, lse);
     return hipGetLastError();
 }
 
