@@ -149,7 +149,8 @@ __device__ __forceinline__ void softmax_step(HeadState<G>& st, const float (&s0)
 // Stream the rows [w0, w1) of a source through one wave, 16 rows per iteration (two per group of 8
 // lanes), in strips of 128 rows whose row numbers are fetched with two coalesced loads.
 //
-// kScored = false (exact rows, the hot path): a three-stage software pipeline.  The loads of
+// kScored = false (exact rows, the hot path): a software pipeline of three stages (two for groups
+// of five heads, none for larger groups: no registers).  The loads of
 // iterations it+1 and it+2 are in flight while iteration it is consumed; they are issued through
 // inline assembly and waited for by count, because the compiler would otherwise sink each load
 // next to its use.  All eight iterations of a strip issue their loads (rows past the end are
@@ -205,8 +206,11 @@ __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S
         for (int j0 = w0; j0 < w1; j0 += kStrip) {
             const int ia = na, ib = nb;
             if (j0 + kStrip < w1) strip_rows(j0 + kStrip, na, nb);
-            if constexpr (G <= 4) {
-                u32x4 buf[3][8];
+            if constexpr (G <= 5) {
+                // loads of kStages - 1 later iterations are in flight while one is consumed: three
+                // stages where the registers allow it, two for the group of five
+                constexpr int kStages = G <= 4 ? 3 : 2;
+                u32x4 buf[kStages][8];
                 auto issue = [&](int it, u32x4 (&b)[8]) {
                     const int slot = it * 16 + r;
                     const int src_reg = (slot < 64) ? ia : ib;   // resolved at compile time after unrolling
@@ -226,13 +230,13 @@ __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S
                     issue_load16(b[7], v1 + 8);
                 };
                 issue(0, buf[0]);
-                if (kIters > 1) issue(1, buf[1]);
+                if (kStages > 2 && kIters > 1) issue(1, buf[1 % kStages]);
 #pragma unroll
                 for (int it = 0; it < kIters; ++it) {
                     const int jj = j0 + it * 16;
-                    if (it + 2 < kIters) issue(it + 2, buf[(it + 2) % 3]);
-                    u32x4(&b)[8] = buf[it % 3];
-                    if (it + 2 < kIters) wait_rows<16>(b);
+                    if (it + kStages - 1 < kIters) issue(it + kStages - 1, buf[(it + kStages - 1) % kStages]);
+                    u32x4(&b)[8] = buf[it % kStages];
+                    if (kStages > 2 && it + 2 < kIters) wait_rows<16>(b);
                     else if (it + 1 < kIters) wait_rows<8>(b);
                     else wait_rows<0>(b);
                     if (jj < w1) {
