@@ -38,6 +38,128 @@ constexpr int kRowBytes = 256 + 16;       // LDS row of one centroid: 128 dims, 
 constexpr float kMarginScale = 1.0f / 8192.0f;   // 2^-13
 constexpr float kNoCentroid = -3.0e38f;          // score of a padded row (finite: index bits are packed into scores)
 
+// Scores of 32 centroids (one LDS tile: rows of kRowBytes, -|c|^2/2 in three bf16 pieces behind the
+// 128 dims) against this wave's 2 x 32 points, folded into the running best / second best of every
+// point.  Accumulator rows of a lane: m(i) = 8 (i / 4) + 4 half + i % 4.  The slot i of a score
+// inside the tile rides in its four lowest mantissa bits (a change of at most 2^-19 of its
+// magnitude), so that a pair of scores costs one max3, one med3 and one max; the tile of the best
+// score is noted per tile.
+__device__ __forceinline__ void fold_scores(const f32x16_t (&acc)[2], int j0, float (&best)[2], float (&second)[2],
+                                            int (&btile)[2])
+{
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const float before = best[c];
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            const float va = __uint_as_float((__float_as_uint(acc[c][i]) & ~15u) | (uint32_t)i);
+            const float vb = __uint_as_float((__float_as_uint(acc[c][i + 1]) & ~15u) | (uint32_t)(i + 1));
+            second[c] = fmaxf(second[c], __builtin_amdgcn_fmed3f(best[c], va, vb));
+            best[c] = fmaxf(fmaxf(va, vb), best[c]);
+        }
+        btile[c] = best[c] != before ? j0 : btile[c];
+    }
+}
+
+// The nine operand fragments a lane takes from one tile: the offset slots, then dims [16 ks + 8 half, +8).
+__device__ __forceinline__ void read_fragments(const unsigned char* tile, int col, int half, bf16x8_t (&f)[9])
+{
+    const unsigned char* row = tile + col * kRowBytes;
+    f[8] = *reinterpret_cast<const bf16x8_t*>(row + 256);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) f[ks] = *reinterpret_cast<const bf16x8_t*>(row + 32 * ks + 16 * half);
+}
+
+__device__ __forceinline__ void multiply_tile(const bf16x8_t (&f)[9], const bf16x8_t (&xb)[2][8], bf16x8_t ones,
+                                              bf16x8_t ones_too, f32x16_t (&acc)[2])
+{
+    const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[8], ones, zero, 0, 0, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[8], ones_too, zero, 0, 0, 0);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[ks], xb[0][ks], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[ks], xb[1][ks], acc[1], 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ void tile_scores(const unsigned char* tile, int col, int half, const bf16x8_t (&xb)[2][8],
+                                            bf16x8_t ones, bf16x8_t ones_too, int j0, float (&best)[2],
+                                            float (&second)[2], int (&btile)[2])
+{
+    f32x16_t acc[2];
+    {
+        const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(tile + col * kRowBytes + 256);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, ones, zero, 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, ones_too, zero, 0, 0, 0);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(tile + col * kRowBytes + 32 * ks + 16 * half);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[0][ks], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[1][ks], acc[1], 0, 0, 0);
+    }
+    fold_scores(acc, j0, best, second, btile);
+}
+
+// One 16-byte piece of a centroid row goes to its place in an LDS tile; the 16 lanes that hold a
+// row add up |c|^2 (exact products, a dozen fp32 roundings: at most 2^-20 of its value, far below
+// the bound on a score), and the lane with the first piece writes -|c|^2/2 behind the row, split
+// exactly into three bf16 values (24 significant bits in three pieces of 8).  Returns |c|^2.
+__device__ __forceinline__ float deposit_piece(unsigned char* tile_row, int seg, uint4 w, bool exists)
+{
+    *reinterpret_cast<uint4*>(tile_row + seg * 16) = w;
+    float s = dot2_bf16(w.x, w.x, 0.f);
+    s = dot2_bf16(w.y, w.y, s);
+    s = dot2_bf16(w.z, w.z, s);
+    s = dot2_bf16(w.w, w.w, s);
+    s = sum8(s);
+    s += dpp_f32<kDppMirror>(s);      // the other 8 lanes of the row of 16
+    if (seg == 0) {
+        const float v = exists ? -0.5f * s : kNoCentroid;
+        const uint32_t hi = __float_as_uint(v) & 0xffff0000u;
+        const float r1 = v - __uint_as_float(hi);
+        const uint32_t mid = __float_as_uint(r1) & 0xffff0000u;
+        const uint32_t lo = __float_as_uint(r1 - __uint_as_float(mid)) & 0xffff0000u;
+        *reinterpret_cast<uint4*>(tile_row + 256) = make_uint4((hi >> 16) | mid, lo >> 16, 0u, 0u);
+    }
+    return s;
+}
+
+// The two halves of a wave hold the other accumulator rows of the same points: combine them, write
+// the stage-1 assignment, and list the point for the exact pass unless its two best scores are
+// further apart than the margin.
+__device__ __forceinline__ void finish_points(int half, const float (&best)[2], const float (&second)[2],
+                                              const int (&btile)[2], const float (&x2)[2], const int (&tpt)[2], int x0,
+                                              int x1, float c2max, int32_t* assign_u, int32_t* amb_list_u,
+                                              int32_t* amb_cnt_ub)
+{
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int slot = (int)(__float_as_uint(best[c]) & 15u);
+        const int bj = btile[c] + 8 * (slot >> 2) + 4 * half + (slot & 3);
+        const float ob = __shfl_xor(best[c], 32, 64), os = __shfl_xor(second[c], 32, 64);
+        const int oj = __shfl_xor(bj, 32, 64);
+        const float ox = __shfl_xor(x2[c], 32, 64);
+        const float sec = fmaxf(fmaxf(second[c], os), fminf(best[c], ob));
+        int j = bj;
+        if (ob > best[c] || (ob == best[c] && oj < j)) j = oj;
+        const float bst = fmaxf(best[c], ob);
+        const float xx = x2[c] + ox;
+        const int t = tpt[c];
+        if (t < x1 && half == 0) {
+            assign_u[t] = j;
+            const float margin = kMarginScale * fmaxf(xx, c2max);
+            // (written so that a point without any comparable score also goes to the exact pass)
+            if (!(bst - sec > margin)) {
+                const int pos = atomicAdd(amb_cnt_ub, 1);
+                amb_list_u[x0 + pos] = t;
+            }
+        }
+    }
+}
+
 // grid = (ceil(max points per block / 256), nb, U); 256 threads = 4 waves of 64 points (two MFMA
 // column tiles that share every centroid fragment).  Centroid tiles are double-buffered in LDS; their
 // rows are requested two tiles ahead and wait in registers until the buffer they go to is free.
@@ -107,26 +229,9 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
         for (int pass = 0; pass < 2; ++pass) {
             const int e = pass * 256 + tid;
             const int row = e >> 4, seg = e & 15;
-            const uint4 w = (j0 + row < k1) ? pre[pass] : make_uint4(0, 0, 0, 0);
-            *reinterpret_cast<uint4*>(tile[buf] + row * kRowBytes + seg * 16) = w;
-            // |c|^2 from exact products, a dozen fp32 roundings: at most 2^-20 of its value, far below
-            // the bound on a score
-            float s = dot2_bf16(w.x, w.x, 0.f);
-            s = dot2_bf16(w.y, w.y, s);
-            s = dot2_bf16(w.z, w.z, s);
-            s = dot2_bf16(w.w, w.w, s);
-            s = sum8(s);
-            s += dpp_f32<kDppMirror>(s);      // the other 8 lanes of the row of 16
-            c2max = fmaxf(c2max, s);          // (rows past the last centroid are zeros)
-            if (seg == 0) {
-                // v = hi + mid + lo exactly: 24 significant bits in three pieces of 8
-                const float v = (j0 + row < k1) ? -0.5f * s : kNoCentroid;
-                const uint32_t hi = __float_as_uint(v) & 0xffff0000u;
-                const float r1 = v - __uint_as_float(hi);
-                const uint32_t mid = __float_as_uint(r1) & 0xffff0000u;
-                const uint32_t lo = __float_as_uint(r1 - __uint_as_float(mid)) & 0xffff0000u;
-                *reinterpret_cast<uint4*>(tile[buf] + row * kRowBytes + 256) = make_uint4((hi >> 16) | mid, lo >> 16, 0u, 0u);
-            }
+            const bool exists = j0 + row < k1;
+            const uint4 w = exists ? pre[pass] : make_uint4(0, 0, 0, 0);
+            c2max = fmaxf(c2max, deposit_piece(tile[buf] + row * kRowBytes, seg, w, exists));   // (absent rows are zeros)
         }
     };
     float best[2] = {-INFINITY, -INFINITY}, second[2] = {-INFINITY, -INFINITY};
@@ -142,35 +247,7 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
         const bool more = j0 + kTile < k1;
         request(j0 + 2 * kTile, after);
         __builtin_amdgcn_sched_barrier(0);      // (the compiler would sink the loads below the multiplications)
-        // accumulator rows of this lane: m(i) = 8 (i / 4) + 4 half + i % 4
-        f32x16_t acc[2];
-        {
-            const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(tile[buf] + col * kRowBytes + 256);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, ones, zero, 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, ones_too, zero, 0, 0, 0);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(tile[buf] + col * kRowBytes + 32 * ks + 16 * half);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[0][ks], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[1][ks], acc[1], 0, 0, 0);
-        }
-        // best and second best per point.  The slot i of a score inside the tile rides in its four
-        // lowest mantissa bits (a change of at most 2^-19 of its magnitude), so that a pair of scores
-        // costs one max3, one med3 and one max; the tile of the best score is noted per tile.
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const float before = best[c];
-#pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                const float va = __uint_as_float((__float_as_uint(acc[c][i]) & ~15u) | (uint32_t)i);
-                const float vb = __uint_as_float((__float_as_uint(acc[c][i + 1]) & ~15u) | (uint32_t)(i + 1));
-                second[c] = fmaxf(second[c], __builtin_amdgcn_fmed3f(best[c], va, vb));
-                best[c] = fmaxf(fmaxf(va, vb), best[c]);
-            }
-            btile[c] = best[c] != before ? j0 : btile[c];
-        }
+        tile_scores(tile[buf], col, half, xb, ones, ones_too, j0, best, second, btile);
         if (more) deposit(j0 + kTile, buf ^ 1, next);
         __syncthreads();
     };
@@ -185,29 +262,119 @@ __global__ __launch_bounds__(256) void assign_mfma_kernel(const uint16_t* __rest
     if (lane == 0) wave_c2max[wave] = c2max;
     __syncthreads();
     c2max = fmaxf(fmaxf(wave_c2max[0], wave_c2max[1]), fmaxf(wave_c2max[2], wave_c2max[3]));
-    // the two halves of the wave hold the other rows of the same points
+    finish_points(half, best, second, btile, x2, tpt, x0, x1, c2max, assign + u * assign_stride,
+                  amb_list + u * list_stride, amb_cnt + u * cnt_stride + b);
+}
+
+// The same stage for blocks of at most kResidentK centroids (every blockwise build with one centroid
+// per 32 tokens and blocks of 8192): all centroids of the block stay in LDS, a workgroup walks
+// several chunks of 256 points of its (block, unit), and the points of the next chunk are on their
+// way from memory while the current ones are multiplied.  No barrier after the centroids are in
+// place.  grid = (workgroups per (block, unit), nb, U), dynamic LDS = kResidentK rows.
+constexpr int kResidentK = 256;
+__global__ __launch_bounds__(256) void assign_resident_kernel(const uint16_t* __restrict__ X, long long x_unit_rows,
+                                                              const int32_t* __restrict__ blocks,
+                                                              const uint16_t* __restrict__ C, long long c_unit_rows,
+                                                              int32_t* __restrict__ assign, long long assign_stride,
+                                                              int32_t* __restrict__ amb_list, long long list_stride,
+                                                              int32_t* __restrict__ amb_cnt, int cnt_stride)
+{
+    extern __shared__ __align__(16) unsigned char ctile[];      // [kResidentK][kRowBytes]
+    __shared__ float wave_c2max[4];
+    const int u = blockIdx.z, b = blockIdx.y;
+    const int x0 = blocks[4 * b + 0], x1 = blocks[4 * b + 1], k0 = blocks[4 * b + 2];
+    const int k1 = min(blocks[4 * b + 3], k0 + kResidentK);     // (the launch guarantees the block has no more)
+    const int n_chunks = (x1 - x0 + kPtsPerWg - 1) / kPtsPerWg;
+    int chunk = blockIdx.x;
+    if (chunk >= n_chunks) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    const uint16_t* Xu = X + (long long)u * x_unit_rows * kHeadDim;
+
+    bf16x8_t xb[2][8], xn[2][8];
+    auto load_points = [&](int ch, bf16x8_t (&dst)[2][8]) {
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        const int slot = (int)(__float_as_uint(best[c]) & 15u);
-        const int bj = btile[c] + 8 * (slot >> 2) + 4 * half + (slot & 3);
-        const float ob = __shfl_xor(best[c], 32, 64), os = __shfl_xor(second[c], 32, 64);
-        const int oj = __shfl_xor(bj, 32, 64);
-        const float ox = __shfl_xor(x2[c], 32, 64);
-        const float sec = fmaxf(fmaxf(second[c], os), fminf(best[c], ob));
-        int j = bj;
-        if (ob > best[c] || (ob == best[c] && oj < j)) j = oj;
-        const float bst = fmaxf(best[c], ob);
-        const float xx = x2[c] + ox;
-        const int t = tpt[c];
-        if (t < x1 && half == 0) {
-            assign[u * assign_stride + t] = j;
-            const float margin = kMarginScale * fmaxf(xx, c2max);
-            // (written so that a point without any comparable score also goes to the exact pass)
-            if (!(bst - sec > margin)) {
-                const int pos = atomicAdd(&amb_cnt[u * cnt_stride + b], 1);
-                amb_list[u * list_stride + x0 + pos] = t;
+        for (int c = 0; c < 2; ++c) {
+            const int t = x0 + ch * kPtsPerWg + wave * 64 + 32 * c + col;
+            const uint4* xp = reinterpret_cast<const uint4*>(Xu + (long long)(t < x1 ? t : x0) * kHeadDim);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) dst[c][ks] = __builtin_bit_cast(bf16x8_t, xp[2 * ks + half]);
+        }
+    };
+    load_points(chunk, xb);
+
+    // ---- the block's centroids: 16 lanes per row, rows past the last centroid are zeros that can never win ----
+    const int ntiles = (k1 - k0 + kTile - 1) / kTile;
+    float c2max = 0.f;
+    {
+        const uint16_t* Cu = C + (long long)u * c_unit_rows * kHeadDim;
+        for (int e = tid; e < ntiles * kTile * 16; e += 256) {
+            const int row = e >> 4, seg = e & 15;
+            const bool exists = k0 + row < k1;
+            uint4 w = make_uint4(0, 0, 0, 0);
+            if (exists) w = reinterpret_cast<const uint4*>(Cu + (long long)(k0 + row) * kHeadDim)[seg];
+            c2max = fmaxf(c2max, deposit_piece(ctile + row * kRowBytes, seg, w, exists));
+        }
+    }
+    c2max = wave_max_f32(c2max);
+    if (lane == 0) wave_c2max[wave] = c2max;
+    __syncthreads();
+    c2max = fmaxf(fmaxf(wave_c2max[0], wave_c2max[1]), fmaxf(wave_c2max[2], wave_c2max[3]));
+
+    const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, half == 0 ? make_uint4(0x3f803f80u, 0x00003f80u, 0u, 0u)
+                                                                  : make_uint4(0u, 0u, 0u, 0u));
+    bf16x8_t ones_too = ones;
+    asm volatile("" : "+v"(ones_too));
+    while (true) {
+        const int next = chunk + (int)gridDim.x;
+        const bool has_next = next < n_chunks;
+        if (has_next) load_points(next, xn);
+        float x2[2] = {0.f, 0.f};
+        int tpt[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            tpt[c] = x0 + chunk * kPtsPerWg + wave * 64 + 32 * c + col;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const uint4 w = __builtin_bit_cast(uint4, xb[c][ks]);
+                x2[c] = dot2_bf16(w.x, w.x, x2[c]);      // |x|^2 only scales the margin
+                x2[c] = dot2_bf16(w.y, w.y, x2[c]);
+                x2[c] = dot2_bf16(w.z, w.z, x2[c]);
+                x2[c] = dot2_bf16(w.w, w.w, x2[c]);
             }
         }
+        float best[2] = {-INFINITY, -INFINITY}, second[2] = {-INFINITY, -INFINITY};
+        int btile[2] = {k0, k0};
+        // The comparison of one tile's scores runs while the next tile is multiplied: two accumulator
+        // sets, and an instruction order that puts a few comparison instructions behind every matrix
+        // instruction (a matrix instruction waits for its predecessor on the same accumulators anyway).
+        auto multiply_and_fold = [&](int t, f32x16_t (&cur)[2], const f32x16_t (&prev)[2], bool fold) {
+            bf16x8_t f[9];
+            read_fragments(ctile + t * kTile * kRowBytes, col, half, f);
+            multiply_tile(f, xb, ones, ones_too, cur);
+            if (fold) fold_scores(prev, k0 + (t - 1) * kTile, best, second, btile);
+#pragma unroll
+            for (int q = 0; q < 18; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one matrix instruction
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);     // four vector instructions
+            }
+        };
+        f32x16_t acc_a[2], acc_b[2];
+        multiply_and_fold(0, acc_a, acc_b, false);
+        for (int t = 1; t < ntiles; t += 2) {
+            multiply_and_fold(t, acc_b, acc_a, true);
+            if (t + 1 < ntiles) multiply_and_fold(t + 1, acc_a, acc_b, true);
+        }
+        if (ntiles & 1) fold_scores(acc_a, k0 + (ntiles - 1) * kTile, best, second, btile);
+        else fold_scores(acc_b, k0 + (ntiles - 1) * kTile, best, second, btile);
+        finish_points(half, best, second, btile, x2, tpt, x0, x1, c2max, assign + u * assign_stride,
+                      amb_list + u * list_stride, amb_cnt + u * cnt_stride + b);
+        if (!has_next) break;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) xb[c][ks] = xn[c][ks];
+        chunk = next;
     }
 }
 
@@ -386,15 +553,33 @@ __global__ __launch_bounds__(256) void assign_recheck_kernel(const uint16_t* __r
 }  // namespace
 
 hipError_t launch_assign(const uint16_t* X, long long x_unit_rows, const int32_t* blocks_dev, int nb, int max_pts,
-                         int U, const uint16_t* C, long long c_unit_rows, int32_t* assign, long long assign_stride,
-                         int32_t* amb_list, long long list_stride, int32_t* amb_cnt, int cnt_stride, hipStream_t s)
+                         int max_k, int U, const uint16_t* C, long long c_unit_rows, int32_t* assign,
+                         long long assign_stride, int32_t* amb_list, long long list_stride, int32_t* amb_cnt,
+                         int cnt_stride, hipStream_t s)
 {
     if (nb <= 0 || max_pts <= 0 || U <= 0) return hipSuccess;
     if (nb > cnt_stride || U > 65535) return hipErrorInvalidValue;
     hipError_t e = launch_fill_i32(amb_cnt, (long long)U * cnt_stride, 0, s);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(assign_mfma_kernel, dim3((max_pts + kPtsPerWg - 1) / kPtsPerWg, nb, U), dim3(256), 0, s, X, x_unit_rows,
-                       blocks_dev, C, c_unit_rows, assign, assign_stride, amb_list, list_stride, amb_cnt, cnt_stride);
+    const int n_chunks = (max_pts + kPtsPerWg - 1) / kPtsPerWg;
+    if (max_k > 0 && max_k <= kResidentK && n_chunks >= 4) {
+        // enough workgroups to fill the chip, several chunks each where the blocks are long enough
+        static bool configured = false;
+        const int smem = kResidentK * kRowBytes;
+        if (!configured) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&assign_resident_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (e != hipSuccess) return e;
+            configured = true;
+        }
+        const long long groups = (long long)nb * U;
+        const int gx = (int)std::min<long long>(n_chunks, std::max<long long>(4, (1024 + groups - 1) / groups));
+        hipLaunchKernelGGL(assign_resident_kernel, dim3(gx, nb, U), dim3(256), smem, s, X, x_unit_rows, blocks_dev, C,
+                           c_unit_rows, assign, assign_stride, amb_list, list_stride, amb_cnt, cnt_stride);
+    } else {
+        hipLaunchKernelGGL(assign_mfma_kernel, dim3(n_chunks, nb, U), dim3(256), 0, s, X, x_unit_rows, blocks_dev, C,
+                           c_unit_rows, assign, assign_stride, amb_list, list_stride, amb_cnt, cnt_stride);
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int z = std::min(128, (max_pts + 3) / 4);

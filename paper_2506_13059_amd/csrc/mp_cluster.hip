@@ -176,7 +176,7 @@ struct Problem {
 mp_status launch_assign(mp_ctx* ctx, const Problem& pr, hipStream_t s)
 {
     // the member-list array is free during the assignment step and holds the points of the exact pass
-    MP_HIPC(mp::launch_assign(pr.X, pr.x_unit_rows, pr.blocks_dev, pr.nb, pr.max_pts, ctx->U, pr.C, pr.c_unit_rows,
+    MP_HIPC(mp::launch_assign(pr.X, pr.x_unit_rows, pr.blocks_dev, pr.nb, pr.max_pts, pr.max_k, ctx->U, pr.C, pr.c_unit_rows,
                               pr.assign, pr.assign_stride, pr.list, pr.list_stride, ctx->km_amb, ctx->max_blocks, s));
     return MP_OK;
 }
@@ -605,7 +605,7 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* k_new
         MP_HIPC(hipGetLastError());
     }
     // ---- one-shot assignment of the appended tokens + running mean of the touched centroids ----
-    MP_HIPC(mp::launch_assign(ctx->Kfb, (long long)ctx->FBcap, ctx->blocks_dev, 1, n_new, U, ctx->km_Cf, Fcap,
+    MP_HIPC(mp::launch_assign(ctx->Kfb, (long long)ctx->FBcap, ctx->blocks_dev, 1, n_new, 0, U, ctx->km_Cf, Fcap,
                               ctx->km_assign, Ncap, ctx->km_list, Ncap, ctx->km_amb, ctx->max_blocks, s));
     MP_HIPC(hipMemcpy2DAsync(ctx->km_assign, (size_t)Ncap * 4, ctx->fot + t0, (size_t)Ncap * 4, (size_t)nb_old * 4, U,
                              hipMemcpyDeviceToDevice, s));
