@@ -346,24 +346,33 @@ __global__ __launch_bounds__(256) void assign_resident_kernel(const uint16_t* __
         float best[2] = {-INFINITY, -INFINITY}, second[2] = {-INFINITY, -INFINITY};
         int btile[2] = {k0, k0};
         // The comparison of one tile's scores runs while the next tile is multiplied: two accumulator
-        // sets, and an instruction order that puts a few comparison instructions behind every matrix
-        // instruction (a matrix instruction waits for its predecessor on the same accumulators anyway).
-        auto multiply_and_fold = [&](int t, f32x16_t (&cur)[2], const f32x16_t (&prev)[2], bool fold) {
+        // sets, and an instruction order that puts a few comparison instructions behind every pair of
+        // matrix instructions (a matrix instruction waits for its predecessor on the same accumulators
+        // anyway) and keeps one LDS read in flight.
+        auto multiply_and_fold = [&](int t, f32x16_t (&cur)[2], const f32x16_t (&prev)[2]) {
             bf16x8_t f[9];
             read_fragments(ctile + t * kTile * kRowBytes, col, half, f);
             multiply_tile(f, xb, ones, ones_too, cur);
-            if (fold) fold_scores(prev, k0 + (t - 1) * kTile, best, second, btile);
+            fold_scores(prev, k0 + (t - 1) * kTile, best, second, btile);
+            // order: fragment reads run one step ahead of the pair of matrix instructions that use them,
+            // eight comparison instructions follow every pair
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
-            for (int q = 0; q < 18; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one matrix instruction
-                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);     // four vector instructions
+            for (int q = 0; q < 9; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);     // two matrix instructions
+                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);     // eight vector instructions
+                if (q < 7) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // the read after next
             }
         };
         f32x16_t acc_a[2], acc_b[2];
-        multiply_and_fold(0, acc_a, acc_b, false);
+        {
+            bf16x8_t f[9];
+            read_fragments(ctile, col, half, f);
+            multiply_tile(f, xb, ones, ones_too, acc_a);
+        }
         for (int t = 1; t < ntiles; t += 2) {
-            multiply_and_fold(t, acc_b, acc_a, true);
-            if (t + 1 < ntiles) multiply_and_fold(t + 1, acc_a, acc_b, true);
+            multiply_and_fold(t, acc_b, acc_a);
+            if (t + 1 < ntiles) multiply_and_fold(t + 1, acc_a, acc_b);
         }
         if (ntiles & 1) fold_scores(acc_a, k0 + (ntiles - 1) * kTile, best, second, btile);
         else fold_scores(acc_b, k0 + (ntiles - 1) * kTile, best, second, btile);
