@@ -379,9 +379,7 @@ __global__ __launch_bounds__(256) void assign_resident_kernel(const uint16_t* __
         finish_points(half, best, second, btile, x2, tpt, x0, x1, c2max, assign + u * assign_stride,
                       amb_list + u * list_stride, amb_cnt + u * cnt_stride + b);
         if (!has_next) break;
-#pragma unroll
         for (int c = 0; c < 2; ++c)
-#pragma unroll
             for (int ks = 0; ks < 8; ++ks) xb[c][ks] = xn[c][ks];
         chunk = next;
     }
