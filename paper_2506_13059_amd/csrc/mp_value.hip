@@ -157,15 +157,18 @@ __device__ __forceinline__ void softmax_step(HeadState<G>& st, const float (&s0)
 // clamped to the last valid row and masked), so the counts are static.
 // kScored = true (centroid terms): logits are read ready-made (log2 units, ln N included) and
 // only the value-centroid row is loaded; this stream is short and uses plain loads.
+// The G heads of `st` are the heads h0, h0 + 1, ... of the unit's gt heads (clamped to the last one:
+// a wave that owns fewer than G heads computes the last one again and its caller drops the copy).
 template <int G, bool kScored, int kIters>
 __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S, const ValuePassParams& p, int u,
-                                            int w0, int w1, int end, int r, int c, int lane)
+                                            int w0, int w1, int end, int r, int c, int lane, int gt, int h0)
 {
+    auto head = [&](int h) { return h0 + h < gt ? h0 + h : gt - 1; };
     const uint16_t* __restrict__ Vb = S.V + (long long)u * S.unit_rows * kHeadDim;
     const int32_t* __restrict__ rows = S.rows ? S.rows + (long long)u * S.rows_stride : nullptr;
     constexpr int kStrip = 16 * kIters;   // rows a wave handles between two refills of its index registers
     if constexpr (kScored) {
-        const float* __restrict__ sc = S.scores + (long long)u * S.rows_stride * G;
+        const float* __restrict__ sc = S.scores + (long long)u * S.rows_stride * gt;
         for (int j0 = w0; j0 < w1; j0 += 16) {
             const int ja = j0 + r, jb = j0 + 8 + r;
             const bool va = ja < w1, vb = jb < w1;
@@ -177,8 +180,8 @@ __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S
             float s0[G], s1[G];
 #pragma unroll
             for (int h = 0; h < G; ++h) {
-                s0[h] = va ? sc[(long long)pa * G + h] : -INFINITY;
-                s1[h] = vb ? sc[(long long)pb * G + h] : -INFINITY;
+                s0[h] = va ? sc[(long long)pa * gt + head(h)] : -INFINITY;
+                s1[h] = vb ? sc[(long long)pb * gt + head(h)] : -INFINITY;
             }
             softmax_step<G>(st, s0, s1, t0, t1);
         }
@@ -187,7 +190,7 @@ __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S
         uint4 qlo[G], qhi[G];
 #pragma unroll
         for (int h = 0; h < G; ++h) {
-            const uint4* qp = reinterpret_cast<const uint4*>(p.q + ((long long)u * G + h) * kHeadDim) + c;
+            const uint4* qp = reinterpret_cast<const uint4*>(p.q + ((long long)u * gt + head(h)) * kHeadDim) + c;
             qlo[h] = qp[0];
             qhi[h] = qp[8];
         }
@@ -321,24 +324,31 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
         return;
     }
 
-    HeadState<G> st;
+    // Groups of more than five heads do not fit one wave's registers next to the load pipeline: the
+    // waves then work in pairs on the same rows, each wave of a pair on one half of the heads (the
+    // second request for a row is served by the cache), two row streams per workgroup instead of four.
+    constexpr bool kSplit = G > 5;
+    constexpr int GH = kSplit ? (G + 1) / 2 : G;        // heads per wave
+    const int half = kSplit ? (wave & 1) : 0;           // which heads: [0, GH) or [GH, G)
+    HeadState<GH> st;
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
+    for (int h = 0; h < GH; ++h) {
         st.m[h] = -INFINITY;
         st.l[h] = 0.f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) st.acc[h][e] = 0.f;
     }
 
-    const int wave_rows = chunk_rows >> 2;
-    const int w0 = begin + wave * wave_rows;
+    const int wave_rows = kSplit ? chunk_rows >> 1 : chunk_rows >> 2;
+    const int w0 = begin + (kSplit ? wave >> 1 : wave) * wave_rows;
     const int w1 = (w0 + wave_rows < end) ? w0 + wave_rows : end;
+    const int h0 = half * GH;
     if (S.scores != nullptr)
-        stream_rows<G, true, 8>(st, S, p, u, w0, w1, end, r, c, lane);
+        stream_rows<GH, true, 8>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
     else if (chunk_rows >= 512)
-        stream_rows<G, false, 8>(st, S, p, u, w0, w1, end, r, c, lane);
+        stream_rows<GH, false, 8>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
     else
-        stream_rows<G, false, 2>(st, S, p, u, w0, w1, end, r, c, lane);
+        stream_rows<GH, false, 2>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
 
     // -------- combine the 32 row groups of the workgroup (4 waves x 8 groups), HB heads per round ----
     float* sm_m = smem;             // [32][HB]
@@ -354,15 +364,22 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
         for (int hh = 0; hh < HB; ++hh) {
             const int h = hb + hh;
             if (h < G) {
+                // this wave's state of head h, or nothing (m = -inf, zeros) for a head of the other half
+                const int ia = h < GH ? h : 0, ib = h >= GH ? h - GH : 0;      // index as half 0 / half 1
+                const bool own = !kSplit || (half == 0 ? h < GH : h >= GH);
+                const float hm = half == 0 ? st.m[ia] : st.m[ib], hl = half == 0 ? st.l[ia] : st.l[ib];
+                float a[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) a[e] = own ? (half == 0 ? st.acc[ia][e] : st.acc[ib][e]) : 0.f;
                 if (c == 0) {
-                    sm_m[sid * HB + hh] = st.m[h];
-                    sm_l[sid * HB + hh] = st.l[h];
+                    sm_m[sid * HB + hh] = own ? hm : -INFINITY;
+                    sm_l[sid * HB + hh] = own ? hl : 0.f;
                 }
                 float4* dst = reinterpret_cast<float4*>(sm_acc + ((sid * HB + hh) * kHeadDim));
-                dst[2 * c] = make_float4(st.acc[h][0], st.acc[h][1], st.acc[h][2], st.acc[h][3]);
-                dst[2 * c + 1] = make_float4(st.acc[h][4], st.acc[h][5], st.acc[h][6], st.acc[h][7]);
-                dst[16 + 2 * c] = make_float4(st.acc[h][8], st.acc[h][9], st.acc[h][10], st.acc[h][11]);
-                dst[16 + 2 * c + 1] = make_float4(st.acc[h][12], st.acc[h][13], st.acc[h][14], st.acc[h][15]);
+                dst[2 * c] = make_float4(a[0], a[1], a[2], a[3]);
+                dst[2 * c + 1] = make_float4(a[4], a[5], a[6], a[7]);
+                dst[16 + 2 * c] = make_float4(a[8], a[9], a[10], a[11]);
+                dst[16 + 2 * c + 1] = make_float4(a[12], a[13], a[14], a[15]);
             }
         }
         __syncthreads();
