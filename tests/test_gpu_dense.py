@@ -42,6 +42,8 @@ def _check(out, lse, ref, ref_lse):
     (3, 6, 3, 2049),      # group of 2, chunk boundary + 1
     (1, 7, 1, 515),
     (1, 3, 1, 64),
+    (2, 12, 2, 3000),     # group of 6: two half-groups per row stream, several chunks
+    (1, 8, 1, 5003),      # group of 8 over several chunks with a ragged end
 ])
 def test_dense_matches_oracle(B, Hq, Hkv, n):
     from paper_2506_13059_amd import binding as mp
