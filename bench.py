@@ -63,7 +63,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one process, one device); --gpus must be 1. "
-              "Units (sequence x KV head) shard over GPUs without any exchange; see DESIGN.md.", file=sys.stderr)
+              "Units (sequence x KV head) are independent and would shard over GPUs without any exchange.", file=sys.stderr)
         sys.exit(2)
 
     import torch
