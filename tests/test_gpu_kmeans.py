@@ -84,6 +84,16 @@ def test_cluster_all_points_equal_many_coinciding_centroids():
     ctx.close()
 
 
+def test_cluster_duplicates_and_coinciding_centroids_in_long_blocks():
+    # the same two degenerate inputs at sizes that take the assignment kernel which keeps a block's
+    # centroids in LDS (at least four chunks of 256 points, at most 256 centroids), the second with
+    # a ragged last chunk
+    ctx, K, V = _run_case(1, 2, 2, 1536, 12, 2, 32, 4, 0, 0, iters=3, seed=17, distinct_rows=12)
+    ctx.close()
+    ctx, K, V = _run_case(1, 2, 1, 1100, 4, 1, 100, 0, 0, 0, iters=2, seed=18, distinct_rows=1)
+    ctx.close()
+
+
 def test_cluster_thousands_of_centroids_in_one_block():
     # 4100 centroids in a single block: few list-building waves, scores of the exact pass not cached
     ctx, K, V = _run_case(1, 2, 1, 6000, 300, 1, 4100, 0, 0, 0, iters=2, seed=16)
