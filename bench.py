@@ -90,12 +90,15 @@ def main():
     ctx = mp.MpContext(w.batch, w.n_q_heads, w.n_kv_heads, max_tokens=w.context, levels=w.levels, max_fine=w.n_fine,
                        max_coarse=w.n_coarse, block_w=w.block_w, block_alpha=w.block_alpha, max_tail=256)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    ctx.mp_cluster_kv(K, V, w.n_fine, w.n_coarse, iters=w.kmeans_iters, init_fine=data["init_fine"],
-                      init_coarse=data["init_coarse"] if w.levels == 2 else None)
-    e1.record()
-    torch.cuda.synchronize()
-    cluster_ms = e0.elapsed_time(e1)
+    cluster_runs = []
+    for _ in range(2):      # the first build also loads the kernels' code objects (a few ms, once per process)
+        e0.record()
+        ctx.mp_cluster_kv(K, V, w.n_fine, w.n_coarse, iters=w.kmeans_iters, init_fine=data["init_fine"],
+                          init_coarse=data["init_coarse"] if w.levels == 2 else None)
+        e1.record()
+        torch.cuda.synchronize()
+        cluster_runs.append(e0.elapsed_time(e1))
+    cluster_ms = cluster_runs[1]
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -212,6 +215,7 @@ def main():
                                     "speedup_vs_dense": round(dense_us / r["us"], 3)}
                           for kb, r in results.items() if kb != kb0},
         "cluster_build_ms": round(cluster_ms, 2),
+        "cluster_build_first_call_ms": round(cluster_runs[0], 2),
         "cluster_build_mtokens_per_s": round(w.units * w.context / cluster_ms / 1e3, 1),
         "online_generation": None if args.no_online else online_generation(mp, inputs, dev),
         "other_workloads": None if args.no_others else {
