@@ -212,17 +212,29 @@ inline uint64_t splitmix64(uint64_t& x)
     return z ^ (z >> 31);
 }
 
-// k distinct integers of [0, n): partial Fisher-Yates driven by splitmix64(seed)
+// k distinct integers of [0, n): partial Fisher-Yates driven by splitmix64(seed).  The identity
+// array it shuffles is kept between calls and put back after each (only the 2k touched places), so
+// a call costs O(k), not O(n): a build draws thousands of short lists from long ranges.
 void draw_distinct(uint64_t seed, int n, int k, int32_t* out)
 {
-    std::vector<int32_t> idx((size_t)n);
-    for (int i = 0; i < n; ++i) idx[i] = i;
+    static thread_local std::vector<int32_t> idx;
+    if ((int)idx.size() < n) {
+        const int old = (int)idx.size();
+        idx.resize((size_t)n);
+        for (int i = old; i < n; ++i) idx[i] = i;
+    }
     uint64_t st = seed;
     for (int i = 0; i < k; ++i) {
         const int j = i + (int)(splitmix64(st) % (uint64_t)(n - i));
         std::swap(idx[i], idx[j]);
         out[i] = idx[i];
     }
+    st = seed;
+    for (int i = 0; i < k; ++i) {
+        const int j = i + (int)(splitmix64(st) % (uint64_t)(n - i));
+        idx[j] = j;
+    }
+    for (int i = 0; i < k; ++i) idx[i] = i;
 }
 
 bool distinct_in_range(const int32_t* v, int k, int n)
