@@ -319,6 +319,28 @@ mp_status mp_dense_attention(const void* q, const void* k, const void* v, int32_
                              int32_t n_q_heads, int32_t n_kv_heads, int32_t n, float softmax_scale,
                              void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * mp_dense_attention_static -- mp_dense_attention for callers that cannot allocate: code under
+ * HIP graph capture, serving loops with a fixed memory plan, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels and bit-identical results, but no workspace argument: the
+ * partial results go to an array of MP_DENSE_STATIC_SCRATCH_BYTES bytes built into the library
+ * (every GPU the library runs on holds its own copy until the process ends).  The call allocates
+ * nothing and frees nothing.
+ *
+ * Limits: shapes with mp_dense_workspace_bytes(B, Hq, Hkv, n) > mp_dense_static_scratch_bytes()
+ * are rejected with MP_ECAPACITY (nothing enqueued).  All calls on one GPU share that GPU's array:
+ * calls that may overlap on the GPU (different streams without ordering, or another host thread)
+ * race on it -- order them on one stream.  The array keeps the last call's contents; nothing in
+ * it has to start at zero (every partial is written before it is read).
+ * Other errors: as mp_dense_attention; MP_EHIP if the array's address cannot be resolved (done
+ * once per device: by mp_create, else by the first call of this function on that device).
+ * ------------------------------------------------------------------------------------------- */
+#define MP_DENSE_STATIC_SCRATCH_BYTES (8u << 20)
+size_t mp_dense_static_scratch_bytes(void);
+mp_status mp_dense_attention_static(const void* q, const void* k, const void* v, int32_t batch,
+                                    int32_t n_q_heads, int32_t n_kv_heads, int32_t n, float softmax_scale,
+                                    void* out, float* lse, void* stream);
+
 /* Library version string. */
 const char* mp_version(void);
 

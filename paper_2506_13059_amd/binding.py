@@ -22,6 +22,7 @@ EXPORTS = [
     "mp_set_clustering", "mp_update_clusters", "mp_decode_attention", "mp_get_sizes", "mp_get_assignments",
     "mp_get_centroids", "mp_get_selection", "mp_get_counters", "mp_get_layout", "mp_dense_workspace_bytes",
     "mp_dense_attention", "mp_version", "mp_enable_stage_timing", "mp_get_stage_timing", "mp_update_seed_counts", "mp_local_buffer_init", "mp_local_buffer_size", "mp_decode_step",
+    "mp_dense_static_scratch_bytes", "mp_dense_attention_static",
 ]
 
 
@@ -79,6 +80,9 @@ def lib():
         L.mp_dense_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.mp_dense_workspace_bytes.restype = sz
         L.mp_dense_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
+        L.mp_dense_static_scratch_bytes.argtypes = []
+        L.mp_dense_static_scratch_bytes.restype = sz
+        L.mp_dense_attention_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -133,6 +137,20 @@ def mp_dense_attention(q, k, v, out=None, lse=None, workspace=None, softmax_scal
         out = torch.empty_like(q)
     st = lib().mp_dense_attention(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, n, softmax_scale, _ptr(out), _ptr(lse),
                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    _check(st)
+    return out
+
+
+def mp_dense_static_scratch_bytes():
+    return int(lib().mp_dense_static_scratch_bytes())
+
+
+def mp_dense_attention_static(q, k, v, out, lse=None, softmax_scale=0.0):
+    """mp_dense_attention without a workspace: `out` (and lse) are the caller's, nothing is allocated."""
+    B, Hq, _ = q.shape
+    Hkv, n = k.shape[1], k.shape[2]
+    st = lib().mp_dense_attention_static(_ptr(q), _ptr(k), _ptr(v), B, Hq, Hkv, n, softmax_scale, _ptr(out), _ptr(lse),
+                                         _stream())
     _check(st)
     return out
 

@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -29,6 +30,7 @@ mp_status set_clustering_impl(mp_ctx* ctx, const void* k, const void* k_lookup, 
                               const int32_t* fine_of_token, int32_t n_fine, const int32_t* coarse_of_fine, int32_t n_coarse,
                               hipStream_t s);
 void update_seed_counts(const mp_ctx* ctx, int n_new, int n_new_fine, int n_new_coarse, int32_t counts[6]);
+hipError_t resolve_static_scratch();   // further down in this file
 
 thread_local std::string g_err;   // errors of context-free calls
 
@@ -182,6 +184,7 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
                 mp::max_stream_chunks((int)ctx->tab_rows, ctx->U, 512);
 
     hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) e = mp::resolve_static_scratch();
     const size_t U = ctx->U, N = ctx->Ncap, F = ctx->Fcap, Cc = std::max(ctx->Ccap, 1), T = ctx->tab_rows, D = kHeadDimHost;
 #define A(ptr, count) if (e == hipSuccess) e = dev_alloc(ctx, &ctx->ptr, (count))
     A(Kp, U * N * D); A(Vp, U * N * D); A(perm, U * N); A(fot, U * N);
@@ -671,23 +674,20 @@ size_t mp_dense_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_h
     return sizeof(float) * (size_t)U * chunks * G * kPartStride;
 }
 
-mp_status mp_dense_attention(const void* q, const void* k, const void* v, int32_t batch, int32_t n_q_heads,
-                             int32_t n_kv_heads, int32_t n, float softmax_scale, void* out, float* lse, void* workspace,
-                             size_t workspace_bytes, void* stream)
-{
-    if (!q || !out || !workspace) return fail(nullptr, MP_EINVAL, "mp_dense_attention: null pointer");
-    if (batch <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || n < 0 || n_q_heads % n_kv_heads)
-        return fail(nullptr, MP_EINVAL, "mp_dense_attention: bad shape B=%d Hq=%d Hkv=%d n=%d", batch, n_q_heads, n_kv_heads, n);
-    if (n > 0 && (!k || !v)) return fail(nullptr, MP_EINVAL, "mp_dense_attention: null k/v with n > 0");
-    const int U = batch * n_kv_heads, G = n_q_heads / n_kv_heads;
-    if (G > 8) return fail(nullptr, MP_EINVAL, "mp_dense_attention: group size %d > 8 is not supported", G);
-    const size_t need = mp_dense_workspace_bytes(batch, n_q_heads, n_kv_heads, n);
-    if (workspace_bytes < need) return fail(nullptr, MP_EINVAL, "mp_dense_attention: workspace %zu < %zu bytes", workspace_bytes, need);
-    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)kHeadDimHost);
+}  // extern "C"
 
+namespace {
+
+// Split-KV launch sequence of the dense kernel; `partials` holds mp_dense_workspace_bytes() bytes.
+mp_status dense_impl(const char* who, const void* q, const void* k, const void* v, int32_t batch, int32_t n_q_heads,
+                     int32_t n_kv_heads, int32_t n, float softmax_scale, void* out, float* lse, float* partials,
+                     hipStream_t s)
+{
+    const int U = batch * n_kv_heads, G = n_q_heads / n_kv_heads;
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)kHeadDimHost);
     ValuePassParams p{};
     p.q = (const uint16_t*)q;
-    p.partials = (float*)workspace;
+    p.partials = partials;
     p.n_units = U;
     const int dcr = pick_chunk_rows(n, U);
     p.chunks_per_unit = ceil_div(n > 0 ? n : 1, dcr);
@@ -701,10 +701,97 @@ mp_status mp_dense_attention(const void* q, const void* k, const void* v, int32_
     p.src[0].count_max = n;
     p.src[0].chunk0 = 0;
     p.src[0].n_chunks = p.chunks_per_unit;
-    hipStream_t s = (hipStream_t)stream;
-    MP_HIP(nullptr, launch_value_pass(p, G, s));
-    MP_HIP(nullptr, launch_merge(p.partials, U, p.chunks_per_unit, G, (uint16_t*)out, lse, s));
+    hipError_t e = launch_value_pass(p, G, s);
+    if (e == hipSuccess) e = launch_merge(p.partials, U, p.chunks_per_unit, G, (uint16_t*)out, lse, s);
+    if (e != hipSuccess) return fail(nullptr, MP_EHIP, "%s: %s", who, hipGetErrorString(e));
     return MP_OK;
+}
+
+mp_status dense_args_ok(const char* who, const void* q, const void* k, const void* v, int32_t batch, int32_t n_q_heads,
+                        int32_t n_kv_heads, int32_t n, const void* out)
+{
+    if (!q || !out) return fail(nullptr, MP_EINVAL, "%s: null pointer", who);
+    if (batch <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || n < 0 || n_q_heads % n_kv_heads)
+        return fail(nullptr, MP_EINVAL, "%s: bad shape B=%d Hq=%d Hkv=%d n=%d", who, batch, n_q_heads, n_kv_heads, n);
+    if (n > 0 && (!k || !v)) return fail(nullptr, MP_EINVAL, "%s: null k/v with n > 0", who);
+    if (n_q_heads / n_kv_heads > 8) return fail(nullptr, MP_EINVAL, "%s: group size %d > 8 is not supported", who, n_q_heads / n_kv_heads);
+    return MP_OK;
+}
+
+// Partial results of mp_dense_attention_static: one array per GPU, part of the library's image on
+// that GPU for the life of the process.  Host code never uses the name `scratch` as an address:
+// scratch_on_device() asks the runtime for the array's address on the current device once and
+// hands out that pointer.
+constexpr size_t kStaticScratchBytes = MP_DENSE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t scratch_on_device(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+}  // namespace
+
+namespace mp {
+// The library's set-up call (mp_create) resolves the array on its device, so that a later
+// mp_dense_attention_static on that device makes no runtime query at all.
+hipError_t resolve_static_scratch()
+{
+    void* p = nullptr;
+    return scratch_on_device(&p);
+}
+}  // namespace mp
+
+extern "C" {
+
+mp_status mp_dense_attention(const void* q, const void* k, const void* v, int32_t batch, int32_t n_q_heads,
+                             int32_t n_kv_heads, int32_t n, float softmax_scale, void* out, float* lse, void* workspace,
+                             size_t workspace_bytes, void* stream)
+{
+    if (!workspace) return fail(nullptr, MP_EINVAL, "mp_dense_attention: null pointer");
+    const mp_status st = dense_args_ok("mp_dense_attention", q, k, v, batch, n_q_heads, n_kv_heads, n, out);
+    if (st != MP_OK) return st;
+    const size_t need = mp_dense_workspace_bytes(batch, n_q_heads, n_kv_heads, n);
+    if (workspace_bytes < need) return fail(nullptr, MP_EINVAL, "mp_dense_attention: workspace %zu < %zu bytes", workspace_bytes, need);
+    return dense_impl("mp_dense_attention", q, k, v, batch, n_q_heads, n_kv_heads, n, softmax_scale, out, lse,
+                      (float*)workspace, (hipStream_t)stream);
+}
+
+size_t mp_dense_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+mp_status mp_dense_attention_static(const void* q, const void* k, const void* v, int32_t batch, int32_t n_q_heads,
+                                    int32_t n_kv_heads, int32_t n, float softmax_scale, void* out, float* lse, void* stream)
+{
+    const mp_status st = dense_args_ok("mp_dense_attention_static", q, k, v, batch, n_q_heads, n_kv_heads, n, out);
+    if (st != MP_OK) return st;
+    const size_t need = mp_dense_workspace_bytes(batch, n_q_heads, n_kv_heads, n);
+    if (need > kStaticScratchBytes)
+        return fail(nullptr, MP_ECAPACITY, "mp_dense_attention_static: this shape needs %zu bytes of partial results, the built-in "
+                    "scratch array holds %zu (use mp_dense_attention with a workspace)", need, kStaticScratchBytes);
+    void* base = nullptr;
+    const hipError_t e = scratch_on_device(&base);
+    if (e != hipSuccess) return fail(nullptr, MP_EHIP, "mp_dense_attention_static: hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    // every chunk of every unit writes its partial (an empty chunk writes an empty one) before the
+    // merge reads it, so nothing of the previous call's contents is ever read: no clearing needed
+    return dense_impl("mp_dense_attention_static", q, k, v, batch, n_q_heads, n_kv_heads, n, softmax_scale, out, lse,
+                      (float*)base, (hipStream_t)stream);
 }
 
 }  // extern "C"
