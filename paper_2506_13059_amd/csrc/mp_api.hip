@@ -185,6 +185,7 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
 
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) e = mp::resolve_static_scratch();
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&ctx->n_cus, hipDeviceAttributeMultiprocessorCount, ctx->device);
     const size_t U = ctx->U, N = ctx->Ncap, F = ctx->Fcap, Cc = std::max(ctx->Ccap, 1), T = ctx->tab_rows, D = kHeadDimHost;
 #define A(ptr, count) if (e == hipSuccess) e = dev_alloc(ctx, &ctx->ptr, (count))
     A(Kp, U * N * D); A(Vp, U * N * D); A(perm, U * N); A(fot, U * N);
@@ -199,7 +200,7 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     ctx->Lcap = (int32_t)std::max(F, Cc);
     const size_t Lc = ctx->Lcap;
     A(lg, U * G * Lc); A(sc_keys, U * Lc); A(sc_wts, U * Lc); A(sc_ids, U * Lc); A(sc_aux, U * Lc); A(sc_aux2, U * Lc);
-    A(sc_flags, U * Lc); A(r_c, U * Cc); A(r_f, U * F); A(flag_c, U * Cc); A(flag_f, U * F);
+    A(sc_flags, U * Lc); A(key_c, U * Cc); A(key_f, U * F); A(key_mode, U * 2); A(flag_c, U * Cc); A(flag_f, U * F);
     A(cand, U * F); A(n_cand, U); A(unprom_lse, U * G); A(rows, U * N); A(n_rows, U);
     A(mp_rows, U * T); A(mp_scores, U * T * G); A(n_mp, U); A(counters, U * 4);
     A(partials, U * (size_t)ctx->Pcap * G * kPartStride);
@@ -368,8 +369,8 @@ static mp_status decode_impl(mp_ctx* ctx, const void* q, const void* q_lookup, c
     sp.cstart = ctx->cstart; sp.cstart_stride = ctx->Ccap + 1; sp.fstart = ctx->fstart; sp.fstart_stride = ctx->Fcap + 1;
     sp.lg = ctx->lg; sp.lg_stride = ctx->Lcap; sp.g_keys = ctx->sc_keys; sp.g_wts = ctx->sc_wts; sp.g_ids = ctx->sc_ids;
     sp.g_aux = ctx->sc_aux; sp.g_aux2 = ctx->sc_aux2; sp.g_flags = ctx->sc_flags; sp.g_stride = ctx->Lcap;
-    sp.r_c = ctx->r_c; sp.flag_c = ctx->flag_c; sp.c_stride = std::max(ctx->Ccap, 1);
-    sp.r_f = ctx->r_f; sp.flag_f = ctx->flag_f; sp.f_stride = ctx->Fcap; sp.cand = ctx->cand; sp.n_cand = ctx->n_cand;
+    sp.key_c = ctx->key_c; sp.flag_c = ctx->flag_c; sp.c_stride = std::max(ctx->Ccap, 1);
+    sp.key_f = ctx->key_f; sp.key_mode = ctx->key_mode; sp.flag_f = ctx->flag_f; sp.f_stride = ctx->Fcap; sp.cand = ctx->cand; sp.n_cand = ctx->n_cand;
     sp.rows = ctx->rows; sp.rows_stride = ctx->Ncap; sp.n_rows = ctx->n_rows;
     sp.mp_rows = ctx->mp_rows; sp.mp_scores = ctx->mp_scores; sp.mp_stride = ctx->tab_rows; sp.n_mp = ctx->n_mp;
     sp.use_mp = use_mp; sp.counters = ctx->counters; sp.n_tail = n_tail;
@@ -381,7 +382,7 @@ static mp_status decode_impl(mp_ctx* ctx, const void* q, const void* q_lookup, c
     }
     if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[0], s));
     if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[1], s));
-    MP_HIP(ctx, launch_score_select(sp, s));
+    MP_HIP(ctx, launch_score_select(sp, ctx->n_cus, s));
     if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[2], s));
 
     ValuePassParams vp{};
@@ -627,10 +628,11 @@ mp_status mp_get_selection(mp_ctx* ctx, uint8_t* fine_selected, uint8_t* coarse_
     const bool two = ctx->cfg.levels == 2;
     if (fine_selected || r_fine)
         MP_HIP(ctx, launch_scatter_selection(two ? ctx->cand : nullptr, ctx->Fcap, two ? ctx->n_cand : nullptr, ctx->n_fine,
-                                             ctx->flag_f, ctx->r_f, ctx->Fcap, ctx->n_fine, ctx->U, fine_selected, r_fine, s));
+                                             ctx->flag_f, ctx->key_f, ctx->key_mode, 1, ctx->G, ctx->Fcap, ctx->n_fine, ctx->U,
+                                             fine_selected, r_fine, s));
     if (two && (coarse_promising || r_coarse))
-        MP_HIP(ctx, launch_scatter_selection(nullptr, 0, nullptr, ctx->n_coarse, ctx->flag_c, ctx->r_c, std::max(ctx->Ccap, 1), ctx->n_coarse,
-                                             ctx->U, coarse_promising, r_coarse, s));
+        MP_HIP(ctx, launch_scatter_selection(nullptr, 0, nullptr, ctx->n_coarse, ctx->flag_c, ctx->key_c, ctx->key_mode, 0, ctx->G,
+                                             std::max(ctx->Ccap, 1), ctx->n_coarse, ctx->U, coarse_promising, r_coarse, s));
     return MP_OK;
 }
 

@@ -54,6 +54,7 @@ struct mp_ctx {
     mp_config cfg{};
     std::string err;
     int device = 0;
+    int n_cus = 0;                 // compute units of that device
     int U = 0, G = 0;
     float scale = 0.f;
     double scale_d = 0.0;          // softmax scale in double (0 in cfg => exactly 1/sqrt(128) in fp64)
@@ -106,8 +107,9 @@ struct mp_ctx {
     int32_t* sc_aux2 = nullptr;
     uint8_t* sc_flags = nullptr;
     int32_t Lcap = 0;
-    double* r_c = nullptr;         // [U, Ccap]
-    double* r_f = nullptr;         // [U, Fcap] by candidate position
+    unsigned long long* key_c = nullptr;   // [U, Ccap] keys the coarse clusters were ranked by in the last call
+    unsigned long long* key_f = nullptr;   // [U, Fcap] the same for the fine level, by candidate position
+    int32_t* key_mode = nullptr;   // [U, 2] what those keys are (see launch_scatter_selection)
     uint8_t* flag_c = nullptr;     // [U, Ccap] promising
     uint8_t* flag_f = nullptr;     // [U, Fcap] selected, by candidate position
     int32_t* cand = nullptr;       // [U, Fcap]

@@ -325,13 +325,16 @@ __global__ __launch_bounds__(256) void scatter_selection_kernel(const int32_t* _
                                                                 long long cand_stride,
                                                                 const int32_t* __restrict__ n_cand_dev,
                                                                 int n_cand_fixed, const uint8_t* __restrict__ flag,
-                                                                const double* __restrict__ r, long long pos_stride,
-                                                                int n_ids, uint8_t* __restrict__ sel_out,
-                                                                double* __restrict__ r_out)
+                                                                const unsigned long long* __restrict__ keys,
+                                                                const int32_t* __restrict__ key_mode, int level, int G,
+                                                                long long pos_stride, int n_ids,
+                                                                uint8_t* __restrict__ sel_out, double* __restrict__ r_out)
 {
     const int u = blockIdx.x;
     const int n = n_cand_dev ? n_cand_dev[u] : n_cand_fixed;
     const double nan = __longlong_as_double(0x7ff8000000000000ll);
+    const int mode = key_mode[2 * u + level];
+    const double logG = log((double)G);
     for (int i = threadIdx.x; i < n_ids; i += 256) {
         if (sel_out) sel_out[(long long)u * n_ids + i] = 0;
         if (r_out) r_out[(long long)u * n_ids + i] = nan;
@@ -340,19 +343,33 @@ __global__ __launch_bounds__(256) void scatter_selection_kernel(const int32_t* _
     for (int i = threadIdx.x; i < n; i += 256) {
         const int id = cand ? cand[u * cand_stride + i] : i;
         if (sel_out) sel_out[(long long)u * n_ids + id] = flag[u * pos_stride + i];
-        if (r_out) r_out[(long long)u * n_ids + id] = r[u * pos_stride + i];
+        if (r_out) {
+            const unsigned long long key = keys[u * pos_stride + i];
+            double r = nan;
+            if (key != ~0ull) {
+                if (mode == 1) {
+                    r = log(__longlong_as_double((long long)~key)) - logG;
+                } else {    // undo the order-preserving map of the rank key
+                    unsigned long long b = ~key;
+                    b = (b >> 63) ? (b & 0x7fffffffffffffffull) : ~b;
+                    r = __longlong_as_double((long long)b);
+                }
+            }
+            r_out[(long long)u * n_ids + id] = r;
+        }
     }
 }
 
 }  // namespace
 
 hipError_t launch_scatter_selection(const int32_t* cand, long long cand_stride, const int32_t* n_cand_dev,
-                                    int n_cand_fixed, const uint8_t* flag, const double* r, long long pos_stride,
-                                    int n_ids, int U, uint8_t* sel_out, double* r_out, hipStream_t s)
+                                    int n_cand_fixed, const uint8_t* flag, const unsigned long long* keys,
+                                    const int32_t* key_mode, int level, int G, long long pos_stride, int n_ids, int U,
+                                    uint8_t* sel_out, double* r_out, hipStream_t s)
 {
     if (n_ids <= 0) return hipSuccess;
     hipLaunchKernelGGL(scatter_selection_kernel, dim3(U), dim3(256), 0, s, cand, cand_stride, n_cand_dev,
-                       n_cand_fixed, flag, r, pos_stride, n_ids, sel_out, r_out);
+                       n_cand_fixed, flag, keys, key_mode, level, G, pos_stride, n_ids, sel_out, r_out);
     return hipGetLastError();
 }
 

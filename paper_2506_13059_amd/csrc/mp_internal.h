@@ -73,13 +73,15 @@ struct ScoreParams {
     int32_t* g_aux2;
     uint8_t* g_flags;
     long long g_stride;
-    // per-position views of the last call (for the getters)
-    double* r_c;                // [U, c_stride] coarse rank keys (NaN if N == 0)
+    // per-position views of the last call (for the getters): the key each entry was ranked by (all
+    // ones: took no part) and, per unit and level, what the keys are (key_mode, see launch_scatter_selection)
+    unsigned long long* key_c;  // [U, c_stride] coarse
     uint8_t* flag_c;            // [U, c_stride] promising
     long long c_stride;
-    double* r_f;                // [U, f_stride] fine rank keys by candidate position
+    unsigned long long* key_f;  // [U, f_stride] fine, by candidate position
     uint8_t* flag_f;            // [U, f_stride] selected, by candidate position
     long long f_stride;
+    int32_t* key_mode;          // [U, 2] coarse, fine
     int32_t* cand;              // [U, f_stride] candidate fine ids (two levels)
     int32_t* n_cand;            // [U]
     // outputs for the value pass
@@ -105,7 +107,8 @@ struct ScoreParams {
     int G, U;
 };
 
-hipError_t launch_score_select(const ScoreParams& p, hipStream_t stream);
+// n_compute_units: of the device the launch goes to (decides whether units get a second, shadow workgroup).
+hipError_t launch_score_select(const ScoreParams& p, int n_compute_units, hipStream_t stream);
 size_t score_smem_bytes(int G, int cap);
 
 // ------------------------------------------------------------------------------------------------
@@ -154,8 +157,12 @@ hipError_t launch_offset_lists(const int32_t* start, long long start_stride, int
 hipError_t launch_ids_from_lists(const int32_t* list, long long list_stride, const int32_t* start,
                                  long long start_stride, int k, int U, int32_t* ids, long long ids_stride,
                                  hipStream_t s);
+// Views of the last scoring launch, by cluster id.  keys [U, pos_stride] by position; key_mode[2*u + level]
+// says what they are: 0 = order-preserving image of the rank key r = log mean_h e^{l - LSE_h}; 1 = complement
+// of the bit pattern of sum_h e^{l - LSE_h} (then r = log(sum) - log G).  r_out receives r (NaN: took no part).
 hipError_t launch_scatter_selection(const int32_t* cand, long long cand_stride, const int32_t* n_cand_dev,
-                                    int n_cand_fixed, const uint8_t* flag, const double* r, long long pos_stride,
-                                    int n_ids, int U, uint8_t* sel_out, double* r_out, hipStream_t s);
+                                    int n_cand_fixed, const uint8_t* flag, const unsigned long long* keys,
+                                    const int32_t* key_mode, int level, int G, long long pos_stride, int n_ids, int U,
+                                    uint8_t* sel_out, double* r_out, hipStream_t s);
 
 }  // namespace mp

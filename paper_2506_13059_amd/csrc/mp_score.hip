@@ -1,22 +1,40 @@
 // Centroid scoring and budgeted cluster selection for gfx950 (Eq. 1, Sec. 3.1; two levels: Sec. 3.4).
 //
 // One launch per decode step, one workgroup of 512 threads per unit; the coarse level and the fine
-// level run back to back in the same workgroup.
+// level run back to back in the same workgroup.  The launch moves a few per cent of the step's
+// bytes and nothing can overlap it (the value pass needs its result), so what counts is the length
+// of the chain a wave executes: per level one trip to memory for the centroid rows, all requested at
+// once, then a handful of short phases between workgroup barriers.  Two measured facts shape it:
+//   * one compute unit pulls only about 20 GB/s out of a cold HBM (the chip's bandwidth is the sum
+//     over its 256 units), so the 64-128 KiB of centroid rows per level are the largest single cost;
+//   * with one workgroup per compute unit every instruction of the chain costs 8-9 cycles, so the
+//     chain is kept short: the products run on the fp64 matrix pipe, every thread then owns ONE entry
+//     (no loops at the benchmark's sizes), one exponential per (entry, head), no logarithm, and what
+//     is the same for the whole workgroup (one value per head) is worked out once per wave, the heads
+//     side by side in the lanes.  (More waves would shorten the per-entry part and lengthen that one:
+//     512 threads is where the two balance for levels of 256-512 entries.)
 //
 // Logits l[h,i] = scale * q_h . Kc_i are accumulated in fp64 (products of bf16 numbers are exact,
 // so the sum carries ~1e-16 relative error and the ranking agrees with an fp64 reference except on
-// ties far below any tolerance).  A group of 8 lanes (16 for more than 4 heads) shares one centroid
-// row with coalesced 16-byte loads; each lane keeps its slice of every query head in registers as
-// doubles and partial sums are combined with DPP.  The rank key is log(mean_h exp(l[h,i] - LSE_h)),
-// the logarithm of Eq. 1 averaged over the query heads of the group.  Selection = "take clusters in
-// descending key order (ties: lower id) while the running token count stays within the budget, stop
-// at the first that does not fit"; token counts are positive, so this is a threshold on (key, id),
-// found by a weighted most-significant-digit radix select instead of a sort.
+// ties far below any tolerance) with v_mfma_f64_4x4x4 (four independent 4x4x4 blocks per
+// instruction: 16 entries x 4 heads per wave and round).  The score of an entry is
+// sum_h e^{l[h,i] - LSE_h}, G times Eq. 1 averaged over the query heads of the group; it is compared
+// in the linear domain (same order as its logarithm, the rank key the getters report).  Selection =
+// "take clusters in descending score order (ties: lower id) while the running token count stays
+// within the budget, stop at the first that does not fit"; token counts are positive, so this is a
+// threshold on (score, id): one 256-bucket histogram over the leading bits of the score and a direct
+// comparison among the entries of the boundary bucket (a most-significant-digit radix search takes
+// over where that bucket is crowded).
 //
 // Per-entry working arrays (logits, keys, counts, ids, row starts, flags) live in LDS when a level
-// has at most lds_cap entries and in a global scratch area otherwise.  The two cases are separate
-// template instantiations, so that the LDS case uses LDS instructions and LDS-only barriers (the
-// kernel's global stores are never read back by the same workgroup in that case).
+// has at most lds_cap entries and in a global scratch area otherwise (separate template
+// instantiations: LDS instructions and LDS-only barriers in the first case).
+//
+// Shadow workgroups: with spare compute units (2 U <= units of the chip, U a multiple of eight: the
+// blocks of a launch go round the eight L2 slices), a second workgroup per unit, placed on the same
+// L2 slice, runs the same code without storing anything and asks for the centroid rows in the
+// opposite order, so that each of the two finds part of its rows already in the shared L2.  It never
+// communicates with the first.
 //
 // Outputs for the value pass: the flat list of stored rows of the selected clusters' keys, and one
 // "centroid term" entry (value-centroid row + ready-made logits) per cluster that stays behind at
@@ -32,29 +50,35 @@ namespace {
 
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
+constexpr int kInFlight = 4;                          // rounds (16 entries per wave) whose centroid rows are requested ahead
+constexpr int kHistBits = 8;                          // first (and normally only) digit of the selection
+constexpr int kHistBuckets = 1 << kHistBits;
+constexpr int kListCap = 64;                          // boundary-bucket entries ordered by direct comparison
+static_assert(kThreads == 512, "a thread carries one element per head group of the 512-element query operand");
+static_assert(kWaves <= 16, "the (head, wave) lane layout below uses rows of 16 lanes");
+constexpr int kKeep = 2;                              // chunks of kThreads entries whose e^{l - M} stay in registers
 
+// Order-preserving 64-bit image of a rank key r, ascending = descending r.
 __device__ __forceinline__ uint64_t descending_key(double r)
 {
     uint64_t b = (uint64_t)__double_as_longlong(r);
     b = (b >> 63) ? ~b : (b | 0x8000000000000000ull);   // ascending in r
     return ~b;                                           // ascending key = descending r
 }
-__device__ __forceinline__ double key_to_rank(uint64_t key)
-{
-    uint64_t b = ~key;
-    b = (b >> 63) ? (b & 0x7fffffffffffffffull) : ~b;
-    return __longlong_as_double((long long)b);
-}
 
 struct Scratch {
-    float gmax[kWaves * 8];           // per wave, per head: largest logit of an entry that takes part
-    double red_s[kWaves * 8];         // per wave, per head: sum of N e^{l - shift}
-    double extra[8];                  // log-sum of the unpromising coarse clusters' N e^l, per head
     unsigned long long hist[3][256];  // radix digit histograms: entry count << 40 | token count
     unsigned long long hkey[3][256];  // a key that fell into each bucket (THE key where the bucket holds one entry)
     unsigned long long rk_min[kWaves], rk_max[kWaves];  // per wave: smallest / largest key that takes part
     uint32_t rk_wt[kWaves], rk_cn[kWaves];              // ... their token total and their number
     uint32_t wsum[2][kWaves][2];      // per-wave totals of the two-value scan, double-buffered
+    double wm[kWaves][8];             // per wave and head: largest logit of an entry that takes part
+    double ws[kWaves][8];             // per wave and head: sum of N e^{l - M_h}
+    double bm[8], bs[8];              // what stayed behind at the coarse level, per head: shift and sum of N e^{l - shift}
+    // extremes of the keys, token total, "some score too small" flag and boundary-list length of the
+    // level in progress, maintained with LDS atomics
+    unsigned long long key_min, key_max;
+    uint32_t key_total, key_tiny, bl_count;
 };
 
 struct Arrays {
@@ -62,7 +86,7 @@ struct Arrays {
     long long lg_stride;
     uint64_t* keys;
     uint32_t* wts;
-    int32_t* ids;
+    int32_t* ids;          // candidate fine ids (fine level of two)
     int32_t* aux;          // fine: first stored row; coarse: first child
     int32_t* aux2;         // coarse: end of children; fine: offset of the cluster's rows in the row list
     uint8_t* flags;
@@ -83,63 +107,10 @@ __device__ __forceinline__ void phase_sync()
     }
 }
 
-// What a level hands from its log-sum-exp to later sums over subsets of its entries: the shift per
-// head (the largest logit of an entry that takes part, rounded to float) and, for levels of up to
-// 2 * kThreads entries, this thread's terms N_i e^{l[h,i] - shift_h} of entries tid and tid + kThreads.
-template <int G>
-struct LevelTerms {
-    double shift[G];
-    double e[2][G];
-    bool kept;
-};
-
-// lse[h] = shift_h + log( sum over the workgroup of sm[h]  [+ e^{extra_h - shift_h}] ) for every head,
-// where sm[h] is this thread's sum of terms already divided by e^{shift_h}.  One barrier: per-wave sums
-// via DPP, then every wave adds the eight of them itself (one row of 16 lanes per head), so the
-// result needs no second barrier.  S.red_s is reused by the next call: callers have a barrier
-// between two calls.
-template <int G, bool kLds>
-__device__ __forceinline__ void combine_lse(Scratch& S, const double (&shift)[G], const double (&sm)[G], bool with_extra,
-                                            double (&lse)[G])
-{
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-        const double t = wave_sum_f64(sm[h]);
-        if (lane == 0) S.red_s[wave * 8 + h] = t;
-    }
-    phase_sync<kLds>();
-#pragma unroll
-    for (int h0 = 0; h0 < G; h0 += 4) {
-        const int h = h0 + (lane >> 4), w = lane & 15;
-        const bool live = h < G && w < kWaves;
-        double t = row_sum_f64(live ? S.red_s[w * 8 + h] : 0.0);
-        double sh = -INFINITY;
-#pragma unroll
-        for (int hh = 0; hh < 4; ++hh)
-            if (h0 + hh < G && (lane >> 4) == hh) sh = shift[h0 + hh];
-        double r;
-        if (with_extra && h < G) {
-            const double ex = S.extra[h];
-            const double M = fmax(sh, ex);
-            if (M == -INFINITY) {
-                r = -INFINITY;
-            } else {
-                const double a = (t > 0.0) ? t * exp_shifted(sh - M) : 0.0;
-                r = M + log(a + exp_shifted(ex - M));
-            }
-        } else {
-            r = (t > 0.0) ? sh + log(t) : -INFINITY;
-        }
-#pragma unroll
-        for (int hh = 0; hh < 4; ++hh)
-            if (h0 + hh < G) lse[h0 + hh] = readlane_f64(r, 16 * hh);
-    }
-}
-
 // Exclusive prefix sums of two values per thread over one chunk of kThreads threads, with running
 // totals carried in registers (every thread adds the same chunk totals, so they stay uniform).
-// One barrier per call: the per-wave totals are double-buffered by the parity of `calls`.
+// One barrier per call: the per-wave totals are double-buffered by the parity of `calls`; after the
+// barrier the first 16 lanes of every wave scan them.
 struct ScanState {
     uint32_t carry_a = 0, carry_b = 0, calls = 0;
 };
@@ -156,15 +127,13 @@ __device__ __forceinline__ void chunk_excl_scan2(uint32_t a, uint32_t b, Scratch
         s.wsum[par][wave][1] = ib;
     }
     phase_sync<kLds>();
-    uint32_t off_a = 0, off_b = 0, tot_a = 0, tot_b = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        const uint32_t wa = s.wsum[par][w][0], wb = s.wsum[par][w][1];
-        off_a += (w < wave) ? wa : 0u;
-        off_b += (w < wave) ? wb : 0u;
-        tot_a += wa;
-        tot_b += wb;
-    }
+    const uint32_t wa = lane < kWaves ? s.wsum[par][lane][0] : 0u, wb = lane < kWaves ? s.wsum[par][lane][1] : 0u;
+    const uint32_t sa = wave_incl_scan_u32(wa), sb = wave_incl_scan_u32(wb);
+    const int w = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t off_a = (uint32_t)__builtin_amdgcn_readlane((int)(sa - wa), w);
+    const uint32_t off_b = (uint32_t)__builtin_amdgcn_readlane((int)(sb - wb), w);
+    const uint32_t tot_a = (uint32_t)__builtin_amdgcn_readlane((int)sa, kWaves - 1);
+    const uint32_t tot_b = (uint32_t)__builtin_amdgcn_readlane((int)sb, kWaves - 1);
     ex_a = st.carry_a + off_a + ia - a;
     ex_b = st.carry_b + off_b + ib - b;
     st.carry_a += tot_a;
@@ -323,308 +292,581 @@ __device__ __forceinline__ bool radix_select(const uint64_t* keys, const uint32_
     return true;
 }
 
-template <int kLanes>
-__device__ __forceinline__ double group_sum_f64(double v)
+// ------------------------------------------------------------------------------------------------
+// Dynamic LDS behind the Scratch block: the query in matrix-operand order, the selection's
+// histogram and boundary list, then the per-entry working arrays (cap = p.lds_cap entries each).
+// ------------------------------------------------------------------------------------------------
+struct Lds {
+    double* qB;                 // [GH][32][16]: slice s, dim group k, head j (see query_operand_element)
+    unsigned long long* hist;   // [kHistBuckets] entry count << 40 | token count
+    unsigned long long* blist;  // [kListCap][2]: key, position << 32 | token count
+    Arrays A;
+};
+
+__host__ __device__ constexpr size_t align16(size_t x) { return (x + 15) & ~size_t(15); }
+
+template <int G>
+__device__ __forceinline__ Lds carve_lds(unsigned char* lds, int cap)
 {
-    v += dpp_f64<kDppXor1>(v);
-    v += dpp_f64<kDppXor2>(v);
-    v += dpp_f64<kDppHalfMirror>(v);
-    if constexpr (kLanes == 16) v += dpp_f64<kDppMirror>(v);
+    constexpr int GH = (G + 3) / 4;
+    Lds L;
+    L.qB = reinterpret_cast<double*>(lds);
+    L.hist = reinterpret_cast<unsigned long long*>(L.qB + GH * 512);
+    L.blist = L.hist + kHistBuckets;
+    L.A.lg = reinterpret_cast<double*>(L.blist + 2 * kListCap);
+    L.A.lg_stride = cap;
+    L.A.keys = reinterpret_cast<uint64_t*>(L.A.lg + (size_t)G * cap);
+    L.A.wts = reinterpret_cast<uint32_t*>(L.A.keys + cap);
+    L.A.ids = reinterpret_cast<int32_t*>(L.A.wts + cap);
+    L.A.aux = L.A.ids + cap;
+    L.A.aux2 = L.A.aux + cap;
+    L.A.flags = reinterpret_cast<uint8_t*>(L.A.aux2 + cap);
+    return L;
+}
+
+template <int G>
+__device__ __forceinline__ Arrays global_arrays(const ScoreParams& p, int u)
+{
+    Arrays A;
+    A.lg = p.lg + (long long)u * G * p.lg_stride;
+    A.lg_stride = p.lg_stride;
+    A.keys = reinterpret_cast<uint64_t*>(p.g_keys) + (long long)u * p.g_stride;
+    A.wts = p.g_wts + (long long)u * p.g_stride;
+    A.ids = p.cand + (long long)u * p.f_stride;       // the candidate list itself
+    A.aux = p.g_aux + (long long)u * p.g_stride;
+    A.aux2 = p.g_aux2 + (long long)u * p.g_stride;
+    A.flags = p.g_flags + (long long)u * p.g_stride;
+    return A;
+}
+
+// ------------------------------------------------------------------------------------------------
+// The matrix product.
+//
+// v_mfma_f64_4x4x4 computes four independent blocks D_b[i][j] += sum_k A_b[i][k] * B_b[k][j] with
+// (measured lane map) A_b[i][k] in lane 16k + 4b + i, B_b[k][j] in lane 16k + 4b + j and D_b[i][j]
+// in lane 16i + 4b + j.  Here i = entry inside a block, j = head, k = one of four groups of 32
+// dimensions: lane (k, e = 4b + i) holds, for entry e of the wave's 16, the dimensions
+// {32c + 8k + r : c < 4, r < 8} (four 16-byte pieces of the row, so that one load instruction of the
+// wave covers 64 contiguous bytes of 16 rows), and 32 instructions, one per (c, r), add up the whole
+// product.  The B operand (the query, the same for every block) is read from LDS: element x of qB,
+// x = (hg * 32 + 8c + r) * 16 + 4k + j, is dimension 32c + 8k + r of head 4 hg + j.
+// After the product lane (i, b, j) owns the logit of entry 4b + i and head j.
+// ------------------------------------------------------------------------------------------------
+template <int G>
+__device__ __forceinline__ double query_operand_element(const ScoreParams& p, int u, int x)
+{
+    const int hg = x >> 9, s = (x >> 4) & 31, k = (x >> 2) & 3, j = x & 3;
+    const int h = 4 * hg + j, d = 32 * (s >> 3) + 8 * k + (s & 7);
+    return h < G ? (double)bf16_to_f32(p.q[((long long)u * G + h) * kHeadDim + d]) : 0.0;
+}
+
+__device__ __forceinline__ double shfl_xor_f64(double v, int m)
+{
+    const long long b = __double_as_longlong(v);
+    const int lo = __shfl_xor((int)(b & 0xffffffffll), m, 64), hi = __shfl_xor((int)(b >> 32), m, 64);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+constexpr int kDppRowRor4 = 0x124, kDppRowRor8 = 0x128;
+// Largest value over the 16 lanes of a wave that own the same head (lanes equal modulo 4).
+__device__ __forceinline__ double max_same_head(double x)
+{
+    x = fmax(x, dpp_f64<kDppRowRor4>(x));
+    x = fmax(x, dpp_f64<kDppRowRor8>(x));
+    x = fmax(x, shfl_xor_f64(x, 16));
+    x = fmax(x, shfl_xor_f64(x, 32));
+    return x;
+}
+__device__ __forceinline__ double row_min_f64(double v)
+{
+    v = fmin(v, dpp_f64<kDppXor1>(v));
+    v = fmin(v, dpp_f64<kDppXor2>(v));
+    v = fmin(v, dpp_f64<kDppHalfMirror>(v));
+    v = fmin(v, dpp_f64<kDppMirror>(v));
     return v;
 }
 
-// One level: logits, Eq. 1 normaliser, rank keys, budgeted selection.  On return A.flags holds the
-// selected / promising mask, A.wts the member counts (0 = takes no part), A.lg the logits, A.keys
-// the rank keys.  Entry i stands for cluster id (use_ids ? A.ids[i] : i).
-template <int G, bool kLds, int LPE>
-__device__ __forceinline__ void score_level(const ScoreParams& p, const Arrays& A, Scratch& S, int u, int n,
-                                            bool use_ids, bool coarse, const double (&qreg)[G][128 / LPE],
-                                            long long budget, bool with_extra, LevelTerms<G>& T)
+// One value per head from a [kWaves][8] table of per-wave values: lane 16 hh + w of every wave takes
+// the value of (wave w, head 4 hg + hh), the row is combined, `post` (head group, head, combined value) is applied
+// -- once per head group, the heads side by side in the lanes -- and every lane receives the G results.
+template <int G, typename RowOp, typename Post>
+__device__ __forceinline__ void combine_waves(const double (&tab)[kWaves][8], double neutral, RowOp row_op, Post post,
+                                              double (&out)[G])
 {
-    constexpr int DPL = 128 / LPE;           // dims per lane: 16 or 8
-    constexpr int EPI = kThreads / LPE;      // entries per pass of the workgroup
-    const int tid = threadIdx.x;
-    const int row_off = coarse ? p.fcap : 0;
-    const int32_t* Nu = p.N + (long long)u * p.tab_rows + row_off;
-    const uint16_t* Kcu = p.Kc + ((long long)u * p.tab_rows + row_off) * kHeadDim;
-    const int32_t* st = coarse ? p.cstart + (long long)u * p.cstart_stride : p.fstart + (long long)u * p.fstart_stride;
-
-    // member counts and row starts of the first 2*kThreads entries: loads issued now, stored after the logits
-    int pre_w[2] = {0, 0}, pre_a[2] = {0, 0}, pre_b[2] = {0, 0};
+    constexpr int GH = (G + 3) / 4;
+    const int lane = threadIdx.x & 63;
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        const int i = tid + k * kThreads;
-        if (i < n) {
-            const int id = use_ids ? A.ids[i] : i;
-            pre_w[k] = Nu[id];
-            pre_a[k] = st[id];
-            if (coarse) pre_b[k] = st[id + 1];
-        }
+    for (int hg = 0; hg < GH; ++hg) {
+        const int h = 4 * hg + (lane >> 4), w = lane & 15;
+        const int hc = h < G ? h : G - 1;
+        const double v = post(hg, hc, row_op((h < G && w < kWaves) ? tab[w][h] : neutral));
+#pragma unroll
+        for (int hh = 0; hh < 4; ++hh)
+            if (4 * hg + hh < G) out[4 * hg + hh] = readlane_f64(v, 16 * hh);
     }
-    // ---- logits: LPE lanes per entry, DPL dims per lane; two entries per lane and pass, the rows of
-    // the next pass are requested before the current ones are used ----
-    {
-        const int sub = tid % LPE, grp = tid / LPE;
-        uint4 nxt[2][DPL / 8];
-        int nxt_w[2];
-        float mxf[G];        // largest logit, per head, of the entries with members that this lane finishes
-#pragma unroll
-        for (int h = 0; h < G; ++h) mxf[h] = -INFINITY;
-        auto request = [&](int i0) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int i = i0 + j * EPI + grp;
-#pragma unroll
-                for (int v = 0; v < DPL / 8; ++v) nxt[j][v] = make_uint4(0, 0, 0, 0);
-                nxt_w[j] = 0;
-                if (i < n) {
-                    const int id = use_ids ? A.ids[i] : i;
-                    const uint4* kp = reinterpret_cast<const uint4*>(Kcu + (long long)id * kHeadDim + DPL * sub);
-#pragma unroll
-                    for (int v = 0; v < DPL / 8; ++v) nxt[j][v] = kp[v];
-                    nxt_w[j] = Nu[id];
-                }
-            }
-        };
-        request(0);
-        for (int i0 = 0; i0 < n; i0 += 2 * EPI) {
-            uint4 kv[2][DPL / 8];
-            int kw[2];
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-#pragma unroll
-                for (int v = 0; v < DPL / 8; ++v) kv[j][v] = nxt[j][v];
-                kw[j] = nxt_w[j];
-            }
-            if (i0 + 2 * EPI < n) request(i0 + 2 * EPI);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int i = i0 + j * EPI + grp;
-                double kd[DPL];
-#pragma unroll
-                for (int v = 0; v < DPL / 8; ++v) {
-                    const uint32_t w[4] = {kv[j][v].x, kv[j][v].y, kv[j][v].z, kv[j][v].w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        kd[8 * v + 2 * e] = (double)bf16lo_to_f32(w[e]);
-                        kd[8 * v + 2 * e + 1] = (double)bf16hi_to_f32(w[e]);
-                    }
-                }
-#pragma unroll
-                for (int h = 0; h < G; ++h) {
-                    double a = 0.0;
-#pragma unroll
-                    for (int e = 0; e < DPL; ++e) a = fma(qreg[h][e], kd[e], a);
-                    a = group_sum_f64<LPE>(a) * p.scale;
-                    if (sub == 0 && i < n) {
-                        A.lg[h * A.lg_stride + i] = a;
-                        if (kw[j] > 0) mxf[h] = fmaxf(mxf[h], (float)a);
-                    }
-                }
-            }
-        }
-        const int lane = tid & 63, wave = tid >> 6;
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            const float m = wave_max_f32(mxf[h]);
-            if (lane == 0) S.gmax[wave * 8 + h] = m;
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        const int i = tid + k * kThreads;
-        if (i < n) {
-            A.wts[i] = (uint32_t)(pre_w[k] > 0 ? pre_w[k] : 0);
-            A.aux[i] = pre_a[k];
-            if (coarse) A.aux2[i] = pre_b[k];
-        }
-    }
-    for (int i = tid + 2 * kThreads; i < n; i += kThreads) {
-        const int id = use_ids ? A.ids[i] : i;
-        const int w = Nu[id];
-        A.wts[i] = (uint32_t)(w > 0 ? w : 0);
-        A.aux[i] = st[id];
-        if (coarse) A.aux2[i] = st[id + 1];
-    }
-    phase_sync<kLds>();
-
-    // ---- per-head normaliser of Eq. 1: LSE_h = log( sum_i N_i e^{l[h,i]} + e^{extra_h} ) ----
-    // shift: the largest logit of the level (the waves left theirs in S.gmax before the barrier above)
-    double lse[G];
-    {
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            float m = S.gmax[h];
-#pragma unroll
-            for (int w = 1; w < kWaves; ++w) m = fmaxf(m, S.gmax[w * 8 + h]);
-            T.shift[h] = (double)m;
-        }
-        T.kept = (G <= 6) && n <= 2 * kThreads;     // (larger groups have no registers to spare for the kept terms)
-        double sm[G];
-#pragma unroll
-        for (int h = 0; h < G; ++h) sm[h] = T.e[0][h] = T.e[1][h] = 0.0;
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int i = tid + k * kThreads;
-            if (i < n && A.wts[i] != 0) {
-                const double w = (double)A.wts[i];
-#pragma unroll
-                for (int h = 0; h < G; ++h) {
-                    const double e = w * exp_shifted(A.lg[h * A.lg_stride + i] - T.shift[h]);
-                    if constexpr (G <= 6) T.e[k][h] = e;
-                    sm[h] += e;
-                }
-            }
-        }
-        for (int i = tid + 2 * kThreads; i < n; i += kThreads)
-            if (A.wts[i] != 0) {
-                const double w = (double)A.wts[i];
-#pragma unroll
-                for (int h = 0; h < G; ++h) sm[h] += w * exp_shifted(A.lg[h * A.lg_stride + i] - T.shift[h]);
-            }
-        combine_lse<G, kLds>(S, T.shift, sm, with_extra, lse);
-    }
-
-    // ---- rank keys ----
-    const double logG = log((double)G);
-    for (int i = tid; i < n; i += kThreads) {
-        uint64_t key = ~0ull;
-        if (A.wts[i]) {
-            double t[G], tm = -INFINITY;
-#pragma unroll
-            for (int h = 0; h < G; ++h) {
-                t[h] = A.lg[h * A.lg_stride + i] - lse[h];
-                tm = fmax(tm, t[h]);
-            }
-            double r = tm - logG;
-            if constexpr (G > 1) {
-                double ssum = 0.0;
-#pragma unroll
-                for (int h = 0; h < G; ++h) ssum += exp_shifted(t[h] - tm);
-                r += log(ssum);
-            }
-            key = descending_key(r);
-        }
-        A.keys[i] = key;
-    }
-    // (the barrier that publishes the keys is the first one inside radix_select)
-
-    // ---- budgeted selection ----
-    uint64_t kstar = 0, acc = 0;
-    uint32_t ties = 0;
-    const bool bounded = radix_select<kLds>(A.keys, A.wts, n, budget, S, kstar, acc, ties);
-    for (int i = tid; i < n; i += kThreads) {
-        uint8_t f = 0;
-        if (A.wts[i]) {
-            if (!bounded) f = 1;
-            else {
-                const uint64_t k = A.keys[i];
-                if (k < kstar) f = 1;
-                else if (k == kstar && ties > 1) {
-                    // exactly equal keys: lower position first, keep while the running count still fits
-                    uint64_t run = acc;
-                    for (int j = 0; j <= i; ++j)
-                        if (A.wts[j] && A.keys[j] == kstar) run += A.wts[j];
-                    f = ((long long)run <= budget) ? 1 : 0;
-                }
-            }
-        }
-        A.flags[i] = f;
-    }
-    phase_sync<kLds>();
 }
 
-// Per-position views for the getters: rank key (NaN where the entry took no part) and flag.
-__device__ __forceinline__ void write_views(const Arrays& A, int n, double* r_out, uint8_t* flag_out)
+// The value itself, but the compiler can neither move its evaluation out of the branch it stands in nor
+// evaluate it ahead of time (used to keep rarely needed logarithms out of the common path).
+__device__ __forceinline__ double not_hoisted(double v)
 {
-    for (int i = threadIdx.x; i < n; i += kThreads) {
-        r_out[i] = A.wts[i] ? key_to_rank(A.keys[i]) : __longlong_as_double(0x7ff8000000000000ll);
-        flag_out[i] = A.flags[i];
-    }
+    asm volatile("" : "+v"(v));
+    return v;
 }
 
 // One centroid-term entry (Eq. 2): the row of the value centroid and log2( N_i e^{l[h,i]} ) per head.
 template <int G>
 __device__ __forceinline__ void emit_term(const ScoreParams& p, const Arrays& A, int u, int i, int row, uint32_t slot)
 {
-    const double kLog2e = 1.4426950408889634;
     const long long o = (long long)u * p.mp_stride + slot;
     p.mp_rows[o] = row;
-    const double lnN = log((double)A.wts[i]);
+    const float lgN = __builtin_amdgcn_logf((float)A.wts[i]);
 #pragma unroll
-    for (int h = 0; h < G; ++h) p.mp_scores[o * G + h] = (float)((A.lg[h * A.lg_stride + i] + lnN) * kLog2e);
+    for (int h = 0; h < G; ++h) p.mp_scores[o * G + h] = (float)(A.lg[h * A.lg_stride + i] * 1.4426950408889634) + lgN;
 }
 
-template <int G, bool kLds>
-__device__ __forceinline__ Arrays make_arrays(unsigned char* lds, const ScoreParams& p, int u)
+// One level: logits, Eq. 1 normaliser, scores, budgeted selection.
+// Entry x stands for cluster id (use_ids ? A.ids[x] : x).  `with_behind`: the normaliser also covers
+// the coarse clusters that stayed behind (S.bm / S.bs).  `meanwhile` runs (in every thread) once the
+// level's centroid rows have been asked for: work of the previous level that the requests did not
+// have to wait for.  `q_pending`: the
+// query operand still has to go to LDS (first level of the launch; qv = this thread's element).
+// `quiet`: store nothing in global memory (shadow workgroup); `reverse`: ask for the rows last round
+// first.  On return A holds logits, keys, member counts (0 = takes no part), row starts and flags,
+// all published by a barrier.  Returns 1 if the keys are linear-domain scores, 0 if they are
+// logarithmic rank keys (the rare case of scores below the range of a double).
+// What a level keeps of its own entries after the selection: the shift per head, and for the first
+// kKeep chunks of kThreads entries the member count and e^{l - shift} of this thread's entry.
+template <int G>
+struct LevelState {
+    double M[G];
+    double ek[kKeep][G];
+    uint32_t wk[kKeep];
+};
+
+template <int G, bool kLds, typename Meanwhile>
+__device__ __forceinline__ int score_level(const ScoreParams& p, const Lds& L, const Arrays& A, Scratch& S, int u, int n,
+                                           bool use_ids, bool coarse, long long budget, bool with_behind,
+                                           bool q_pending, const double (&qv)[(G + 3) / 4], bool quiet, bool reverse,
+                                           unsigned long long* key_out, uint8_t* flag_out, LevelState<G>& state,
+                                           Meanwhile meanwhile)
 {
-    Arrays A;
-    if constexpr (kLds) {
-        A.lg = reinterpret_cast<double*>(lds);
-        A.lg_stride = p.lds_cap;
-        A.keys = reinterpret_cast<uint64_t*>(A.lg + (size_t)G * p.lds_cap);
-        A.wts = reinterpret_cast<uint32_t*>(A.keys + p.lds_cap);
-        A.ids = reinterpret_cast<int32_t*>(A.wts + p.lds_cap);
-        A.aux = A.ids + p.lds_cap;
-        A.aux2 = A.aux + p.lds_cap;
-        A.flags = reinterpret_cast<uint8_t*>(A.aux2 + p.lds_cap);
-    } else {
-        A.lg = p.lg + (long long)u * G * p.lg_stride;
-        A.lg_stride = p.lg_stride;
-        A.keys = reinterpret_cast<uint64_t*>(p.g_keys) + (long long)u * p.g_stride;
-        A.wts = p.g_wts + (long long)u * p.g_stride;
-        A.ids = p.cand + (long long)u * p.f_stride;       // the candidate list itself
-        A.aux = p.g_aux + (long long)u * p.g_stride;
-        A.aux2 = p.g_aux2 + (long long)u * p.g_stride;
-        A.flags = p.g_flags + (long long)u * p.g_stride;
+    constexpr int GH = (G + 3) / 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const double ninf = -INFINITY;
+    const int row_off = coarse ? p.fcap : 0;
+    const int32_t* Nu = p.N + (long long)u * p.tab_rows + row_off;
+    const uint16_t* Kcu = p.Kc + ((long long)u * p.tab_rows + row_off) * kHeadDim;
+    const int32_t* st = coarse ? p.cstart + (long long)u * p.cstart_stride : p.fstart + (long long)u * p.fstart_stride;
+    const int chunks = (n + kThreads - 1) / kThreads;
+
+    // ================= logits: matrix layout, 16 entries per wave and round =================
+    {
+        const int kA = lane >> 4, eA = lane & 15;                       // operand layout: dim group, entry
+        const int jD = lane & 3, eD = ((lane >> 2) & 3) * 4 + (lane >> 4);   // result layout: head, entry
+        const int bsel = kA * 4 + jD;                                   // this lane's slot in a slice of qB
+        const int rounds = (n + 16 * kWaves - 1) / (16 * kWaves);
+        uint4 raw[kInFlight][4];
+        int cntD[kInFlight], auxD[kInFlight], aux2D[kInFlight];
+        auto request = [&](int t, uint4 (&r)[4], int& cnt, int& a1, int& a2) {
+            const int base = ((reverse ? rounds - 1 - t : t) * kWaves + wave) * 16;
+            const int xa = base + eA, xd = base + eD;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) r[c] = make_uint4(0, 0, 0, 0);
+            cnt = a1 = a2 = 0;
+            if (xa < n) {
+                const int id = use_ids ? A.ids[xa] : xa;
+                const uint4* kp = reinterpret_cast<const uint4*>(Kcu + (long long)id * kHeadDim) + kA;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) r[c] = kp[4 * c];
+            }
+            if (xd < n) {
+                const int id = use_ids ? A.ids[xd] : xd;
+                cnt = Nu[id];
+                a1 = st[id];
+                if (coarse) a2 = st[id + 1];
+            }
+        };
+#pragma unroll
+        for (int t = 0; t < kInFlight; ++t) {
+            if (t < rounds) request(t, raw[t], cntD[t], auxD[t], aux2D[t]);
+            else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) raw[t][c] = make_uint4(0, 0, 0, 0);
+                cntD[t] = auxD[t] = aux2D[t] = 0;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // while the rows travel: empty histogram and extremes for this level's selection (their last
+        // readers passed a barrier long ago), and the query operand
+        if (tid < kHistBuckets) L.hist[tid] = 0;
+        if (tid == 0) {
+            S.bl_count = 0;
+            S.key_min = ~0ull;
+            S.key_max = 0;
+            S.key_total = 0;
+            S.key_tiny = 0;
+        }
+        if (q_pending) {
+#pragma unroll
+            for (int hg = 0; hg < GH; ++hg) L.qB[tid + hg * kThreads] = qv[hg];
+            phase_sync<true>();
+        }
+        meanwhile();
+
+        double mx[GH];
+#pragma unroll
+        for (int hg = 0; hg < GH; ++hg) mx[hg] = ninf;
+#pragma unroll 1
+        for (int t0 = 0; t0 < rounds; t0 += kInFlight) {
+#pragma unroll
+            for (int j = 0; j < kInFlight; ++j) {
+                const int t = t0 + j;
+                if (t < rounds) {
+                    double acc[GH];
+#pragma unroll
+                    for (int hg = 0; hg < GH; ++hg) acc[hg] = 0.0;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const uint32_t w4[4] = {raw[j][c].x, raw[j][c].y, raw[j][c].z, raw[j][c].w};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const double a = (double)((e & 1) ? bf16hi_to_f32(w4[e >> 1]) : bf16lo_to_f32(w4[e >> 1]));
+#pragma unroll
+                            for (int hg = 0; hg < GH; ++hg)
+                                acc[hg] = __builtin_amdgcn_mfma_f64_4x4x4f64(a, L.qB[(hg * 32 + 8 * c + e) * 16 + bsel], acc[hg], 0, 0, 0);
+                        }
+                    }
+                    const int xd = ((reverse ? rounds - 1 - t : t) * kWaves + wave) * 16 + eD;
+                    const bool part = xd < n && cntD[j] > 0;
+                    if (xd < n && jD == 0) {
+                        A.wts[xd] = part ? (uint32_t)cntD[j] : 0u;
+                        A.aux[xd] = auxD[j];
+                        if (coarse) A.aux2[xd] = aux2D[j];
+                    }
+#pragma unroll
+                    for (int hg = 0; hg < GH; ++hg) {
+                        const double l = acc[hg] * p.scale;
+                        if (xd < n && 4 * hg + jD < G) {
+                            A.lg[(4 * hg + jD) * A.lg_stride + xd] = l;
+                            if (part) mx[hg] = fmax(mx[hg], l);
+                        }
+                    }
+                    if (t + kInFlight < rounds) request(t + kInFlight, raw[j], cntD[j], auxD[j], aux2D[j]);
+                }
+            }
+        }
+#pragma unroll
+        for (int hg = 0; hg < GH; ++hg) {
+            mx[hg] = max_same_head(mx[hg]);
+            if (lane < 4 && 4 * hg + lane < G) S.wm[wave][4 * hg + lane] = mx[hg];
+        }
     }
-    return A;
+    phase_sync<kLds>();
+
+    // ================= from here on thread tid owns entry tid (+ kThreads per further chunk) =================
+    // shift of the level: the largest logit that takes part (and the shift of what stayed behind)
+    double (&M)[G] = state.M;
+    combine_waves<G>(S.wm, ninf, [](double v) { return row_max_f64(v); },
+                     [&](int, int h, double v) { return (with_behind && S.bs[h] > 0.0) ? fmax(v, S.bm[h]) : v; }, M);
+    // e^{l - M_h} of the own entries (kept in registers for the first kKeep chunks) and the sums of N e^{l - M_h}
+    double (&ek)[kKeep][G] = state.ek;
+    uint32_t (&wk)[kKeep] = state.wk;
+    double sm[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) sm[h] = 0.0;
+#pragma unroll
+    for (int c = 0; c < kKeep; ++c) {
+        wk[c] = 0;
+#pragma unroll
+        for (int h = 0; h < G; ++h) ek[c][h] = 0.0;
+        const int i = tid + c * kThreads;
+        if (i < n) wk[c] = A.wts[i];
+        if (wk[c]) {
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                ek[c][h] = exp_shifted(A.lg[h * A.lg_stride + i] - M[h]);
+                sm[h] += (double)wk[c] * ek[c][h];
+            }
+        }
+    }
+    for (int c = kKeep; c < chunks; ++c) {
+        const int i = tid + c * kThreads;
+        const uint32_t w = i < n ? A.wts[i] : 0u;
+        if (w) {
+#pragma unroll
+            for (int h = 0; h < G; ++h) sm[h] += (double)w * exp_shifted(A.lg[h * A.lg_stride + i] - M[h]);
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        const double t = wave_sum_f64(sm[h]);
+        if (lane == 0) S.ws[wave][h] = t;
+    }
+    phase_sync<kLds>();
+    // 1 / sum_i N_i e^{l - M_h} per head (0 where nothing takes part)
+    double inv[G];
+    combine_waves<G>(S.ws, 0.0, [](double v) { return row_sum_f64(v); },
+                     [&](int, int h, double v) {
+                         if (with_behind && S.bs[h] > 0.0) {
+                             // this row's head: its shift once more, from the table (cheaper than routing M here)
+                             const int w = lane & 15;
+                             const double m = fmax(row_max_f64(w < kWaves ? S.wm[w][h] : ninf), S.bm[h]);
+                             v += S.bs[h] * exp_shifted(S.bm[h] - m);
+                         }
+                         return v > 0.0 ? 1.0 / v : 0.0;
+                     }, inv);
+
+    // ---- keys.  Linear domain: the complement of the bit pattern of sum_h e^{l - LSE_h} (ascending
+    // key = descending score).  If a score leaves the range of a double, the whole level ranks by
+    // log mean_h e^{l - LSE_h} worked out in the log domain instead (second trip; uniform). ----
+    int linear = 1;
+    constexpr double kLogGs[9] = {0.0, 0.0, 0.6931471805599453094, 1.0986122886681097821, 1.3862943611198906188,
+                                  1.6094379124341002818, 1.7917594692280549573, 1.9459101090932196052, 2.0794415416798357477};
+    constexpr double kLogG = kLogGs[G];
+    for (;;) {
+        double smin = INFINITY, smax = ninf;     // extremes of the score (linear) / of the rank key (log)
+        uint32_t wsum = 0;
+        bool tiny = false;
+        auto one_key = [&](int i, uint32_t w, const double (&e)[G], bool kept) {
+            uint64_t key = ~0ull;
+            if (w) {
+                double sc;
+                if (linear) {
+                    sc = 0.0;
+#pragma unroll
+                    for (int h = 0; h < G; ++h)
+                        sc += (kept ? e[h] : exp_shifted(A.lg[h * A.lg_stride + i] - M[h])) * inv[h];
+                    tiny |= !(sc >= 1e-280);
+                    key = ~(uint64_t)__double_as_longlong(sc);
+                } else {
+                    double th[G], tm = ninf;
+#pragma unroll
+                    for (int h = 0; h < G; ++h) {
+                        th[h] = A.lg[h * A.lg_stride + i] - (M[h] - log(not_hoisted(inv[h])));
+                        tm = fmax(tm, th[h]);
+                    }
+                    double ss = 0.0;
+#pragma unroll
+                    for (int h = 0; h < G; ++h) ss += exp_shifted(th[h] - tm);
+                    sc = tm - kLogG + log(ss);
+                    key = descending_key(sc);
+                }
+                smin = fmin(smin, sc);
+                smax = fmax(smax, sc);
+                wsum += w;
+            }
+            if (i < n) {
+                A.keys[i] = key;
+                if (!quiet) key_out[i] = key;
+            }
+        };
+#pragma unroll
+        for (int c = 0; c < kKeep; ++c)
+            if (c < chunks) one_key(tid + c * kThreads, wk[c], ek[c], true);
+        for (int c = kKeep; c < chunks; ++c) {
+            const int i = tid + c * kThreads;
+            one_key(i, i < n ? A.wts[i] : 0u, ek[0], false);
+        }
+        smin = row_min_f64(smin);
+        smax = row_max_f64(smax);
+        smin = fmin(fmin(readlane_f64(smin, 0), readlane_f64(smin, 16)), fmin(readlane_f64(smin, 32), readlane_f64(smin, 48)));
+        smax = fmax(fmax(readlane_f64(smax, 0), readlane_f64(smax, 16)), fmax(readlane_f64(smax, 32), readlane_f64(smax, 48)));
+        wsum = wave_reduce(wsum, [](uint32_t a, uint32_t b) { return a + b; });
+        if (lane == 0 && wsum) {
+            // the largest score carries the smallest key
+            const uint64_t klo = linear ? ~(uint64_t)__double_as_longlong(smax) : descending_key(smax);
+            const uint64_t khi = linear ? ~(uint64_t)__double_as_longlong(smin) : descending_key(smin);
+            atomicMin(&S.key_min, (unsigned long long)klo);
+            atomicMax(&S.key_max, (unsigned long long)khi);
+            atomicAdd(&S.key_total, wsum);
+        }
+        if (__any(tiny) && lane == 0) atomicOr(&S.key_tiny, 1u);
+        phase_sync<kLds>();
+        if (!linear || !S.key_tiny) break;
+        linear = 0;
+        phase_sync<kLds>();       // everyone has seen the flag
+        if (tid == 0) {
+            S.key_min = ~0ull;
+            S.key_max = 0;
+            S.key_total = 0;
+            S.key_tiny = 0;
+        }
+        phase_sync<kLds>();
+    }
+
+    // ---- budgeted selection ----
+    const uint64_t kmin = S.key_min, kmax = S.key_max;
+    const uint32_t total = S.key_total;
+    const uint32_t bud = budget < 0 ? 0u : (budget > 0xffffffffll ? 0xffffffffu : (uint32_t)budget);
+    constexpr unsigned long long kWtMask = (1ull << 40) - 1;
+    if (total <= bud) {
+        for (int c = 0; c < chunks; ++c) {
+            const int i = tid + c * kThreads;
+            if (i < n) {
+                const uint8_t f = A.wts[i] ? 1 : 0;
+                A.flags[i] = f;
+                if (!quiet) flag_out[i] = f;
+            }
+        }
+    } else {
+        const uint64_t range = kmax - kmin;
+        const int hi = range ? 64 - __clzll((long long)range) : 0;
+        const int bits = hi < kHistBits ? hi : kHistBits, shift = hi - bits;
+        for (int c = 0; c < chunks; ++c) {
+            const int i = tid + c * kThreads;
+            const uint32_t w = i < n ? A.wts[i] : 0u;
+            if (w) atomicAdd(&L.hist[(uint32_t)((A.keys[i] - kmin) >> shift)], (1ull << 40) | w);
+        }
+        phase_sync<kLds>();
+        // every wave scans the histogram for itself: kHistBuckets / 64 buckets per lane
+        constexpr int BPL = kHistBuckets / 64;
+        unsigned long long hb[BPL];
+        uint32_t sum = 0;
+#pragma unroll
+        for (int j = 0; j < BPL; ++j) {
+            hb[j] = L.hist[BPL * lane + j];
+            sum += (uint32_t)(hb[j] & kWtMask);
+        }
+        const uint32_t incl = wave_incl_scan_u32(sum);
+        const unsigned long long crossing = __ballot((unsigned long long)incl > bud);
+        const int first = crossing ? __ffsll((long long)crossing) - 1 : 63;
+        uint32_t a = incl - sum, d = BPL * lane, cn = 0;
+        bool done = false;
+#pragma unroll
+        for (int j = 0; j < BPL; ++j) {
+            const uint32_t wj = (uint32_t)(hb[j] & kWtMask);
+            if (!done) {
+                if ((unsigned long long)a + wj > bud) {
+                    d = BPL * lane + j;
+                    cn = (uint32_t)(hb[j] >> 40);
+                    done = true;
+                } else {
+                    a += wj;
+                }
+            }
+        }
+        const uint32_t acc = (uint32_t)__builtin_amdgcn_readlane((int)a, first);
+        const uint32_t bcnt = (uint32_t)__builtin_amdgcn_readlane((int)cn, first);
+        const uint32_t bstar = (uint32_t)__builtin_amdgcn_readlane((int)d, first);
+        if (bcnt <= (uint32_t)kListCap) {
+            // entries before the boundary bucket are taken, entries behind it are not; those inside it
+            // (often one: the first that does not fit) queue up to be ordered by (key, position)
+            for (int c = 0; c < chunks; ++c) {
+                const int i = tid + c * kThreads;
+                if (i >= n) continue;
+                const uint32_t w = A.wts[i];
+                const uint32_t b = w ? (uint32_t)((A.keys[i] - kmin) >> shift) : ~0u;
+                if (b == bstar && bcnt > 1) {
+                    const uint32_t slot = atomicAdd(&S.bl_count, 1u);
+                    L.blist[2 * slot] = A.keys[i];
+                    L.blist[2 * slot + 1] = ((unsigned long long)(uint32_t)i << 32) | w;
+                    continue;
+                }
+                const uint8_t f = (w && b < bstar) ? 1 : 0;
+                A.flags[i] = f;
+                if (!quiet) flag_out[i] = f;
+            }
+            if (bcnt > 1) {
+                phase_sync<kLds>();
+                if ((uint32_t)tid < bcnt) {
+                    const unsigned long long mk = L.blist[2 * tid], mv = L.blist[2 * tid + 1];
+                    const uint32_t mpos = (uint32_t)(mv >> 32);
+                    unsigned long long run = (unsigned long long)acc + (uint32_t)mv;
+                    for (uint32_t m = 0; m < bcnt; ++m) {
+                        const unsigned long long ok = L.blist[2 * m], ov = L.blist[2 * m + 1];
+                        if (ok < mk || (ok == mk && (uint32_t)(ov >> 32) < mpos)) run += (uint32_t)ov;
+                    }
+                    const uint8_t f = run <= bud ? 1 : 0;
+                    A.flags[mpos] = f;
+                    if (!quiet) flag_out[mpos] = f;
+                }
+            }
+        } else {
+            // a crowded boundary bucket (many equal or nearly equal scores): the general search
+            uint64_t kstar = 0, acc2 = 0;
+            uint32_t ties = 0;
+            const bool bounded = radix_select<kLds>(A.keys, A.wts, n, budget, S, kstar, acc2, ties);
+            for (int i = tid; i < n; i += kThreads) {
+                uint8_t f = 0;
+                if (A.wts[i]) {
+                    if (!bounded) f = 1;
+                    else {
+                        const uint64_t k = A.keys[i];
+                        if (k < kstar) f = 1;
+                        else if (k == kstar && ties > 1) {
+                            // exactly equal keys: lower position first, keep while the running count still fits
+                            uint64_t run = acc2;
+                            for (int j = 0; j <= i; ++j)
+                                if (A.wts[j] && A.keys[j] == kstar) run += A.wts[j];
+                            f = ((long long)run <= budget) ? 1 : 0;
+                        }
+                    }
+                }
+                A.flags[i] = f;
+                if (!quiet) flag_out[i] = f;
+            }
+        }
+    }
+    phase_sync<kLds>();
+
+    return linear;
 }
 
-// Coarse level (Sec. 3.4): score all coarse clusters, keep the promising ones, emit centroid terms
-// for the others, leave the log-sum of their N e^l in S.extra and the candidate list (children of
-// the promising clusters, ascending fine id) in global memory and, as far as it fits, in the LDS
-// slot the fine level reads its ids from (unused by the coarse level, whose entries are 0..n-1).
-template <int G, bool kLds, int LPE>
-__device__ __forceinline__ void coarse_phase(const ScoreParams& p, unsigned char* lds, Scratch& S, ScanState& sc,
-                                             int u, const double (&qreg)[G][128 / LPE], int& n_cand,
-                                             uint32_t& n_terms)
+// The clusters a level did not take enter the next level's normaliser through their centroid: their
+// shift and their sum of N e^{l - shift} per head go to S.bm / S.bs (published by the caller's next barrier).
+template <int G, bool kLds>
+__device__ __forceinline__ void leave_behind(const Arrays& A, Scratch& S, int n, const LevelState<G>& st)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int chunks = (n + kThreads - 1) / kThreads;
+    double sm[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) sm[h] = 0.0;
+#pragma unroll
+    for (int c = 0; c < kKeep; ++c) {
+        const int i = tid + c * kThreads;
+        if (st.wk[c] && !A.flags[i]) {
+#pragma unroll
+            for (int h = 0; h < G; ++h) sm[h] += (double)st.wk[c] * st.ek[c][h];
+        }
+    }
+    for (int c = kKeep; c < chunks; ++c) {
+        const int i = tid + c * kThreads;
+        const uint32_t w = i < n ? A.wts[i] : 0u;
+        if (w && !A.flags[i]) {
+#pragma unroll
+            for (int h = 0; h < G; ++h) sm[h] += (double)w * exp_shifted(A.lg[h * A.lg_stride + i] - st.M[h]);
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        const double t = wave_sum_f64(sm[h]);
+        if (lane == 0) S.ws[wave][h] = t;
+    }
+    phase_sync<kLds>();
+    double bsum[G];
+    combine_waves<G>(S.ws, 0.0, [](double v) { return row_sum_f64(v); }, [](int, int, double v) { return v; }, bsum);
+    if (tid == 0) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            S.bm[h] = st.M[h];
+            S.bs[h] = bsum[h];
+        }
+    }
+}
+
+// Coarse level (Sec. 3.4), after scoring and selection: the candidate list (children of the promising
+// clusters, ascending fine id) goes to global memory and, as far as it fits, to the LDS slot the fine
+// level reads its ids from; every cluster that stays behind gets the slot of its centroid term (left
+// in C.aux, which only promising clusters need otherwise).  The terms themselves are written later,
+// by emit_coarse_terms, while the fine level's rows travel.
+template <int G, bool kLds>
+__device__ __forceinline__ void coarse_candidates(const ScoreParams& p, const Arrays& C, int32_t* cand_l, Scratch& S,
+                                                  ScanState& sc, int u, bool quiet, int& n_cand, uint32_t& n_terms)
 {
     const int tid = threadIdx.x;
     const int n_c = p.n_coarse;
-    const Arrays C = make_arrays<G, kLds>(lds, p, u);
-    LevelTerms<G> T;
-    score_level<G, kLds, LPE>(p, C, S, u, n_c, false, true, qreg, p.coarse_budget, false, T);
-    // log-sum of the unpromising clusters: the same terms as in the level's own normaliser, so the
-    // exponentials are not taken again where they were kept
-    double ex[G];
-    {
-        double sm[G];
-#pragma unroll
-        for (int h = 0; h < G; ++h) sm[h] = 0.0;
-        if (G <= 6 && T.kept) {
-#pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                const int i = tid + k * kThreads;
-                if (i < n_c && C.wts[i] != 0 && !C.flags[i])
-#pragma unroll
-                    for (int h = 0; h < G; ++h) sm[h] += T.e[k][h];
-            }
-        } else {
-            for (int i = tid; i < n_c; i += kThreads)
-                if (C.wts[i] != 0 && !C.flags[i]) {
-                    const double w = (double)C.wts[i];
-#pragma unroll
-                    for (int h = 0; h < G; ++h) sm[h] += w * exp_shifted(C.lg[h * C.lg_stride + i] - T.shift[h]);
-                }
-        }
-        combine_lse<G, kLds>(S, T.shift, sm, false, ex);
-    }
-#pragma unroll
-    for (int h = 0; h < G; ++h)
-        if (tid == h) S.extra[h] = ex[h];
     int32_t* cand_g = p.cand + (long long)u * p.f_stride;
-    int32_t* cand_l = make_arrays<G, true>(lds, p, u).ids;
     sc.carry_a = sc.carry_b = 0;
     for (int i0 = 0; i0 < n_c; i0 += kThreads) {
         const int i = i0 + tid;
@@ -637,39 +879,37 @@ __device__ __forceinline__ void coarse_phase(const ScoreParams& p, unsigned char
         chunk_excl_scan2<kLds>((uint32_t)(c1 - c0), emit ? 1u : 0u, S, sc, pos, slot);
         for (int f = c0; f < c1; ++f) {
             const uint32_t o = pos + (uint32_t)(f - c0);
-            cand_g[o] = f;
+            if (!quiet) cand_g[o] = f;
             if (o < (uint32_t)p.lds_cap) cand_l[o] = f;
         }
-        if (emit) emit_term<G>(p, C, u, i, p.fcap + i, slot);
+        if (emit) C.aux[i] = (int32_t)slot;
     }
     n_cand = (int)sc.carry_a;
     n_terms = sc.carry_b;
-    write_views(C, n_c, p.r_c + (long long)u * p.c_stride, p.flag_c + (long long)u * p.c_stride);
-    if (tid == 0) {
+    if (tid == 0 && !quiet) {
         p.n_cand[u] = n_cand;
         p.counters[4 * u + 2] = n_c;
     }
-    // the fine level reuses the coarse level's working arrays; with more candidates than fit in LDS
-    // it also reads the candidate list back from global memory
-    __syncthreads();
 }
 
-// Fine level: score the candidates, select within the key budget, emit centroid terms for the
-// unselected candidates and the flat list of stored rows of the selected clusters.
-template <int G, bool kLds, int LPE>
-__device__ __forceinline__ void fine_phase(const ScoreParams& p, unsigned char* lds, Scratch& S, ScanState& sc,
-                                           int u, const double (&qreg)[G][128 / LPE], int n_f, bool two,
-                                           uint32_t n_terms)
+template <int G>
+__device__ __forceinline__ void emit_coarse_terms(const ScoreParams& p, const Arrays& C, int u)
+{
+    if (!p.use_mp) return;
+    for (int i = threadIdx.x; i < p.n_coarse; i += kThreads)
+        if (C.wts[i] != 0 && !C.flags[i]) emit_term<G>(p, C, u, i, p.fcap + i, (uint32_t)C.aux[i]);
+}
+
+// Fine level, after scoring and selection: emit centroid terms for the unselected candidates and
+// the flat list of stored rows of the selected clusters.
+template <int G, bool kLds>
+__device__ __forceinline__ void fine_epilogue(const ScoreParams& p, const Arrays& F, Scratch& S, ScanState& sc, int u,
+                                              int n_f, bool two, uint32_t n_terms)
 {
     const int tid = threadIdx.x;
-    const Arrays F = make_arrays<G, kLds>(lds, p, u);
-    LevelTerms<G> T;
-    score_level<G, kLds, LPE>(p, F, S, u, n_f, two, false, qreg, p.key_budget, two, T);
-    write_views(F, n_f, p.r_f + (long long)u * p.f_stride, p.flag_f + (long long)u * p.f_stride);
-
     // One scan gives every selected cluster (ascending fine id) its slot in a compact list and the
     // offset of its rows in the flat row list, and every unselected candidate its centroid-term slot.
-    // The compact list reuses the storage of the keys, which nobody reads after the views above.
+    // The compact list reuses the storage of the keys, which nobody reads any more.
     int2* sel_rc = reinterpret_cast<int2*>(F.keys);      // (first stored row, count)
     int32_t* sel_off = F.aux2;
     sc.carry_a = sc.carry_b = 0;
@@ -720,63 +960,112 @@ __device__ __forceinline__ void fine_phase(const ScoreParams& p, unsigned char* 
     }
 }
 
+// What a shadow workgroup does at the last level: ask for the centroid rows of the second half of
+// the level's entries, last entry first, and drop them.
+__device__ __forceinline__ void touch_rows(const ScoreParams& p, const int32_t* ids, int u, int n)
+{
+    const uint16_t* Kcu = p.Kc + (long long)u * p.tab_rows * kHeadDim;
+    const int grp = threadIdx.x >> 4, sub = threadIdx.x & 15;
+    uint32_t x = 0;
+    for (int k = n - 1 - grp; k >= n / 2; k -= kThreads / 16) {
+        const int id = ids ? ids[k] : k;
+        const uint4 v = reinterpret_cast<const uint4*>(Kcu + (long long)id * kHeadDim)[sub];
+        x ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    // (keeps the loads alive: the condition never holds, and the slot would be the unit's own)
+    if (x == 0xfff1fff2u && p.U < 0) p.counters[4 * u] = 0;
+}
+
 template <int G>
 __global__ __launch_bounds__(kThreads) void score_select_kernel(const ScoreParams p)
 {
-    constexpr int LPE = (G <= 4) ? 8 : 16;   // lanes per entry in the logits phase
-    constexpr int DPL = 128 / LPE;
+    constexpr int GH = (G + 3) / 4;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     Scratch& S = *reinterpret_cast<Scratch*>(smem_raw);
-    unsigned char* lds = smem_raw + ((sizeof(Scratch) + 15) & ~size_t(15));
-    const int u = blockIdx.x, tid = threadIdx.x;
+    const Lds L = carve_lds<G>(smem_raw + align16(sizeof(Scratch)), p.lds_cap);
+    const int u = blockIdx.x % p.U, tid = threadIdx.x;
+    const bool shadow = blockIdx.x >= (unsigned)p.U;     // second workgroup of the unit: warms the shared L2, stores nothing
 
-    if (tid < 16 * p.app_n) {       // the step's new rows go to their place in the tail buffers
+    double qv[GH];      // this thread's elements of the query operand (one per head group)
+#pragma unroll
+    for (int hg = 0; hg < GH; ++hg) qv[hg] = query_operand_element<G>(p, u, tid + hg * kThreads);
+    if (!shadow && tid < 16 * p.app_n) {       // the step's new rows go to their place in the tail buffers
         const int a = tid >> 4, c = tid & 15;
         const uint4 w = reinterpret_cast<const uint4*>(p.app_src[a])[(long long)u * 16 + c];
         reinterpret_cast<uint4*>(p.app_dst[a])[((long long)u * p.app_dst_rows + p.app_row) * 16 + c] = w;
     }
 
-    // query slice of this lane: dims [DPL*sub, DPL*sub + DPL) of every head, as doubles
-    double qreg[G][DPL];
-    {
-        const int sub = tid % LPE;
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            const uint4* qp = reinterpret_cast<const uint4*>(p.q + ((long long)u * G + h) * kHeadDim + DPL * sub);
-#pragma unroll
-            for (int v = 0; v < DPL / 8; ++v) {
-                const uint4 qv = qp[v];
-                const uint32_t w[4] = {qv.x, qv.y, qv.z, qv.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    qreg[h][8 * v + 2 * e] = (double)bf16lo_to_f32(w[e]);
-                    qreg[h][8 * v + 2 * e + 1] = (double)bf16hi_to_f32(w[e]);
-                }
-            }
-        }
-    }
-
     const bool two = p.levels == 2;
+    const Arrays Ag = global_arrays<G>(p, u);
     ScanState sc;
+    LevelState<G> stc, stf;
+    const auto nothing = [] {};
     uint32_t n_terms = 0;
     int n_f = p.n_fine;
+    const bool coarse_lds = p.n_coarse <= p.lds_cap;
     if (two) {
-        if (p.n_coarse <= p.lds_cap) coarse_phase<G, true, LPE>(p, lds, S, sc, u, qreg, n_f, n_terms);
-        else coarse_phase<G, false, LPE>(p, lds, S, sc, u, qreg, n_f, n_terms);
+        unsigned long long* kc = p.key_c + (long long)u * p.c_stride;
+        uint8_t* fc = p.flag_c + (long long)u * p.c_stride;
+        if (coarse_lds) {
+            const int lin = score_level<G, true>(p, L, L.A, S, u, p.n_coarse, false, true, p.coarse_budget, false, true, qv,
+                                                 shadow, shadow, kc, fc, stc, nothing);
+            if (tid == 0 && !shadow) p.key_mode[2 * u] = lin;
+            coarse_candidates<G, true>(p, L.A, L.A.ids, S, sc, u, shadow, n_f, n_terms);
+        } else {
+            // (a shadow workgroup would race with the first one on the global working arrays: it leaves)
+            if (shadow) return;
+            const int lin = score_level<G, false>(p, L, Ag, S, u, p.n_coarse, false, true, p.coarse_budget, false, true, qv,
+                                                  false, false, kc, fc, stc, nothing);
+            if (tid == 0) p.key_mode[2 * u] = lin;
+            coarse_candidates<G, false>(p, Ag, L.A.ids, S, sc, u, false, n_f, n_terms);
+        }
+        // the fine level reads the candidate list: from LDS, or back from global memory where it is long
+        __syncthreads();
     }
-    if (n_f <= p.lds_cap) fine_phase<G, true, LPE>(p, lds, S, sc, u, qreg, n_f, two, n_terms);
-    else fine_phase<G, false, LPE>(p, lds, S, sc, u, qreg, n_f, two, n_terms);
+    if (shadow) {
+        if (n_f <= p.lds_cap) touch_rows(p, two ? L.A.ids : nullptr, u, n_f);
+        return;
+    }
+    // What the coarse level still owes -- the centroid terms of the clusters that stayed behind and
+    // their share of the fine level's normaliser -- is done while the fine level's rows travel.  It
+    // reads the coarse level's working arrays, which the fine level is about to reuse: the barrier
+    // inside leave_behind stands between the two.
+    const auto coarse_rest = [&] {
+        if (!two) return;
+        if (coarse_lds) {
+            emit_coarse_terms<G>(p, L.A, u);
+            leave_behind<G, true>(L.A, S, p.n_coarse, stc);
+        } else {
+            emit_coarse_terms<G>(p, Ag, u);
+            leave_behind<G, false>(Ag, S, p.n_coarse, stc);
+        }
+    };
+    unsigned long long* kf = p.key_f + (long long)u * p.f_stride;
+    uint8_t* ff = p.flag_f + (long long)u * p.f_stride;
+    if (n_f <= p.lds_cap) {
+        const int lin = score_level<G, true>(p, L, L.A, S, u, n_f, two, false, p.key_budget, two, !two, qv, false, false, kf, ff,
+                                             stf, coarse_rest);
+        if (tid == 0) p.key_mode[2 * u + 1] = lin;
+        fine_epilogue<G, true>(p, L.A, S, sc, u, n_f, two, n_terms);
+    } else {
+        const int lin = score_level<G, false>(p, L, Ag, S, u, n_f, two, false, p.key_budget, two, !two, qv, false, false, kf, ff,
+                                              stf, coarse_rest);
+        if (tid == 0) p.key_mode[2 * u + 1] = lin;
+        fine_epilogue<G, false>(p, Ag, S, sc, u, n_f, two, n_terms);
+    }
 }
 
 }  // namespace
 
 size_t score_smem_bytes(int G, int lds_cap)
 {
-    return ((sizeof(Scratch) + 15) & ~size_t(15)) + (size_t)lds_cap * (8 * (size_t)G + 8 + 4 * 4 + 1) + 32;
+    const size_t GH = (size_t)(G + 3) / 4;
+    return align16(sizeof(Scratch)) + GH * 512 * 8 + (size_t)kHistBuckets * 8 + (size_t)kListCap * 16 +
+           (size_t)lds_cap * (8 * (size_t)G + 8 + 4 * 4 + 1) + 32;
 }
 
 template <int G>
-static hipError_t launch_score_g(const ScoreParams& p, hipStream_t s)
+static hipError_t launch_score_g(const ScoreParams& p, int copies, hipStream_t s)
 {
     static size_t configured = 48 * 1024;
     const size_t smem = score_smem_bytes(G, p.lds_cap);
@@ -786,21 +1075,24 @@ static hipError_t launch_score_g(const ScoreParams& p, hipStream_t s)
         if (e != hipSuccess) return e;
         configured = smem;
     }
-    hipLaunchKernelGGL((score_select_kernel<G>), dim3(p.U), dim3(kThreads), smem, s, p);
+    hipLaunchKernelGGL((score_select_kernel<G>), dim3(p.U * copies), dim3(kThreads), smem, s, p);
     return hipGetLastError();
 }
 
-hipError_t launch_score_select(const ScoreParams& p, hipStream_t s)
+hipError_t launch_score_select(const ScoreParams& p, int n_compute_units, hipStream_t s)
 {
+    // a shadow workgroup per unit where the chip has compute units to spare and the second workgroup
+    // of unit u (block u + U) lands on the same L2 slice as the first (blocks go round the 8 slices)
+    const int copies = (p.U % 8 == 0 && 2 * p.U <= n_compute_units) ? 2 : 1;
     switch (p.G) {
-        case 1: return launch_score_g<1>(p, s);
-        case 2: return launch_score_g<2>(p, s);
-        case 3: return launch_score_g<3>(p, s);
-        case 4: return launch_score_g<4>(p, s);
-        case 5: return launch_score_g<5>(p, s);
-        case 6: return launch_score_g<6>(p, s);
-        case 7: return launch_score_g<7>(p, s);
-        case 8: return launch_score_g<8>(p, s);
+        case 1: return launch_score_g<1>(p, copies, s);
+        case 2: return launch_score_g<2>(p, copies, s);
+        case 3: return launch_score_g<3>(p, copies, s);
+        case 4: return launch_score_g<4>(p, copies, s);
+        case 5: return launch_score_g<5>(p, copies, s);
+        case 6: return launch_score_g<6>(p, copies, s);
+        case 7: return launch_score_g<7>(p, copies, s);
+        case 8: return launch_score_g<8>(p, copies, s);
         default: return hipErrorInvalidValue;
     }
 }
