@@ -143,6 +143,55 @@ def decode_unit(q, cl, key_budget, coarse_budget=0, Kx=None, Vx=None, scale=None
                 r_f=r_f[:Cf], n_sel_keys=int(nsel.value))
 
 
+def decode_batch(q, cls, key_budget, coarse_budget=0, Kx=None, Vx=None, scale=None, mp_terms=True):
+    """:func:`decode_unit` for a batch of units of identical shape, one OpenMP thread per unit (what
+    the benchmark times as its CPU baseline).  q [U,G,d]; cls: list of U clustering dicts; Kx, Vx
+    [U,nx,d] or None.  Returns out [U,G,d], lse [U,G], promising [U,Cc] (or None), selected [U,Cf]."""
+    q = _f64(q)
+    U, G, d = q.shape
+    assert len(cls) == U
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    levels = int(cls[0]["levels"])
+    st = lambda key, conv: conv(np.stack([np.asarray(c[key]) for c in cls]))
+    K, V, fot = st("K", _f64), st("V", _f64), st("fine_of_token", _i32)
+    Kc_f, Vc_f, N_f = st("Kc_f", _f64), st("Vc_f", _f64), st("N_f", _i32)
+    n, Cf = K.shape[1], N_f.shape[1]
+    if levels == 2:
+        cof, Kc_c, Vc_c, N_c = st("coarse_of_fine", _i32), st("Kc_c", _f64), st("Vc_c", _f64), st("N_c", _i32)
+        Cc = N_c.shape[1]
+    else:
+        cof = Kc_c = Vc_c = N_c = None
+        Cc = 0
+    nx = 0 if Kx is None else int(np.asarray(Kx).shape[1])
+    Kx = _f64(Kx) if nx else None
+    Vx = _f64(Vx) if nx else None
+    out = np.zeros((U, G, d))
+    lse = np.zeros((U, G))
+    promising = np.zeros((U, max(Cc, 1)), dtype=np.uint8)
+    selected = np.zeros((U, max(Cf, 1)), dtype=np.uint8)
+    fails = lib().mpo_decode_batch(
+        C.c_int(U), _d(q), C.c_int(G), C.c_int(d), C.c_double(scale), _d(K), _d(V), C.c_int(n), _i(fot), C.c_int(Cf),
+        _d(Kc_f), _d(Vc_f), _i(N_f), C.c_int(levels), C.c_int(Cc), _i(cof), _d(Kc_c), _d(Vc_c), _i(N_c), _d(Kx), _d(Vx),
+        C.c_int(nx), C.c_int64(int(key_budget)), C.c_int64(int(coarse_budget)), C.c_int(1 if mp_terms else 0), _d(out),
+        _d(lse), _b(promising), _b(selected))
+    if fails:
+        raise ValueError(f"{fails} units with an inconsistent clustering")
+    return out, lse, (promising if levels == 2 else None), selected
+
+
+def full_attention_batch(q, K, V, scale):
+    """:func:`full_attention` for a batch of units, one OpenMP thread per unit.  q [U,G,d], K, V [U,n,d]."""
+    q, K, V = _f64(q), _f64(K), _f64(V)
+    U, G, d = q.shape
+    n = K.shape[1]
+    out = np.zeros((U, G, d))
+    lse = np.zeros((U, G))
+    lib().mpo_full_attention_batch(C.c_int(U), _d(q), _d(K), _d(V), C.c_int(G), C.c_int(n), C.c_int(d), C.c_double(scale),
+                                   _d(out), _d(lse))
+    return out, lse
+
+
 def assign(X, Cn):
     """Nearest-centroid assignment, squared Euclidean distance, ties to the lowest index."""
     X, Cn = _f64(X), _f64(Cn)
@@ -239,8 +288,11 @@ def finalize_block(Kb, Vb, a_fine, Cf_kmeans, parent, kc, Cc_kmeans):
     if parent is not None:
         cof = parent[order].astype(np.int32)
         a_coarse = cof[a_new]
-        Skc, N_c = member_sums(Kb, a_coarse, kc)
-        Svc, _ = member_sums(Vb, a_coarse, kc)
+        # member sums of a coarse cluster run over its rows as stored: fine cluster after fine cluster
+        # (ascending new id), sequence order inside a fine cluster
+        stored = np.argsort(a_new, kind="stable")
+        Skc, N_c = member_sums(Kb[stored], a_coarse[stored], kc)
+        Svc, _ = member_sums(Vb[stored], a_coarse[stored], kc)
         Kc_c = _mean_bf16(Skc, N_c)
         Kc_c[N_c == 0] = Cc_kmeans[N_c == 0]
         Vc_c = _mean_bf16(Svc, N_c)
@@ -310,8 +362,9 @@ def clustering_from_assignment(K, V, fine_of_token, n_fine, coarse_of_fine=None,
     if coarse_of_fine is not None:
         cof = _i32(coarse_of_fine)
         ac = cof[fot]
-        Skc, N_c = member_sums(KL, ac, n_coarse)
-        Svc, _ = member_sums(V, ac, n_coarse)
+        stored = np.argsort(fot, kind="stable")      # coarse sums run over the rows as stored (see finalize_block)
+        Skc, N_c = member_sums(KL[stored], ac[stored], n_coarse)
+        Svc, _ = member_sums(V[stored], ac[stored], n_coarse)
         cl.update(coarse_of_fine=cof, Kc_c=_mean_bf16(Skc, N_c), Vc_c=_mean_bf16(Svc, N_c), N_c=N_c)
     if K_lookup is not None:
         cl["KL"] = KL

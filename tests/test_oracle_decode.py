@@ -351,3 +351,40 @@ def test_more_heads_than_clusters():
         np.testing.assert_allclose(r["lse"], (q @ K[0]) / np.sqrt(16), rtol=1e-13, atol=1e-13)
     r = O.decode_unit(q, cl, 1, 1, mp_terms=False)
     np.testing.assert_allclose(r["out"], np.repeat(V, 7, axis=0), rtol=1e-14)
+
+
+def test_batch_entry_points_equal_a_loop_over_units():
+    """mpo_decode_batch / mpo_full_attention_batch (what the benchmark times on the host) against a
+    loop of the per-unit functions that all other pins rest on: bit-identical."""
+    rng = np.random.default_rng(21)
+    U, G, d, n, kf, kc = 5, 3, 16, 300, 20, 4
+
+    def bf16(a):
+        import torch
+        return torch.tensor(np.asarray(a), dtype=torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+
+    cls, qs, Kxs, Vxs = [], [], [], []
+    blocks = O.plan_blocks(n, 0, 0, kf, kc)
+    for u in range(U):
+        centers = rng.normal(size=(8, d)) * 2
+        K = bf16(centers[rng.integers(0, 8, n)] + 0.3 * rng.normal(size=(n, d)))
+        V = bf16(rng.normal(size=(n, d)))
+        cls.append(O.cluster_unit(K, V, blocks, rng.choice(n, kf, replace=False), rng.choice(kf, kc, replace=False), 2, 2))
+        qs.append(bf16(0.5 * centers[rng.integers(0, 8, G)] + 0.3 * rng.normal(size=(G, d))))
+        Kxs.append(bf16(rng.normal(size=(7, d))))
+        Vxs.append(bf16(rng.normal(size=(7, d))))
+    q, Kx, Vx = np.stack(qs), np.stack(Kxs), np.stack(Vxs)
+    for kb, cb, tail, terms in [(60, 150, True, True), (0, 0, False, True), (40, 100, True, False), (10 ** 6, 10 ** 6, False, True)]:
+        out, lse, prom, sel = O.decode_batch(q, cls, kb, cb, Kx if tail else None, Vx if tail else None, mp_terms=terms)
+        for u in range(U):
+            r = O.decode_unit(q[u], cls[u], kb, cb, Kx[u] if tail else None, Vx[u] if tail else None, mp_terms=terms)
+            np.testing.assert_array_equal(out[u], r["out"])
+            np.testing.assert_array_equal(lse[u], r["lse"])
+            np.testing.assert_array_equal(prom[u], r["promising"])
+            np.testing.assert_array_equal(sel[u], r["selected"])
+    K, V = np.stack([c["K"] for c in cls]), np.stack([c["V"] for c in cls])
+    out, lse = O.full_attention_batch(q, K, V, 0.25)
+    for u in range(U):
+        o, l = O.full_attention(q[u], K[u], V[u], 0.25)
+        np.testing.assert_array_equal(out[u], o)
+        np.testing.assert_array_equal(lse[u], l)

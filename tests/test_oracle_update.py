@@ -146,3 +146,102 @@ def test_update_of_a_later_block_leaves_frozen_blocks_untouched():
     res = O.decode_unit(q, out, key_budget=716, coarse_budget=716)
     ref, _ = O.full_attention(q, out["K"], out["V"], 0.25)
     np.testing.assert_allclose(res["out"], ref, rtol=1e-12, atol=1e-14)
+
+
+def test_coarse_refresh_assigns_every_fine_centroid_to_its_nearest_stored_coarse_centroid():
+    """Coarse level of an update (Sec. 3.4 applied to Sec. 3.3), no refinement, no new coarse seed:
+    one Lloyd step of the block's fine working centroids from the stored coarse key centroids.
+    Every appended token seeds a cluster of its own, so the working centroids are known without any
+    arithmetic (stored fine centroids, then the appended keys); the library argmin gives the parents;
+    the stable renumbering and the stored means follow from their definitions."""
+    from sklearn.metrics import pairwise_distances_argmin
+    rng = np.random.default_rng(11)
+    cl, centers = _setup(rng, n=600, kf=24, kc=4, levels=2)
+    n_new = 6
+    Kn, Vn = _new_tokens(rng, centers, n_new)
+    out = O.update_unit(cl, Kn, Vn, n_new, 0, list(range(n_new)), 0, 0, 0)
+    _check_consistent(out)
+    Cw = np.concatenate([cl["Kc_f"], Kn])                      # working fine centroids, old numbering
+    parent = pairwise_distances_argmin(Cw, cl["Kc_c"])         # nearest stored coarse centroid
+    order = np.argsort(parent, kind="stable")                  # children contiguous, stable in the old id
+    np.testing.assert_array_equal(out["coarse_of_fine"], parent[order])
+    old_fot = np.concatenate([cl["fine_of_token"], 24 + np.arange(n_new)])    # each appended token: its own cluster
+    new_of_old = np.empty(30, dtype=np.int64)
+    new_of_old[order] = np.arange(30)
+    np.testing.assert_array_equal(out["fine_of_token"], new_of_old[old_fot])
+    # stored coarse tables = member counts and bf16 means of all member keys / values
+    tok_parent = parent[old_fot]
+    for c in range(4):
+        m = tok_parent == c
+        assert out["N_c"][c] == m.sum()
+        np.testing.assert_array_equal(out["Kc_c"][c], _bf16(out["K"][m].sum(0) / m.sum()))
+        np.testing.assert_array_equal(out["Vc_c"][c], _bf16(out["V"][m].sum(0) / m.sum()))
+
+
+def test_coarse_refresh_with_separated_families_and_a_far_new_coarse_seed():
+    """Two families of fine clusters far apart: after any update each fine cluster must hang under its
+    family's coarse cluster, and a new coarse cluster seeded with a far-away new fine cluster captures
+    exactly that fine cluster."""
+    rng = np.random.default_rng(12)
+    d = 16
+    fam = np.zeros((2, d)); fam[0, 0] = -50.0; fam[1, 0] = 50.0
+    n = 400
+    side = (np.arange(n) % 2)                       # tokens alternate between the families
+    K = _bf16(fam[side] + rng.normal(size=(n, d)))
+    V = _bf16(rng.normal(size=(n, d)))
+    # seeds: 5 fine clusters per family, one coarse seed in each family
+    init_f = np.array([0, 2, 4, 6, 8, 1, 3, 5, 7, 9])
+    blocks = O.plan_blocks(n, 0, 0, 10, 2)
+    cl = O.cluster_unit(K, V, blocks, init_f, np.array([0, 5]), 3, 2)
+    np.testing.assert_array_equal(cl["coarse_of_fine"], [0] * 5 + [1] * 5)
+    # append 8 ordinary tokens and one far away from both families; it seeds a fine and a coarse cluster
+    Kn = _bf16(fam[np.arange(9) % 2] + rng.normal(size=(9, d)))
+    Kn[8] = 0.0; Kn[8, 1] = 200.0
+    Vn = _bf16(rng.normal(size=(9, d)))
+    for refine in (0, 2):
+        out = O.update_unit(cl, Kn, Vn, 1, 1, [8, 0], refine, 0, 0)
+        _check_consistent(out)
+        assert out["N_c"].tolist() == [204, 204, 1]
+        np.testing.assert_array_equal(out["coarse_of_fine"], [0] * 5 + [1] * 5 + [2])
+        f_far = out["fine_of_token"][n + 8]
+        assert f_far == 10 and out["N_f"][10] == 1
+        np.testing.assert_array_equal(out["Kc_c"][2], Kn[8])
+        np.testing.assert_array_equal(out["Vc_c"][2], Vn[8])
+        # every token hangs under the coarse cluster of its family
+        tok_c = out["coarse_of_fine"][out["fine_of_token"]]
+        np.testing.assert_array_equal(tok_c[:n], side)
+        np.testing.assert_array_equal(tok_c[n:n + 8], np.arange(8) % 2)
+
+
+def test_update_seed_counts_values():
+    b1 = [dict(t0=0, t1=600, f0=0, f1=24, c0=0, c1=4)]
+    assert O.update_seed_counts(b1, 32, 3, 1, 0, 0, 2) == [3, 1, 0, 0, 0, 0]          # one block for ever: never a split
+    assert O.update_seed_counts(b1, 32, 3, 1, 0, 0, 1) == [3, 0, 0, 0, 0, 0]          # one level: no coarse seeds
+    # W = 512, alpha = 128: 600 + 40 = 640 tokens reach W + alpha; 24 + 4 = 28 fine and 4 + 2 = 6 coarse clusters are
+    # shared out as 28 * 512 // 640 = 22 / 6 and 6 * 512 // 640 = 4 / 2
+    assert O.update_seed_counts(b1, 40, 4, 2, 512, 128, 2) == [4, 2, 22, 6, 4, 2]
+    assert O.update_seed_counts(b1, 40, 4, 2, 512, 128, 1) == [4, 0, 22, 6, 0, 0]
+    assert O.update_seed_counts(b1, 39, 4, 2, 512, 128, 2) == [4, 2, 0, 0, 0, 0]      # 639 tokens: one short
+    # only the last block counts
+    b2 = [dict(t0=0, t1=512, f0=0, f1=32, c0=0, c1=4), dict(t0=512, t1=700, f0=32, f1=44, c0=4, c1=6)]
+    assert O.update_seed_counts(b2, 452, 8, 1, 512, 128, 2) == [8, 1, (12 + 8) * 512 // 640, 20 - 20 * 512 // 640, 3 * 512 // 640, 3 - 3 * 512 // 640]
+
+
+def test_coarse_refresh_runs_max_1_refine_iters_lloyd_steps():
+    """Hand-worked on a line: fine clusters at 0, 0, 0, 0 and 6, stored coarse key centroids 3.5 and 9.
+    One Lloyd step over the fine centroids puts all five under coarse 0 (6 is 2.5 from 3.5, 3 from 9) and
+    moves that centroid to 6/5; only a second step hands the fine cluster at 6 to coarse 1 (4.8 against 3)."""
+    K = np.array([[0.0], [0.0], [0.0], [0.0], [6.0]])
+    V = np.arange(5, dtype=np.float64)[:, None]
+    cl = O.clustering_from_assignment(K, V, [0, 1, 2, 3, 4], 5, [0, 0, 0, 0, 1], 2)
+    cl["Kc_c"] = np.array([[3.5], [9.0]])          # what an earlier history may have left behind
+    new_k, new_v = np.array([[0.0]]), np.array([[7.0]])
+    out = O.update_unit(cl, new_k, new_v, 0, 0, [], 0, 0, 0)          # no refinement: ONE coarse step
+    np.testing.assert_array_equal(out["coarse_of_fine"], [0, 0, 0, 0, 0])
+    np.testing.assert_array_equal(out["N_c"], [6, 0])
+    assert out["Kc_c"][1, 0] == 9.0 and out["Kc_c"][0, 0] == 1.0      # empty: keeps its centroid; mean key of six tokens
+    assert out["fine_of_token"][5] == 0                                # equal distances: lowest id
+    out = O.update_unit(cl, new_k, new_v, 0, 0, [], 2, 0, 0)          # two refinement iterations: TWO coarse steps
+    np.testing.assert_array_equal(out["coarse_of_fine"], [0, 0, 0, 0, 1])
+    np.testing.assert_array_equal(out["N_c"], [5, 1])
+    np.testing.assert_array_equal(out["Kc_c"][:, 0], [0.0, 6.0])
