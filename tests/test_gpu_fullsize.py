@@ -1,6 +1,7 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
-(cfg3: batch 16, 32/8 heads, 131072 tokens, 4096 fine / 256 coarse clusters, W = 8192), on sampled
-units the oracle can afford, plus properties that hold at any size."""
+"""GPU parity at the benchmark's full sizes, in the launch configurations bench.py times
+(cfg3: batch 16, 32/8 heads, 131072 tokens, 4096 fine / 256 coarse clusters, W = 8192; the online
+workload cfg4: 64 units, 8192-token prefill, refreshes of 128 tokens through the split at W + alpha;
+cfg1 and cfg2 decode), on sampled units the oracle can afford, plus properties that hold at any size."""
 import numpy as np
 import pytest
 import torch
@@ -106,3 +107,56 @@ def test_full_size_tail_and_repeatability(cfg3):
     out2 = ctx.mp_decode_attention(q, 8192, 16384, kt, vt)
     torch.cuda.synchronize()
     assert torch.equal(r["out"], out2)          # bit-reproducible
+
+
+def test_online_workload_shape_update_chain_through_the_split():
+    """cfg4_online's shape: 64 units, 8192-token prefill with 256 fine / 32 coarse clusters in one block
+    (W = 8192, alpha = 4096), refreshes of 128 tokens with 16 + 2 new clusters and 3 refinement
+    iterations.  The benchmark needs 32 refreshes to reach W + alpha = 12288 tokens; here two refreshes,
+    one large append up to 12160 tokens, and the refresh that crosses 12288 and splits the block, then one
+    more refresh of the new last block -- every call's index against the oracle on two sampled units
+    (assignments, counts, fine and coarse tables, layout: bit-exact), then one decode step."""
+    from tests.test_gpu_update import _chain
+    from tests.gpu_util import compare_decode
+    from paper_2506_13059_amd import inputs
+    w = inputs.WORKLOADS["cfg4_online"]
+    big = 12160 - (w.context + 2 * 128)
+    updates = [(128, 16, 2, 3), (128, 16, 2, 3), (big, big // 8, big // 64, 3), (128, 16, 2, 3), (128, 16, 2, 3)]
+    n_end = w.context + sum(u[0] for u in updates)
+    units = [5, 62]
+    ctx, cls, centers = _chain(w.batch, w.n_q_heads, w.n_kv_heads, w.context, w.modes, 2, w.n_fine, w.n_coarse, w.block_w,
+                               w.block_alpha, iters=3, updates=updates, seed=4100, max_tokens=n_end,
+                               max_fine=w.n_fine + sum(u[1] for u in updates), max_coarse=w.n_coarse + sum(u[2] for u in updates),
+                               units=units)
+    assert [(b["t0"], b["t1"]) for b in cls[0]["blocks"]] == [(0, 8192), (8192, n_end)]
+    U = w.units
+    q = inputs.draw_queries(centers, w.group, 1, 4105).view(1, w.batch, w.n_q_heads, 128)[0].contiguous()
+    K = torch.zeros(U, n_end, 128, dtype=torch.bfloat16, device="cuda")
+    V = torch.zeros(U, n_end, 128, dtype=torch.bfloat16, device="cuda")
+    for u, cl in zip(units, cls):       # (only the sampled units' rows are looked at)
+        K[u] = torch.tensor(cl["K"], dtype=torch.float64).to(torch.bfloat16)
+        V[u] = torch.tensor(cl["V"], dtype=torch.float64).to(torch.bfloat16)
+    r = compare_decode(ctx, q, K.view(w.batch, w.n_kv_heads, n_end, 128), V.view(w.batch, w.n_kv_heads, n_end, 128),
+                       n_end // 8, n_end // 4, units=units, label="cfg4 shape after the split")
+    assert r["exempt"] == 0
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,units", [("cfg1_qwen3_8b_32k", [0, 7]), ("cfg2_14b_64k", [3, 30])])
+def test_smaller_benchmark_workloads_decode_sampled_units_match_oracle(name, units):
+    """cfg1 (8 units, 32768 tokens, 1024 fine / 64 coarse) and cfg2 (32 units, groups of 5 query heads,
+    65536 tokens, 2048 fine / 128 coarse) at their benchmark key budget, index built by the library."""
+    from paper_2506_13059_amd import binding as mp, inputs
+    from tests.gpu_util import compare_decode
+    w = inputs.WORKLOADS[name]
+    data = inputs.make_workload(w, "cuda", seed=1000 * list(inputs.WORKLOADS).index(name), n_query_sets=2)
+    ctx = mp.MpContext(w.batch, w.n_q_heads, w.n_kv_heads, max_tokens=w.context, levels=2, max_fine=w.n_fine,
+                       max_coarse=w.n_coarse, block_w=w.block_w, block_alpha=w.block_alpha, max_tail=0)
+    ctx.mp_cluster_kv(data["K"], data["V"], w.n_fine, w.n_coarse, iters=3, init_fine=data["init_fine"],
+                      init_coarse=data["init_coarse"])
+    kb = w.key_budgets[0]
+    r = compare_decode(ctx, data["q"][1].contiguous(), data["K"], data["V"], kb, 2 * kb, units=units, label=name)
+    assert r["exempt"] == 0
+    cnt = ctx.mp_get_counters().cpu().numpy()
+    assert (cnt[:, 0] <= kb).all() and (cnt[:, 0] > 0.9 * kb).all()
+    ctx.close()

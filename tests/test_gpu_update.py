@@ -7,7 +7,8 @@ import torch
 pytestmark = pytest.mark.gpu
 
 
-def _compare_index(ctx, cls, levels, label):
+def _compare_index(ctx, cls, levels, label, units=None):
+    """cls: oracle clusterings of the units listed in `units` (default: all units, in order)."""
     from tests.gpu_util import f64, i32
     fot, cof = ctx.mp_get_assignments()
     kc, vc, nm = ctx.mp_get_centroids(0)
@@ -19,7 +20,7 @@ def _compare_index(ctx, cls, levels, label):
         kcc, vcc, nmc = ctx.mp_get_centroids(1)
         torch.cuda.synchronize()
         cof, kcc, vcc, nmc = i32(cof), f64(kcc), f64(vcc), i32(nmc)
-    for u, cl in enumerate(cls):
+    for u, cl in zip(range(len(cls)) if units is None else units, cls):
         n = cl["K"].shape[0]
         assert sizes["n_tokens"] == n and sizes["n_fine"] == cl["N_f"].shape[0] and sizes["n_blocks"] == len(cl["blocks"])
         np.testing.assert_array_equal(fot[u], cl["fine_of_token"], err_msg=f"{label} unit {u} fine assignment")
@@ -41,14 +42,16 @@ def _compare_index(ctx, cls, levels, label):
 
 
 def _chain(B, Hq, Hkv, n0, modes, levels, nf, nc, W, alpha, iters, updates, seed, max_tokens, max_fine, max_coarse,
-           lookup=None):
-    """updates: list of (n_new, n_new_fine, n_new_coarse, refine_iters).  lookup: None, or how the
+           lookup=None, units=None):
+    """updates: list of (n_new, n_new_fine, n_new_coarse, refine_iters).  units: the units the oracle
+    follows (default: all; the library always works on all of them).  lookup: None, or how the
     lookup keys relate to the stored keys: "rope" (stored keys rotated to their own position, lookup
     keys to one fixed position, Sec. 3.1 last paragraph) or "perm" (a signed permutation)."""
     from paper_2506_13059_amd import binding as mp, inputs
     from oracle import mp_oracle as O
     from tests.gpu_util import f64, rope, signed_permutation
     U = B * Hkv
+    sample = list(range(U)) if units is None else list(units)
     centers = inputs.make_modes(U, modes, "cuda", seed)
     K, V = inputs.draw_tokens(centers, n0, seed + 1)
     A = signed_permutation(128, seed, "cuda")
@@ -68,11 +71,9 @@ def _chain(B, Hq, Hkv, n0, modes, levels, nf, nc, W, alpha, iters, updates, seed
                        block_w=W, block_alpha=alpha, max_tail=0, lookup_keys=lookup is not None)
     ctx.mp_cluster_kv(K.view(B, Hkv, n0, 128), V.view(B, Hkv, n0, 128), nf, nc, iters=iters, init_fine=init_f,
                       init_coarse=init_c if levels == 2 else None, k_lookup=lk(KL, n0))
-    K64, V64 = f64(K), f64(V)
-    KL64 = f64(KL) if lookup else [None] * U
-    cls = [O.cluster_unit(K64[u], V64[u], blocks, init_f[u].numpy(), init_c[u].numpy() if levels == 2 else None,
-                          iters, levels, K_lookup=KL64[u]) for u in range(U)]
-    _compare_index(ctx, cls, levels, "after build")
+    cls = [O.cluster_unit(f64(K[u]), f64(V[u]), blocks, init_f[u].numpy(), init_c[u].numpy() if levels == 2 else None,
+                          iters, levels, K_lookup=f64(KL[u]) if lookup else None) for u in sample]
+    _compare_index(ctx, cls, levels, "after build", sample)
     rng = np.random.default_rng(seed)
     for step, (n_new, nnf, nnc, refine) in enumerate(updates):
         print(f"update {step}: +{n_new} tokens, +{nnf} fine, +{nnc} coarse, refine {refine}", flush=True)
@@ -87,11 +88,9 @@ def _chain(B, Hq, Hkv, n0, modes, levels, nf, nc, W, alpha, iters, updates, seed
                           for _ in range(U)]).astype(np.int32)
         ctx.mp_update_clusters(Kn.view(B, Hkv, n_new, 128), Vn.view(B, Hkv, n_new, 128), nnf, nnc, refine_iters=refine,
                                split_iters=iters, seeds=torch.tensor(seeds), k_new_lookup=lk(KLn, n_new))
-        Kn64, Vn64 = f64(Kn), f64(Vn)
-        KLn64 = f64(KLn) if lookup else [None] * U
-        cls = [O.update_unit(cls[u], Kn64[u], Vn64[u], nnf, nnc, seeds[u], refine, W, alpha, split_iters=iters,
-                             K_new_lookup=KLn64[u]) for u in range(U)]
-        _compare_index(ctx, cls, levels, f"after update {step}")
+        cls = [O.update_unit(cl, f64(Kn[u]), f64(Vn[u]), nnf, nnc, seeds[u], refine, W, alpha, split_iters=iters,
+                             K_new_lookup=f64(KLn[u]) if lookup else None) for u, cl in zip(sample, cls)]
+        _compare_index(ctx, cls, levels, f"after update {step}", sample)
     return ctx, cls, centers
 
 
