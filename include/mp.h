@@ -14,8 +14,13 @@
  *     Tensors are dense, row-major, in the stated shape.  bf16 = bfloat16.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device work is
  *     enqueued on it and the call returns without waiting for the GPU, unless stated otherwise.
- *   - Every function returns an mp_status.  On any status other than MP_OK nothing has been
- *     enqueued and the context is unchanged; mp_last_error() gives a readable message.
+ *   - Every function returns an mp_status; mp_last_error() gives a readable message.  Argument,
+ *     state and capacity errors (MP_EINVAL, MP_ESTATE, MP_ECAPACITY, MP_ENOMEM) are found before
+ *     anything is enqueued and leave the context unchanged.  MP_EHIP means a HIP runtime call
+ *     failed, possibly after part of the call's work was enqueued: outputs are then undefined, and
+ *     if the call was building or updating the index (mp_cluster_kv, mp_set_clustering,
+ *     mp_update_clusters, a refreshing mp_decode_step) the context has no index any more (calls that
+ *     need one return MP_ESTATE until the next successful mp_cluster_kv / mp_set_clustering).
  *     No C++ exception crosses this boundary.
  *   - head_dim must be 128.  1 <= G <= 8.
  *   - A context may be used from one host thread at a time; calls on the same context that
@@ -100,10 +105,10 @@ int32_t mp_plan_blocks(int32_t n_tokens, int32_t block_w, int32_t block_alpha, i
  *               count); ignored when levels == 1.
  *   iters       Lloyd iterations (>= 1) at each level, no early stop (Sec. 5.1 uses 10).
  *   init_fine   host int32 [B*Hkv, n_fine]: seeds, block after block, each the index of a token
- *               inside its block (distinct per block).  NULL: drawn from `seed`.
+ *               inside its block (distinct per block, else MP_EINVAL).  NULL: drawn from `seed`.
  *   init_coarse host int32 [B*Hkv, n_coarse]: seeds of the coarse level, each the index of a fine
  *               cluster inside its block, numbered as produced by the fine k-means (= position of
- *               its seed in init_fine).  NULL: drawn from `seed`.
+ *               its seed in init_fine); distinct per block, else MP_EINVAL.  NULL: drawn from `seed`.
  *
  * Per block: centroids start at the seed keys; each iteration assigns every key to the nearest
  * centroid (squared Euclidean distance in fp64, equal distances -> lowest index) and replaces each

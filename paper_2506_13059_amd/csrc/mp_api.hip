@@ -95,6 +95,17 @@ namespace {
 
 inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 
+// k distinct values, all in [0, n)?
+bool distinct_in_range(const int32_t* v, int k, int n)
+{
+    std::vector<char> seen((size_t)std::max(n, 1), 0);
+    for (int i = 0; i < k; ++i) {
+        if (v[i] < 0 || v[i] >= n || seen[v[i]]) return false;
+        seen[v[i]] = 1;
+    }
+    return true;
+}
+
 template <typename T>
 hipError_t dev_alloc(mp_ctx* ctx, T** p, size_t count)
 {
@@ -272,19 +283,17 @@ mp_status mp_cluster_kv(mp_ctx* ctx, const void* k, const void* k_lookup, const 
     if (init_fine)
         for (int u = 0; u < U; ++u)
             for (const BlockPlan& b : blocks)
-                for (int f = b.f0; f < b.f1; ++f) {
-                    const int32_t t = init_fine[(size_t)u * n_fine + f];
-                    if (t < 0 || t >= b.t1 - b.t0) return fail(ctx, MP_EINVAL, "mp_cluster_kv: init_fine[%d][%d] = %d out of its block", u, f, t);
-                }
+                if (!distinct_in_range(init_fine + (size_t)u * n_fine + b.f0, b.f1 - b.f0, b.t1 - b.t0))
+                    return fail(ctx, MP_EINVAL, "mp_cluster_kv: init_fine of unit %d, block [%d,%d) is not a set of distinct token indices inside the block", u, b.t0, b.t1);
     if (init_coarse && ctx->cfg.levels == 2)
         for (int u = 0; u < U; ++u)
             for (const BlockPlan& b : blocks)
-                for (int c = b.c0; c < b.c1; ++c) {
-                    const int32_t f = init_coarse[(size_t)u * n_coarse + c];
-                    if (f < 0 || f >= b.f1 - b.f0) return fail(ctx, MP_EINVAL, "mp_cluster_kv: init_coarse[%d][%d] = %d out of its block", u, c, f);
-                }
+                if (!distinct_in_range(init_coarse + (size_t)u * n_coarse + b.c0, b.c1 - b.c0, b.f1 - b.f0))
+                    return fail(ctx, MP_EINVAL, "mp_cluster_kv: init_coarse of unit %d, block [%d,%d) is not a set of distinct fine-cluster indices inside the block", u, b.t0, b.t1);
     if (!lookup_arg_ok(ctx, k_lookup)) return fail(ctx, MP_EINVAL, "mp_cluster_kv: k_lookup must be given exactly when the context was created with lookup_keys");
-    return cluster_kv_impl(ctx, k, k_lookup, v, n_tokens, n_fine, n_coarse, iters, seed, init_fine, init_coarse, (hipStream_t)stream);
+    const mp_status st = cluster_kv_impl(ctx, k, k_lookup, v, n_tokens, n_fine, n_coarse, iters, seed, init_fine, init_coarse, (hipStream_t)stream);
+    if (st == MP_EHIP) ctx->has_index = false;      // the launch sequence broke off part-way: no usable index
+    return st;
 }
 
 mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* k_lookup, const void* v, int32_t n_tokens,
@@ -303,7 +312,9 @@ mp_status mp_set_clustering(mp_ctx* ctx, const void* k, const void* k_lookup, co
         n_coarse = 0;
     }
     if (!lookup_arg_ok(ctx, k_lookup)) return fail(ctx, MP_EINVAL, "mp_set_clustering: k_lookup must be given exactly when the context was created with lookup_keys");
-    return set_clustering_impl(ctx, k, k_lookup, v, n_tokens, fine_of_token, n_fine, coarse_of_fine, n_coarse, (hipStream_t)stream);
+    const mp_status st = set_clustering_impl(ctx, k, k_lookup, v, n_tokens, fine_of_token, n_fine, coarse_of_fine, n_coarse, (hipStream_t)stream);
+    if (st == MP_EHIP) ctx->has_index = false;
+    return st;
 }
 
 int32_t mp_update_seed_counts(const mp_ctx* ctx, int32_t n_new, int32_t n_new_fine, int32_t n_new_coarse, int32_t* counts)
@@ -328,8 +339,10 @@ mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* k_new_l
     if (ctx->cfg.levels == 2 && (n_new_coarse < 0 || n_new_coarse > n_new_fine))
         return fail(ctx, MP_EINVAL, "mp_update_clusters: n_new_coarse must be in [0, n_new_fine]");
     if (!lookup_arg_ok(ctx, k_new_lookup)) return fail(ctx, MP_EINVAL, "mp_update_clusters: k_new_lookup must be given exactly when the context was created with lookup_keys");
-    return update_clusters_impl(ctx, k_new, k_new_lookup, v_new, n_new, n_new_fine, ctx->cfg.levels == 2 ? n_new_coarse : 0,
-                                refine_iters, split_iters, seed, seeds, (hipStream_t)stream);
+    const mp_status st = update_clusters_impl(ctx, k_new, k_new_lookup, v_new, n_new, n_new_fine, ctx->cfg.levels == 2 ? n_new_coarse : 0,
+                                              refine_iters, split_iters, seed, seeds, (hipStream_t)stream);
+    if (st == MP_EHIP) ctx->has_index = false;      // the launch sequence broke off part-way: no usable index
+    return st;
 }
 
 }  // extern "C"
@@ -380,10 +393,7 @@ static mp_status decode_impl(mp_ctx* ctx, const void* q, const void* q_lookup, c
         sp.app_n = app->n; sp.app_dst_rows = app->dst_rows; sp.app_row = app->row;
         for (int a = 0; a < app->n; ++a) { sp.app_src[a] = app->src[a]; sp.app_dst[a] = app->dst[a]; }
     }
-    if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[0], s));
-    if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[1], s));
-    MP_HIP(ctx, launch_score_select(sp, ctx->n_cus, s));
-    if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[2], s));
+    // the plan of the value pass first: every check that can fail is made before anything is enqueued
 
     ValuePassParams vp{};
     vp.q = (const uint16_t*)q;
@@ -418,6 +428,10 @@ static mp_status decode_impl(mp_ctx* ctx, const void* q, const void* q_lookup, c
     vp.n_sources = ns;
     vp.chunks_per_unit = chunk0;
     if (chunk0 > ctx->Pcap) return fail(ctx, MP_ECAPACITY, "mp_decode_attention: %d chunks > workspace %d", chunk0, ctx->Pcap);
+    if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[0], s));
+    if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[1], s));
+    MP_HIP(ctx, launch_score_select(sp, ctx->n_cus, s));
+    if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[2], s));
     if (chunk0 > 0) MP_HIP(ctx, launch_value_pass(vp, G, s));
     if (ctx->timing) MP_HIP(ctx, hipEventRecord(ctx->ev[3], s));
     MP_HIP(ctx, launch_merge(ctx->partials, U, chunk0, G, (uint16_t*)out, lse, s));

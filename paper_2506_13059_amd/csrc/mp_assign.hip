@@ -1,5 +1,5 @@
-// Nearest-centroid assignment of blockwise k-means (Sec. 3.2: assignment step of Lloyd's iterations
-// inside each block of the sequence; also the one-shot assignment of appended tokens, Sec. 3.3).
+// Nearest-centroid assignment of k-means on the keys (Sec. 3.1: assignment step of Lloyd's iterations;
+// Sec. 3.3: run inside each block of the sequence, and as the one-shot assignment of appended tokens).
 //
 // The result is defined in fp64: a[t] = argmin_j sum_i (x_t[i] - c_j[i])^2 with the sum taken in
 // index order and the lowest j among equal distances.  Points and centroids are bf16 values, so the

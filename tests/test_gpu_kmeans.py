@@ -145,3 +145,18 @@ def test_cluster_argument_errors():
         ctx.mp_cluster_kv(big, big, 16, 4)
     assert e.value.status == mp.MP_ECAPACITY
     ctx.close()
+
+
+def test_cluster_kv_rejects_duplicate_seeds():
+    from paper_2506_13059_amd import binding as mp
+    ctx = mp.MpContext(1, 2, 1, max_tokens=300, levels=2, max_fine=8, max_coarse=2, max_tail=0)
+    K = torch.randn(1, 1, 300, 128, device="cuda").to(torch.bfloat16)
+    good_f = torch.tensor([[0, 10, 20, 30, 40, 50, 60, 70]], dtype=torch.int32)
+    for init_f, init_c in [(torch.tensor([[0, 10, 20, 30, 40, 50, 60, 10]], dtype=torch.int32), torch.tensor([[0, 1]], dtype=torch.int32)),
+                           (good_f, torch.tensor([[3, 3]], dtype=torch.int32))]:
+        with pytest.raises(mp.MpError) as e:
+            ctx.mp_cluster_kv(K, K, 8, 2, iters=1, init_fine=init_f, init_coarse=init_c)
+        assert e.value.status == mp.MP_EINVAL and "distinct" in str(e.value)
+    ctx.mp_cluster_kv(K, K, 8, 2, iters=1, init_fine=good_f, init_coarse=torch.tensor([[3, 4]], dtype=torch.int32))
+    assert ctx.mp_get_sizes()["n_fine"] == 8
+    ctx.close()
