@@ -143,22 +143,34 @@ def decode_unit(q, cl, key_budget, coarse_budget=0, Kx=None, Vx=None, scale=None
                 r_f=r_f[:Cf], n_sel_keys=int(nsel.value))
 
 
-def decode_batch(q, cls, key_budget, coarse_budget=0, Kx=None, Vx=None, scale=None, mp_terms=True):
-    """:func:`decode_unit` for a batch of units of identical shape, one OpenMP thread per unit (what
-    the benchmark times as its CPU baseline).  q [U,G,d]; cls: list of U clustering dicts; Kx, Vx
-    [U,nx,d] or None.  Returns out [U,G,d], lse [U,G], promising [U,Cc] (or None), selected [U,Cf]."""
-    q = _f64(q)
-    U, G, d = q.shape
-    assert len(cls) == U
-    if scale is None:
-        scale = 1.0 / np.sqrt(d)
+def stack_units(cls):
+    """The clustering dicts of a batch of units of identical shape as one dict of arrays with a
+    leading unit axis (what :func:`decode_batch` works on; worth keeping when it is called repeatedly)."""
     levels = int(cls[0]["levels"])
     st = lambda key, conv: conv(np.stack([np.asarray(c[key]) for c in cls]))
-    K, V, fot = st("K", _f64), st("V", _f64), st("fine_of_token", _i32)
-    Kc_f, Vc_f, N_f = st("Kc_f", _f64), st("Vc_f", _f64), st("N_f", _i32)
+    b = dict(U=len(cls), levels=levels, K=st("K", _f64), V=st("V", _f64), fine_of_token=st("fine_of_token", _i32),
+             Kc_f=st("Kc_f", _f64), Vc_f=st("Vc_f", _f64), N_f=st("N_f", _i32))
+    if levels == 2:
+        b.update(coarse_of_fine=st("coarse_of_fine", _i32), Kc_c=st("Kc_c", _f64), Vc_c=st("Vc_c", _f64), N_c=st("N_c", _i32))
+    return b
+
+
+def decode_batch(q, cls, key_budget, coarse_budget=0, Kx=None, Vx=None, scale=None, mp_terms=True):
+    """:func:`decode_unit` for a batch of units of identical shape, one OpenMP thread per unit (what
+    the benchmark times as its CPU baseline).  q [U,G,d]; cls: list of U clustering dicts, or the
+    result of :func:`stack_units`; Kx, Vx [U,nx,d] or None.  Returns out [U,G,d], lse [U,G],
+    promising [U,Cc] (or None), selected [U,Cf]."""
+    q = _f64(q)
+    U, G, d = q.shape
+    b = cls if isinstance(cls, dict) else stack_units(cls)
+    assert b["U"] == U
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    levels = b["levels"]
+    K, V, fot, Kc_f, Vc_f, N_f = b["K"], b["V"], b["fine_of_token"], b["Kc_f"], b["Vc_f"], b["N_f"]
     n, Cf = K.shape[1], N_f.shape[1]
     if levels == 2:
-        cof, Kc_c, Vc_c, N_c = st("coarse_of_fine", _i32), st("Kc_c", _f64), st("Vc_c", _f64), st("N_c", _i32)
+        cof, Kc_c, Vc_c, N_c = b["coarse_of_fine"], b["Kc_c"], b["Vc_c"], b["N_c"]
         Cc = N_c.shape[1]
     else:
         cof = Kc_c = Vc_c = N_c = None
