@@ -15,7 +15,7 @@
 //      place of a partial sum bounded by max(|x||c|, |c|^2/2), so each score is within
 //      2^-16 max(|x|^2, max_j |c_j|^2) of its exact value (2^-19 more for four mantissa bits that
 //      carry an index during the comparison).  A point whose two best scores are
-//      further apart than 2^-13 of that scale has a unique nearest centroid in exact arithmetic
+//      further apart than 2^-14 of that scale has a unique nearest centroid in exact arithmetic
 //      too (and by far more than fp64 rounding), which is the fp64 answer.
 //   2. Every other point (near-equal or equal distances) goes onto a per-block list and
 //      assign_recheck_kernel decides it exactly as defined above: it collects the centroids whose
@@ -35,7 +35,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kTile = 32;                 // centroids per tile = rows of the MFMA A operand
 constexpr int kRowBytes = 256 + 16;       // LDS row of one centroid: 128 dims, then -|c|^2/2 as three bf16 and five zeros
-constexpr float kMarginScale = 1.0f / 8192.0f;   // 2^-13
+constexpr float kMarginScale = 1.0f / 16384.0f;  // 2^-14: 1.8 times the sum of two scores' error bounds
 constexpr float kNoCentroid = -3.0e38f;          // score of a padded row (finite: index bits are packed into scores)
 
 // Scores of 32 centroids (one LDS tile: rows of kRowBytes, -|c|^2/2 in three bf16 pieces behind the

@@ -90,12 +90,17 @@ __global__ __launch_bounds__(256) void running_mean_kernel(const uint16_t* __res
     double s0 = (double)nold * (double)bf16lo_to_f32(cw), s1 = (double)nold * (double)bf16hi_to_f32(cw);
     const uint32_t* Xu = reinterpret_cast<const uint32_t*>(X + (long long)u * x_unit_rows * kHeadDim);
     int n = 0;
-    for (int t = x0; t < x1; ++t) {
-        if (assign[u * assign_stride + t] != j) continue;   // uniform over the wave
-        const uint32_t w = Xu[(long long)t * 64 + lane];
-        s0 += (double)bf16lo_to_f32(w);
-        s1 += (double)bf16hi_to_f32(w);
-        ++n;
+    for (int t0 = x0; t0 < x1; t0 += 64) {      // 64 appended points at a time: who of them belongs to j?
+        const int t = t0 + lane;
+        unsigned long long mine = __ballot(t < x1 && assign[u * assign_stride + t] == j);
+        while (mine) {                           // ascending bit order = sequence order
+            const int b = __ffsll((long long)mine) - 1;
+            mine &= mine - 1;
+            const uint32_t w = Xu[(long long)(t0 + b) * 64 + lane];
+            s0 += (double)bf16lo_to_f32(w);
+            s1 += (double)bf16hi_to_f32(w);
+            ++n;
+        }
     }
     if (n == 0) return;
     const double den = (double)(nold + n);
