@@ -287,7 +287,7 @@ void upload_descs(const Range& r, int max_blocks, std::vector<int32_t>& bd, int&
 // in ctx->Kc when key_fallback is set.  Block descriptors of the range must be in blocks_dev slot 1.
 mp_status finalize_range(mp_ctx* ctx, const void* Xk, const void* Xs, const void* Xv, long long x_unit_rows, int pt0,
                          int n_pts, const int32_t* ids, long long ids_stride, int f0, int f1, int c0, int c1, int nb,
-                         int max_kf, bool key_fallback, hipStream_t s)
+                         int max_kf, bool key_fallback, bool fine_keys_are_means, hipStream_t s)
 {
     const int U = ctx->U;
     const long long Ncap = ctx->Ncap, tab = ctx->tab_rows;
@@ -299,8 +299,11 @@ mp_status finalize_range(mp_ctx* ctx, const void* Xk, const void* Xs, const void
     MP_HIPC(launch_offset_lists(ctx->km_start, tab + 1, f0, f1, ctx->km_list, Ncap, n_pts, pt0, U, ctx->fstart,
                                 ctx->Fcap + 1, ctx->perm, Ncap, s));
     MP_HIPC(launch_gather_rows(Xs, Xv, x_unit_rows, ctx->km_list, Ncap, n_pts, U, ctx->Kp, ctx->Vp, Ncap, pt0, s));
-    MP_HIPC(launch_cluster_means((const uint16_t*)Xk, x_unit_rows, ctx->km_list, Ncap, ctx->km_start, tab + 1, f0, f1, U,
-                                 ctx->Kc, tab, 0, key_fallback ? ctx->Kc : nullptr, tab, nullptr, 0, 0, s));
+    // (after a Lloyd iteration the working centroids already sitting in ctx->Kc ARE the member means of the
+    // final assignment -- same members, same order of summation, same rounding: nothing to recompute)
+    if (!fine_keys_are_means)
+        MP_HIPC(launch_cluster_means((const uint16_t*)Xk, x_unit_rows, ctx->km_list, Ncap, ctx->km_start, tab + 1, f0, f1, U,
+                                     ctx->Kc, tab, 0, key_fallback ? ctx->Kc : nullptr, tab, nullptr, 0, 0, s));
     MP_HIPC(launch_cluster_means((const uint16_t*)Xv, x_unit_rows, ctx->km_list, Ncap, ctx->km_start, tab + 1, f0, f1, U,
                                  ctx->Vc, tab, 0, nullptr, 0, ctx->Ncl, tab, 0, s));
     if (ctx->cfg.levels == 2) {
@@ -326,7 +329,7 @@ namespace {
 // its points in km_assign (old numbering), and -- two levels -- the coarse working centroids in
 // km_Cc[c0,c1): run the coarse Lloyd iterations (coarse_iters >= 1), renumber, and finalize.
 mp_status coarse_and_finalize(mp_ctx* ctx, const Range& r, int coarse_iters, bool init_coarse_from_seeds,
-                              int max_kf, int max_kc, hipStream_t s)
+                              bool fine_keys_are_means, int max_kf, int max_kc, hipStream_t s)
 {
     const int U = ctx->U;
     const bool two = ctx->cfg.levels == 2;
@@ -373,7 +376,7 @@ mp_status coarse_and_finalize(mp_ctx* ctx, const Range& r, int coarse_iters, boo
         MP_HIPC(hipGetLastError());
     }
     return finalize_range(ctx, r.Xk, r.Xs, r.Xv, r.x_unit_rows, r.pt0, r.n_pts, ctx->km_assign, ctx->Ncap, r.f0, r.f1, r.c0,
-                          r.c1, nb, max_kf, true, s);
+                          r.c1, nb, max_kf, true, fine_keys_are_means, s);
 }
 
 // Fresh clustering of a range: seeds are on the device (km_seed_f / km_seed_c at the range's ids).
@@ -397,7 +400,7 @@ mp_status cluster_range(mp_ctx* ctx, const Range& r, int iters, hipStream_t s)
         const mp_status st = lloyd_iteration(ctx, pf, s);
         if (st != MP_OK) return st;
     }
-    return coarse_and_finalize(ctx, r, iters, true, max_kf, max_kc, s);
+    return coarse_and_finalize(ctx, r, iters, true, iters > 0, max_kf, max_kc, s);
 }
 
 }  // namespace
@@ -486,7 +489,7 @@ mp_status set_clustering_impl(mp_ctx* ctx, const void* k, const void* k_lookup, 
                   ctx->stage_blocks2.size() * sizeof(int32_t), s));
     const void* xk = k_lookup ? k_lookup : k;
     const mp_status st = finalize_range(ctx, xk, k, v, n_tokens, 0, n_tokens, ctx->fot, ctx->Ncap, 0, n_fine, 0, n_coarse, 1,
-                                        max_kf, false, s);
+                                        max_kf, false, false, s);
     if (st != MP_OK) return st;
     if (n_tokens <= ctx->FBcap) {
         const size_t row = kHeadDim * sizeof(uint16_t);
@@ -651,7 +654,7 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* k_new
             MP_HIPC(hipGetLastError());
         }
     }
-    mp_status st = coarse_and_finalize(ctx, r, std::max(1, refine_iters), false, max_kf, max_kc, s);
+    mp_status st = coarse_and_finalize(ctx, r, std::max(1, refine_iters), false, refine_iters > 0, max_kf, max_kc, s);
     if (st != MP_OK) return st;
     lb.t1 = t0 + nb; lb.f1 = f1; lb.c1 = c1;
     ctx->blocks.back() = lb;
