@@ -445,9 +445,45 @@ def error_study(mp, inputs, dev, context=32768, n_fine=4096, n_coarse=512, modes
                     rec["centroids_scored"] = round(scored / n_sets, 1)
                 rows.append(rec)
         ctx.close()
+
+    # Sweeps at a fixed key budget (context / 16), one level and two levels: tokens per fine centroid
+    # (the centroid ratio) and the clustering block length W (alpha = W / 2; 0 = the whole sequence as one
+    # block).  Analogues, on synthetic data, of the paper's hyperparameter ablations ("Hyperparameter
+    # Ablations" appendix: centroid ratio and block size); they say how the output error of this recipe
+    # moves, nothing about model accuracy.
+    def one_point(levels, nf, nc, W, alpha):
+        blocks_ = inputs.plan_blocks(context, W, alpha, nf, nc if levels == 2 else 0)
+        init_f_, init_c_ = inputs.draw_seeds(U, blocks_, levels, seed + 5)
+        c = mp.MpContext(B, Hq, Hkv, max_tokens=context, levels=levels, max_fine=nf, max_coarse=nc if levels == 2 else 0,
+                         block_w=W, block_alpha=alpha)
+        c.mp_cluster_kv(K, V, nf, nc if levels == 2 else 0, iters=10, init_fine=init_f_, init_coarse=init_c_ if levels == 2 else None)
+        kb = context // 16
+        rec = {}
+        for sf, Q, dense in zip(softness, Qs, denses):
+            for name, flags in (("multipole", 0), ("retrieval_only", 1)):
+                err = scored = 0.0
+                for i in range(n_sets):
+                    out = c.mp_decode_attention(Q[i], kb, 4 * kb if levels == 2 else 0, flags=flags).float()
+                    err += float(((out - dense[i]).norm(dim=-1) / dense[i].norm(dim=-1)).mean())
+                    cnt = c.mp_get_counters().float().mean(dim=0)
+                    scored += float(cnt[1] + cnt[2])
+                rec[f"{name}_rel_err_softness_{sf}"] = round(err / n_sets, 5)
+                rec["centroids_scored"] = round(scored / n_sets, 1)
+        c.close()
+        return rec
+
+    ratio_rows, block_rows = [], []
+    for levels in (1, 2):
+        for per in (8, 16, 32, 64):                 # tokens per fine centroid; coarse: 8 fine per coarse
+            nf = context // per
+            ratio_rows.append(dict(levels=levels, tokens_per_fine_centroid=per, n_fine=nf, **one_point(levels, nf, nf // 8, 8192, 4096)))
+        for W in (2048, 4096, 8192, 16384, 0):
+            block_rows.append(dict(levels=levels, block_w=W, block_alpha=W // 2, **one_point(levels, n_fine, n_coarse, W, W // 2)))
     return dict(study="output error against dense attention", data="synthetic, modes with two scales of structure",
                 context=context, n_fine=n_fine, n_coarse=n_coarse, modes=modes, modes_per_family=fan, query_sets=n_sets,
-                coarse_budget="4 x key budget", rows=rows)
+                coarse_budget="4 x key budget", rows=rows,
+                centroid_ratio_sweep=dict(key_budget=context // 16, block_w=8192, rows=ratio_rows),
+                block_size_sweep=dict(key_budget=context // 16, n_fine=n_fine, n_coarse=n_coarse, rows=block_rows))
 
 
 def measured_traffic(workload, key_budget):
