@@ -204,6 +204,51 @@ def full_attention_batch(q, K, V, scale):
     return out, lse
 
 
+# --------------------------------------------------------------------------------------------
+# 8-bit storage of the exactly attended keys and values (the KV quantisation that Sec. 2.3 names as
+# complementary to the method).  Format: OCP e4m3 ("fn": 4 exponent bits with bias 7, 3 mantissa
+# bits, subnormals, no infinities, largest magnitude 448), one fp32 scale per stored row:
+#   scale = fp32(max_d |x_d|) / fp32(448)            (fp32 division; 1 for an all-zero row)
+#   code_d = nearest e4m3 value to fp32(x_d) / scale  (fp32 division, then round to nearest, ties to
+#            the even code, magnitudes above 448 clamp to 448)
+# and the row stands for code_d * scale from then on.  The decode oracle is simply run on those
+# dequantised rows (exactly representable in fp64); centroids are still means of the original rows.
+# --------------------------------------------------------------------------------------------
+
+def e4m3_magnitudes():
+    """The 127 non-negative finite e4m3 values in code order (code 0..126; code 127 is NaN)."""
+    v = np.zeros(127)
+    for code in range(1, 127):
+        e, m = code >> 3, code & 7
+        v[code] = (m / 8.0) * 2.0 ** -6 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7)
+    return v
+
+
+def quantize_rows_e4m3(X):
+    """X [n, d] (bf16 values) -> (codes uint8 [n, d], scale float32 [n]) as defined above."""
+    X32 = np.asarray(X, dtype=np.float32)
+    amax = np.abs(X32).max(axis=1)
+    scale = np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    y = (X32 / scale[:, None]).astype(np.float32)
+    mag = np.minimum(np.abs(y).astype(np.float64), 448.0)
+    tab = e4m3_magnitudes()
+    hi = np.searchsorted(tab, mag, side="left").clip(1, 126)       # tab[hi-1] <= mag <= tab[hi] (mag > 0)
+    lo = hi - 1
+    d_lo, d_hi = mag - tab[lo], tab[hi] - mag
+    code = np.where(d_lo < d_hi, lo, np.where(d_hi < d_lo, hi, np.where(lo % 2 == 0, lo, hi)))
+    code = np.where(mag == 0, 0, code).astype(np.uint8)
+    code |= (np.signbit(y).astype(np.uint8) << 7)
+    return code, scale
+
+
+def dequantize_rows_e4m3(codes, scale):
+    """code * scale as float64 [n, d] (exact: a 4-bit significand times an fp32)."""
+    tab = e4m3_magnitudes()
+    mag = tab[(codes & 0x7f).astype(np.int64)]
+    sign = np.where(codes & 0x80, -1.0, 1.0)
+    return sign * mag * np.asarray(scale, dtype=np.float64)[:, None]
+
+
 def assign(X, Cn):
     """Nearest-centroid assignment, squared Euclidean distance, ties to the lowest index."""
     X, Cn = _f64(X), _f64(Cn)
