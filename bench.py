@@ -29,17 +29,18 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 
 
-def algorithmic_bytes(counters, G):
+def algorithmic_bytes(counters, G, key_bytes=512):
     """Bytes a decode step must read, from the device counters (summed over units).
 
-    per unit: 512 B per exactly attended key (key row + value row) + 4 B of row index,
+    per unit: key_bytes per exactly attended key (512 B: bf16 key row + value row; 8-bit cache: 264 B, two
+              rows of 128 codes and their two fp32 scales) + 4 B of row index,
               256 B per scored centroid (fine and coarse key centroids),
               256 B + 4*G B + 4 B per centroid term (value centroid row, its logits, its row index).
     Returns (whole step, value pass only)."""
     keys = int(counters[:, 0].sum())
     scored = int(counters[:, 1].sum() + counters[:, 2].sum())
     terms = int(counters[:, 3].sum())
-    value_pass = keys * (512 + 4) + terms * (256 + 4 * G + 4)
+    value_pass = keys * (key_bytes + 4) + terms * (256 + 4 * G + 4)
     return value_pass + scored * 256, value_pass
 
 
@@ -53,6 +54,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-online", action="store_true", help="skip the online-generation (cfg4_online) extra")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the smaller workloads (cfg0 - cfg2)")
+    ap.add_argument("--no-fp8", action="store_true", help="skip the run with the 8-bit clustered cache")
     ap.add_argument("--only-online", action="store_true",
                     help="run only the online-generation workload and print its record (for profiling)")
     ap.add_argument("--error-study", action="store_true",
@@ -110,39 +112,7 @@ def main():
 
     out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.bfloat16, device=dev)
     G = w.group
-    results = {}
-    for kb in w.key_budgets:
-        cb = args.coarse_mult * kb
-        for i in range(args.warmup):
-            ctx.mp_decode_attention(Q[i % n_sets], kb, cb, out=out)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(args.steps):
-            ctx.mp_decode_attention(Q[i % n_sets], kb, cb, out=out)
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) / args.steps * 1e3
-        # per-stage durations (HIP events recorded by the library on the launch stream) and byte counters
-        ctx.mp_enable_stage_timing(True)
-        stage = dict(coarse_ms=0.0, fine_ms=0.0, value_ms=0.0, merge_ms=0.0)
-        step_bytes = vp_bytes = 0
-        n_t = min(args.steps, 64)
-        for i in range(n_t):
-            ctx.mp_decode_attention(Q[i % n_sets], kb, cb, out=out)
-            t = ctx.mp_get_stage_timing()
-            for k_ in stage:
-                stage[k_] += t[k_] / n_t
-            if i < n_sets:
-                c = ctx.mp_get_counters().cpu()
-                sb, vb = algorithmic_bytes(c, G)
-                step_bytes += sb / min(n_t, n_sets)
-                vp_bytes += vb / min(n_t, n_sets)
-        ctx.mp_enable_stage_timing(False)
-        stage_us = {"score": (stage["coarse_ms"] + stage["fine_ms"]) * 1e3, "value": stage["value_ms"] * 1e3,
-                    "merge": stage["merge_ms"] * 1e3}
-        results[kb] = dict(us=us, stage_us=stage_us, step_bytes=step_bytes,
-                           vp_bytes=vp_bytes, gbps=step_bytes / us / 1e3,
-                           vp_gbps=vp_bytes / (stage["value_ms"] * 1e3) / 1e3 if stage["value_ms"] > 0 else 0.0)
+    results = {kb: time_decode(ctx, Q, kb, args.coarse_mult * kb, out, args.steps, args.warmup, G) for kb in w.key_budgets}
 
     # the same step replayed from a HIP graph (16 steps, one per query set, captured once): what a
     # multi-layer decode loop that captures its launches would see
@@ -185,6 +155,8 @@ def main():
     if not args.no_cpu:
         out0 = ctx.mp_decode_attention(Q[0], kb0, args.coarse_mult * kb0)
         cpu = cpu_baseline(ctx, w, K, V, Q, kb0, args.coarse_mult * kb0, out0)
+
+    fp8 = None if args.no_fp8 else eight_bit_cache(mp, w, data, ctx, args.coarse_mult, args.steps, args.warmup)
 
     # one Lloyd iteration of the index build (assignment on the matrix cores + exact recheck, member lists,
     # means), as the difference between builds of 6 and of 2 iterations
@@ -242,6 +214,7 @@ def main():
         "note_on_inputs": "the recipe's modes are independent draws, so a coarse cluster averages ~60 unrelated modes and the "
                           "coarse level says little about a query's mode: the selection pattern timed here is that of "
                           "near-random coarse clusters (parity with the oracle is unaffected)",
+        "eight_bit_cache": fp8,
         "online_generation": None if args.no_online else online_generation(mp, inputs, dev, with_oracle=not args.no_cpu),
         "other_workloads": None if args.no_others else {
             name: quick_workload(mp, inputs, dev, name, args.coarse_mult, with_oracle=not args.no_cpu)
@@ -258,6 +231,77 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
+
+
+def time_decode(ctx, Q, kb, cb, out, steps, warmup, G, key_bytes=512):
+    """`steps` decode steps over the query sets in turn, timed as one region; then per-stage durations (HIP
+    events recorded by the library on the launch stream) and the algorithmic bytes from the device counters."""
+    import torch
+    n_sets = Q.shape[0]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(warmup):
+        ctx.mp_decode_attention(Q[i % n_sets], kb, cb, out=out)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(steps):
+        ctx.mp_decode_attention(Q[i % n_sets], kb, cb, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) / steps * 1e3
+    ctx.mp_enable_stage_timing(True)
+    stage = dict(coarse_ms=0.0, fine_ms=0.0, value_ms=0.0, merge_ms=0.0)
+    step_bytes = vp_bytes = 0
+    n_t = min(steps, 64)
+    for i in range(n_t):
+        ctx.mp_decode_attention(Q[i % n_sets], kb, cb, out=out)
+        t = ctx.mp_get_stage_timing()
+        for k_ in stage:
+            stage[k_] += t[k_] / n_t
+        if i < n_sets:
+            c = ctx.mp_get_counters().cpu()
+            sb, vb = algorithmic_bytes(c, G, key_bytes)
+            step_bytes += sb / min(n_t, n_sets)
+            vp_bytes += vb / min(n_t, n_sets)
+    ctx.mp_enable_stage_timing(False)
+    stage_us = {"score": (stage["coarse_ms"] + stage["fine_ms"]) * 1e3, "value": stage["value_ms"] * 1e3,
+                "merge": stage["merge_ms"] * 1e3}
+    return dict(us=us, stage_us=stage_us, step_bytes=step_bytes, vp_bytes=vp_bytes, gbps=step_bytes / us / 1e3,
+                vp_gbps=vp_bytes / (stage["value_ms"] * 1e3) / 1e3 if stage["value_ms"] > 0 else 0.0)
+
+
+def eight_bit_cache(mp, w, data, ctx, coarse_mult, steps, warmup):
+    """The same workload with the clustered keys and values stored as e4m3 codes + per-row fp32 scales, keys
+    as residuals from their fine cluster's key centroid (an extra: a different storage precision, never the
+    headline).  Same index (the centroids are means of the original rows), so the selection is that of the
+    bf16 step; the output differs by the rounding of the attended rows."""
+    import torch
+    K, V, Q = data["K"], data["V"], data["q"]
+    c8 = mp.MpContext(w.batch, w.n_q_heads, w.n_kv_heads, max_tokens=w.context, levels=w.levels, max_fine=w.n_fine,
+                      max_coarse=w.n_coarse, block_w=w.block_w, block_alpha=w.block_alpha, max_tail=256,
+                      kv_format=mp.MP_KV_E4M3)
+    c8.mp_cluster_kv(K, V, w.n_fine, w.n_coarse, iters=w.kmeans_iters, init_fine=data["init_fine"],
+                     init_coarse=data["init_coarse"] if w.levels == 2 else None)
+    out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.bfloat16, device=K.device)
+    rec = {"storage": "e4m3 codes, one fp32 scale per key row and per value row; key rows hold the residual from the key "
+                      "centroid of their fine cluster, whose share of the logit the scoring kernel hands over "
+                      "(264 B per attended key instead of 512, + 4 B of cluster slot and 16 B of logit shares from L2)",
+           "cache_mib": round((2 * K.numel() + 8 * K.numel() // 128) / 2 ** 20, 1),
+           "note": "parity is against the oracle on the dequantised rows (tests); the distance from the bf16 step below is the "
+                   "format's own rounding: three mantissa bits on residuals that, with this recipe's clusters of ~16 unrelated "
+                   "modes per block, are as large as the keys, under logits that span hundreds",
+           "budgets": {}}
+    for kb in w.key_budgets:
+        r = time_decode(c8, Q, kb, coarse_mult * kb, out, steps, warmup, w.group, key_bytes=264 + 4)
+        o8 = c8.mp_decode_attention(Q[0], kb, coarse_mult * kb).float()
+        o16 = ctx.mp_decode_attention(Q[0], kb, coarse_mult * kb).float()
+        same_sel = bool(torch.equal(c8.mp_get_selection()["fine_selected"], ctx.mp_get_selection()["fine_selected"]))
+        rec["budgets"][str(kb)] = {
+            "us_per_step": round(r["us"], 2), "stage_us": {k_: round(v, 2) for k_, v in r["stage_us"].items()},
+            "value_pass_gbps": round(r["vp_gbps"], 1), "value_pass_frac_of_hbm_peak": round(r["vp_gbps"] / HBM_PEAK_GBPS, 4),
+            "algorithmic_bytes_per_step": int(r["step_bytes"]), "same_selection_as_bf16_step": same_sel,
+            "max_abs_diff_from_bf16_step": round(float((o8 - o16).abs().max()), 5)}
+    c8.close()
+    return rec
 
 
 def checksum(t):

@@ -61,7 +61,29 @@ typedef struct {
     int32_t max_tail;      /* capacity: unclustered newest tokens per unit passed to decode     */
     int32_t lookup_keys;   /* 1: clusters are formed on separate lookup keys (see mp_cluster_kv) */
     float softmax_scale;   /* multiplies every q.k and q.centroid product; 0 => 1/sqrt(head_dim) */
+    int32_t kv_format;     /* storage of the clustered keys and values: MP_KV_BF16 or MP_KV_E4M3     */
 } mp_config;
+
+/* Storage formats of the clustered cache (the keys and values that are attended exactly).
+ *
+ * MP_KV_BF16  rows are kept as handed over.
+ * MP_KV_E4M3  8-bit rows (KV quantisation is complementary to the method, Sec. 2.3).  A stored row is
+ *             128 one-byte codes in the OCP e4m3 format (4 exponent bits, bias 7, 3 mantissa bits,
+ *             subnormals, no infinities, largest magnitude 448) plus one fp32 scale:
+ *               scale = fp32(max_d |x_d|) / 448 (fp32 division; 1 for an all-zero row),
+ *               code_d = x_d / scale (fp32 division) rounded to the nearest e4m3 value, ties to
+ *               the even code, magnitudes above 448 clamped,
+ *             and stands for code * scale.  For a value row x is the row itself.  For a key row x is
+ *             the residual from the key centroid c of the row's fine cluster, x_d = fp32(k_d) -
+ *             fp32(c_d) (one fp32 subtraction), so that decode attends c + code * scale: the index
+ *             already holds c and the scoring step already computes q.c, while e4m3's three
+ *             mantissa bits on the key itself would put an error of several percent on every
+ *             logit.  The centroid tables, the unclustered tail and every input stay bf16, and
+ *             the centroids are means of the original rows, so the index is identical to the
+ *             MP_KV_BF16 one.  Not available together with lookup_keys (MP_EINVAL: there the
+ *             centroids are those of the lookup keys, not of the stored keys). */
+#define MP_KV_BF16 0
+#define MP_KV_E4M3 1
 
 /* Create a context: allocates the clustered KV cache, the index tables and all workspaces on the
  * current HIP device (sizes follow the capacities in cfg).  *out receives the context.
@@ -306,9 +328,15 @@ mp_status mp_get_counters(mp_ctx* ctx, int32_t* counters, void* stream);
 
 /* Cluster-contiguous cache as stored: k_perm, v_perm bf16 [U, n_tokens, 128]; perm int32
  * [U, n_tokens] (sequence index of each stored row); fine_start int32 [U, n_fine+1] (first stored
- * row of each fine cluster). */
+ * row of each fine cluster).  A context with MP_KV_E4M3 holds no bf16 rows: k_perm and v_perm must
+ * be NULL there (MP_EINVAL), see mp_get_kv_codes. */
 mp_status mp_get_layout(mp_ctx* ctx, void* k_perm, void* v_perm, int32_t* perm, int32_t* fine_start,
                         void* stream);
+
+/* The 8-bit cache of a context with MP_KV_E4M3, in stored order (MP_EINVAL for any other context):
+ * k_codes (key residuals, see MP_KV_E4M3), v_codes uint8 [U, n_tokens, 128]; scales fp32
+ * [U, n_tokens, 2] = {key scale, value scale} of each stored row.  Device pointers, each may be NULL. */
+mp_status mp_get_kv_codes(mp_ctx* ctx, void* k_codes, void* v_codes, float* scales, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Dense bf16 decode attention over all n keys (the comparison point: split-KV streaming pass and

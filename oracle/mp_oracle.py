@@ -211,8 +211,11 @@ def full_attention_batch(q, K, V, scale):
 #   scale = fp32(max_d |x_d|) / fp32(448)            (fp32 division; 1 for an all-zero row)
 #   code_d = nearest e4m3 value to fp32(x_d) / scale  (fp32 division, then round to nearest, ties to
 #            the even code, magnitudes above 448 clamp to 448)
-# and the row stands for code_d * scale from then on.  The decode oracle is simply run on those
-# dequantised rows (exactly representable in fp64); centroids are still means of the original rows.
+# and the row stands for code_d * scale from then on.  Value rows are stored this way.  A key row is
+# stored as its RESIDUAL from the key centroid of its fine cluster (the index already holds that
+# centroid and the decode step already has q . centroid): r_d = fp32(k_d) - fp32(c_d), one fp32
+# subtraction, quantised as above; the key then stands for c_d + code_d * scale.  The decode oracle
+# is simply run on those dequantised rows (fp64); centroids are still means of the original rows.
 # --------------------------------------------------------------------------------------------
 
 def e4m3_magnitudes():
@@ -247,6 +250,18 @@ def dequantize_rows_e4m3(codes, scale):
     mag = tab[(codes & 0x7f).astype(np.int64)]
     sign = np.where(codes & 0x80, -1.0, 1.0)
     return sign * mag * np.asarray(scale, dtype=np.float64)[:, None]
+
+
+def quantize_keys_e4m3(K, centroid_of_row):
+    """Key rows K [n, d] and the key centroid of each row's fine cluster [n, d] (both bf16 values) ->
+    (codes, scale) of the fp32 residuals."""
+    r = np.asarray(K, dtype=np.float32) - np.asarray(centroid_of_row, dtype=np.float32)
+    return quantize_rows_e4m3(r)
+
+
+def dequantize_keys_e4m3(codes, scale, centroid_of_row):
+    """centroid + code * scale as float64 [n, d]."""
+    return np.asarray(centroid_of_row, dtype=np.float64) + dequantize_rows_e4m3(codes, scale)
 
 
 def assign(X, Cn):

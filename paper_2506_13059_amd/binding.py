@@ -22,8 +22,10 @@ EXPORTS = [
     "mp_set_clustering", "mp_update_clusters", "mp_decode_attention", "mp_get_sizes", "mp_get_assignments",
     "mp_get_centroids", "mp_get_selection", "mp_get_counters", "mp_get_layout", "mp_dense_workspace_bytes",
     "mp_dense_attention", "mp_version", "mp_enable_stage_timing", "mp_get_stage_timing", "mp_update_seed_counts", "mp_local_buffer_init", "mp_local_buffer_size", "mp_decode_step",
-    "mp_dense_static_scratch_bytes", "mp_dense_attention_static",
+    "mp_dense_static_scratch_bytes", "mp_dense_attention_static", "mp_get_kv_codes",
 ]
+
+MP_KV_BF16, MP_KV_E4M3 = 0, 1
 
 
 class MpError(RuntimeError):
@@ -35,7 +37,7 @@ class MpError(RuntimeError):
 class MpConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "max_tokens", "levels", "max_fine", "max_coarse",
-        "block_w", "block_alpha", "max_tail", "lookup_keys")] + [("softmax_scale", C.c_float)]
+        "block_w", "block_alpha", "max_tail", "lookup_keys")] + [("softmax_scale", C.c_float), ("kv_format", C.c_int32)]
 
 
 _lib = None
@@ -77,6 +79,7 @@ def lib():
         L.mp_get_selection.argtypes = [vp, vp, vp, vp, vp, vp]
         L.mp_get_counters.argtypes = [vp, vp, vp]
         L.mp_get_layout.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.mp_get_kv_codes.argtypes = [vp, vp, vp, vp, vp]
         L.mp_dense_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.mp_dense_workspace_bytes.restype = sz
         L.mp_dense_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
@@ -159,9 +162,10 @@ class MpContext:
     """Owns an mp_ctx handle.  Method names and arguments mirror the C entry points."""
 
     def __init__(self, batch, n_q_heads, n_kv_heads, max_tokens, levels, max_fine, max_coarse=0, block_w=0,
-                 block_alpha=0, max_tail=0, softmax_scale=0.0, head_dim=128, lookup_keys=False):
+                 block_alpha=0, max_tail=0, softmax_scale=0.0, head_dim=128, lookup_keys=False, kv_format=MP_KV_BF16):
         self.cfg = MpConfig(batch, n_q_heads, n_kv_heads, head_dim, max_tokens, levels, max_fine, max_coarse,
-                            block_w, block_alpha, max_tail, 1 if lookup_keys else 0, softmax_scale)
+                            block_w, block_alpha, max_tail, 1 if lookup_keys else 0, softmax_scale, kv_format)
+        self.kv_format = kv_format
         self.h = C.c_void_p()
         st = lib().mp_create(C.byref(self.cfg), C.byref(self.h))
         _check(st)
@@ -309,12 +313,26 @@ class MpContext:
         return c
 
     def mp_get_layout(self):
+        """(k_perm, v_perm, perm, fine_start); k_perm and v_perm are None for a context with 8-bit rows."""
         s = self.mp_get_sizes()
         dev = torch.device("cuda")
-        kp = torch.empty(self.U, s["n_tokens"], 128, dtype=torch.bfloat16, device=dev)
-        vp = torch.empty_like(kp)
+        kp = vp = None
+        if self.kv_format == MP_KV_BF16:
+            kp = torch.empty(self.U, s["n_tokens"], 128, dtype=torch.bfloat16, device=dev)
+            vp = torch.empty_like(kp)
         perm = torch.empty(self.U, s["n_tokens"], dtype=torch.int32, device=dev)
         fs = torch.empty(self.U, s["n_fine"] + 1, dtype=torch.int32, device=dev)
         st = lib().mp_get_layout(self.h, _ptr(kp), _ptr(vp), _ptr(perm), _ptr(fs), _stream())
         _check(st, self.h)
         return kp, vp, perm, fs
+
+    def mp_get_kv_codes(self):
+        """(k_codes uint8 [U, n, 128], v_codes, scales fp32 [U, n, 2]) of a context with 8-bit rows."""
+        s = self.mp_get_sizes()
+        dev = torch.device("cuda")
+        kc = torch.empty(self.U, s["n_tokens"], 128, dtype=torch.uint8, device=dev)
+        vc = torch.empty_like(kc)
+        sc = torch.empty(self.U, s["n_tokens"], 2, dtype=torch.float32, device=dev)
+        st = lib().mp_get_kv_codes(self.h, _ptr(kc), _ptr(vc), _ptr(sc), _stream())
+        _check(st, self.h)
+        return kc, vc, sc

@@ -175,6 +175,9 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
         return fail(nullptr, MP_EINVAL, "mp_create: need block_w >= 0 and, with block_w > 0, 1 <= block_alpha <= block_w");
     if (c.max_tail < 0) return fail(nullptr, MP_EINVAL, "mp_create: max_tail < 0");
     if (!(c.softmax_scale >= 0.f)) return fail(nullptr, MP_EINVAL, "mp_create: softmax_scale must be >= 0");
+    if (c.kv_format != MP_KV_BF16 && c.kv_format != MP_KV_E4M3) return fail(nullptr, MP_EINVAL, "mp_create: unknown kv_format %d", c.kv_format);
+    if (c.kv_format == MP_KV_E4M3 && c.lookup_keys)
+        return fail(nullptr, MP_EINVAL, "mp_create: 8-bit keys are residuals from the centroids of the stored keys; not available with lookup_keys");
     if ((long long)c.batch * c.n_kv_heads > 65535) return fail(nullptr, MP_EINVAL, "mp_create: more than 65535 units");
 
     mp_ctx* ctx = new (std::nothrow) mp_ctx();
@@ -199,7 +202,9 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     if (e == hipSuccess) e = hipDeviceGetAttribute(&ctx->n_cus, hipDeviceAttributeMultiprocessorCount, ctx->device);
     const size_t U = ctx->U, N = ctx->Ncap, F = ctx->Fcap, Cc = std::max(ctx->Ccap, 1), T = ctx->tab_rows, D = kHeadDimHost;
 #define A(ptr, count) if (e == hipSuccess) e = dev_alloc(ctx, &ctx->ptr, (count))
-    A(Kp, U * N * D); A(Vp, U * N * D); A(perm, U * N); A(fot, U * N);
+    if (c.kv_format == MP_KV_E4M3) { A(Kq, U * N * D); A(Vq, U * N * D); A(kv_scale, U * N * 2); A(sel_base, U * F * 8); A(row_slot, U * N); }
+    else { A(Kp, U * N * D); A(Vp, U * N * D); }
+    A(perm, U * N); A(fot, U * N);
     A(fstart, U * (F + 1)); A(cof, U * F); A(cstart, U * (Cc + 1)); A(crow, U * (Cc + 1));
     A(Kc, U * T * D); A(Vc, U * T * D); A(Ncl, U * T);
     A(Kfb, U * (size_t)ctx->FBcap * D); A(Vfb, U * (size_t)ctx->FBcap * D);
@@ -385,6 +390,7 @@ static mp_status decode_impl(mp_ctx* ctx, const void* q, const void* q_lookup, c
     sp.key_c = ctx->key_c; sp.flag_c = ctx->flag_c; sp.c_stride = std::max(ctx->Ccap, 1);
     sp.key_f = ctx->key_f; sp.key_mode = ctx->key_mode; sp.flag_f = ctx->flag_f; sp.f_stride = ctx->Fcap; sp.cand = ctx->cand; sp.n_cand = ctx->n_cand;
     sp.rows = ctx->rows; sp.rows_stride = ctx->Ncap; sp.n_rows = ctx->n_rows;
+    sp.sel_base = ctx->sel_base; sp.row_slot = ctx->row_slot;     // (null unless the keys are stored as residuals)
     sp.mp_rows = ctx->mp_rows; sp.mp_scores = ctx->mp_scores; sp.mp_stride = ctx->tab_rows; sp.n_mp = ctx->n_mp;
     sp.use_mp = use_mp; sp.counters = ctx->counters; sp.n_tail = n_tail;
     sp.lds_cap = std::min(1024, std::max(ctx->n_fine, std::max(ctx->n_coarse, 1)));
@@ -421,7 +427,12 @@ static mp_status decode_impl(mp_ctx* ctx, const void* q, const void* q_lookup, c
     if (main_max > 0) {
         const int crm = pick_stream_chunk_rows(main_max, U, 2048);
         RowSource& r = vp.src[ns++];
-        r.K = ctx->Kp; r.V = ctx->Vp; r.unit_rows = ctx->Ncap; r.rows = ctx->rows; r.rows_stride = ctx->Ncap;
+        if (ctx->cfg.kv_format == MP_KV_E4M3) {
+            r.K = (const uint16_t*)ctx->Kq; r.V = (const uint16_t*)ctx->Vq; r.row_scale = ctx->kv_scale;
+            r.row_slot = ctx->row_slot; r.slot_base = ctx->sel_base; r.base_stride = ctx->Fcap;
+        }
+        else { r.K = ctx->Kp; r.V = ctx->Vp; }
+        r.unit_rows = ctx->Ncap; r.rows = ctx->rows; r.rows_stride = ctx->Ncap;
         r.count_dev = ctx->n_rows; r.count_max = main_max; r.scores = nullptr; r.chunk0 = chunk0;
         r.chunk_rows = crm; r.row0 = 0; r.n_chunks = ceil_div(main_max, crm); chunk0 += r.n_chunks;
     }
@@ -664,6 +675,8 @@ mp_status mp_get_layout(mp_ctx* ctx, void* k_perm, void* v_perm, int32_t* perm, 
 {
     if (!ctx) return fail(nullptr, MP_EINVAL, "mp_get_layout: null context");
     if (!ctx->has_index) return fail(ctx, MP_ESTATE, "mp_get_layout: no index yet");
+    if (ctx->cfg.kv_format != MP_KV_BF16 && (k_perm || v_perm))
+        return fail(ctx, MP_EINVAL, "mp_get_layout: this context stores 8-bit rows (use mp_get_kv_codes)");
     hipStream_t s = (hipStream_t)stream;
     const size_t row = kHeadDimHost * 2, n = ctx->n_tokens;
     if (k_perm)
@@ -675,6 +688,22 @@ mp_status mp_get_layout(mp_ctx* ctx, void* k_perm, void* v_perm, int32_t* perm, 
     if (fine_start)
         MP_HIP(ctx, hipMemcpy2DAsync(fine_start, (size_t)(ctx->n_fine + 1) * 4, ctx->fstart, (size_t)(ctx->Fcap + 1) * 4,
                                      (size_t)(ctx->n_fine + 1) * 4, ctx->U, hipMemcpyDeviceToDevice, s));
+    return MP_OK;
+}
+
+mp_status mp_get_kv_codes(mp_ctx* ctx, void* k_codes, void* v_codes, float* scales, void* stream)
+{
+    if (!ctx) return fail(nullptr, MP_EINVAL, "mp_get_kv_codes: null context");
+    if (ctx->cfg.kv_format != MP_KV_E4M3) return fail(ctx, MP_EINVAL, "mp_get_kv_codes: this context does not store 8-bit rows");
+    if (!ctx->has_index) return fail(ctx, MP_ESTATE, "mp_get_kv_codes: no index yet");
+    hipStream_t s = (hipStream_t)stream;
+    const size_t row = kHeadDimHost, n = ctx->n_tokens;
+    if (k_codes)
+        MP_HIP(ctx, hipMemcpy2DAsync(k_codes, n * row, ctx->Kq, (size_t)ctx->Ncap * row, n * row, ctx->U, hipMemcpyDeviceToDevice, s));
+    if (v_codes)
+        MP_HIP(ctx, hipMemcpy2DAsync(v_codes, n * row, ctx->Vq, (size_t)ctx->Ncap * row, n * row, ctx->U, hipMemcpyDeviceToDevice, s));
+    if (scales)
+        MP_HIP(ctx, hipMemcpy2DAsync(scales, n * 8, ctx->kv_scale, (size_t)ctx->Ncap * 8, n * 8, ctx->U, hipMemcpyDeviceToDevice, s));
     return MP_OK;
 }
 

@@ -298,7 +298,9 @@ mp_status finalize_range(mp_ctx* ctx, const void* Xk, const void* Xs, const void
     MP_HIPC(launch_block_lists(ids, ids_stride, bdev, nb, max_kf, 0, U, ctx->km_start, tab + 1, ctx->km_list, Ncap, s));
     MP_HIPC(launch_offset_lists(ctx->km_start, tab + 1, f0, f1, ctx->km_list, Ncap, n_pts, pt0, U, ctx->fstart,
                                 ctx->Fcap + 1, ctx->perm, Ncap, s));
-    MP_HIPC(launch_gather_rows(Xs, Xv, x_unit_rows, ctx->km_list, Ncap, n_pts, U, ctx->Kp, ctx->Vp, Ncap, pt0, s));
+    const bool bytes = ctx->cfg.kv_format == MP_KV_E4M3;
+    if (!bytes)
+        MP_HIPC(launch_gather_rows(Xs, Xv, x_unit_rows, ctx->km_list, Ncap, n_pts, U, ctx->Kp, ctx->Vp, Ncap, pt0, s));
     // (after a Lloyd iteration the working centroids already sitting in ctx->Kc ARE the member means of the
     // final assignment -- same members, same order of summation, same rounding: nothing to recompute)
     if (!fine_keys_are_means)
@@ -306,19 +308,27 @@ mp_status finalize_range(mp_ctx* ctx, const void* Xk, const void* Xs, const void
                                      ctx->Kc, tab, 0, key_fallback ? ctx->Kc : nullptr, tab, nullptr, 0, 0, s));
     MP_HIPC(launch_cluster_means((const uint16_t*)Xv, x_unit_rows, ctx->km_list, Ncap, ctx->km_start, tab + 1, f0, f1, U,
                                  ctx->Vc, tab, 0, nullptr, 0, ctx->Ncl, tab, 0, s));
+    if (bytes)   // (8-bit keys are residuals from the fine key centroids, which are final only now)
+        MP_HIPC(launch_gather_quantize_rows(Xs, Xv, x_unit_rows, ctx->km_list, Ncap, ids, ids_stride, ctx->Kc, tab, n_pts, U,
+                                            ctx->Kq, ctx->Vq, ctx->kv_scale, Ncap, pt0, s));
     if (ctx->cfg.levels == 2) {
         MP_HIPC(launch_coarse_start(ctx->cof, ctx->Fcap, f0, f1, c0, c1, U, ctx->cstart, ctx->Ccap + 1, s));
         MP_HIPC(launch_coarse_row_start(ctx->cstart, ctx->Ccap + 1, ctx->fstart, ctx->Fcap + 1, c0, c1, U, ctx->crow,
                                         ctx->Ccap + 1, s));
         const uint16_t* kfb = key_fallback ? ctx->Kc + (long long)ctx->Fcap * kHeadDim : nullptr;
-        if (Xs == Xk)       // the stored rows of a coarse cluster are contiguous: sum them where they lie
+        if (Xs == Xk && !bytes)   // the stored rows of a coarse cluster are contiguous: sum them where they lie
             MP_HIPC(launch_cluster_means(ctx->Kp, Ncap, nullptr, 0, ctx->crow, ctx->Ccap + 1, c0, c1, U, ctx->Kc, tab, ctx->Fcap,
                                          kfb, tab, nullptr, 0, 0, s));
-        else                // lookup keys are not stored: the same rows, in the same order, through the member list
+        else                // lookup keys are not stored, 8-bit rows are not the originals: the same rows, in the
+                            // same order, through the member list
             MP_HIPC(launch_cluster_means((const uint16_t*)Xk, x_unit_rows, ctx->km_list - pt0, Ncap, ctx->crow, ctx->Ccap + 1,
                                          c0, c1, U, ctx->Kc, tab, ctx->Fcap, kfb, tab, nullptr, 0, 0, s));
-        MP_HIPC(launch_cluster_means(ctx->Vp, Ncap, nullptr, 0, ctx->crow, ctx->Ccap + 1, c0, c1, U, ctx->Vc, tab,
-                                     ctx->Fcap, nullptr, 0, ctx->Ncl, tab, ctx->Fcap, s));
+        if (!bytes)
+            MP_HIPC(launch_cluster_means(ctx->Vp, Ncap, nullptr, 0, ctx->crow, ctx->Ccap + 1, c0, c1, U, ctx->Vc, tab,
+                                         ctx->Fcap, nullptr, 0, ctx->Ncl, tab, ctx->Fcap, s));
+        else
+            MP_HIPC(launch_cluster_means((const uint16_t*)Xv, x_unit_rows, ctx->km_list - pt0, Ncap, ctx->crow, ctx->Ccap + 1,
+                                         c0, c1, U, ctx->Vc, tab, ctx->Fcap, nullptr, 0, ctx->Ncl, tab, ctx->Fcap, s));
     }
     return MP_OK;
 }

@@ -67,6 +67,12 @@ struct mp_ctx {
     // ---- clustered cache and index tables ----
     uint16_t* Kp = nullptr;        // bf16 [U, Ncap, 128] keys, cluster after cluster
     uint16_t* Vp = nullptr;        // bf16 [U, Ncap, 128]
+    // (8-bit storage, cfg.kv_format == MP_KV_E4M3: Kp / Vp stay null and these hold the rows instead)
+    uint8_t* Kq = nullptr;         // e4m3 codes [U, Ncap, 128]
+    uint8_t* Vq = nullptr;
+    float* kv_scale = nullptr;     // fp32 [U, Ncap, 2]: key scale and value scale of each stored row
+    float* sel_base = nullptr;     // fp32 [U, Fcap, 8]: q . centroid of the clusters selected by the last decode call
+    int32_t* row_slot = nullptr;   // [U, Ncap]: for each entry of `rows`, its cluster's position in sel_base
     int32_t* perm = nullptr;       // [U, Ncap] sequence index of each stored row
     int32_t* fot = nullptr;        // [U, Ncap] fine cluster of each token (sequence order)
     int32_t* fstart = nullptr;     // [U, Fcap+1] first stored row of each fine cluster

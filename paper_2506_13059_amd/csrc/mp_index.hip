@@ -212,6 +212,76 @@ __global__ void gather_rows_kernel(const uint4* __restrict__ srcK, const uint4* 
     dstV[((long long)u * dst_unit_rows + dst_row0 + p) * 16 + c] = srcV[((long long)u * src_unit_rows + s) * 16 + c];
 }
 
+// The same gather into 8-bit storage.  A value row becomes 128 e4m3 codes (OCP format: bias 7,
+// largest magnitude 448, no infinities) and one fp32 scale, scale = max|x| / 448 (1 for a zero row),
+// code = x / scale rounded to nearest even; both divisions are IEEE fp32.  A key row is stored the
+// same way as its residual from the key centroid of its fine cluster, x = fp32(k) - fp32(centroid):
+// the decode step already has q . centroid, and the residual is small where the key itself is not.
+// Sixteen threads share a row (8 elements of the key and 8 of the value each);
+// scales[u][row] = {key scale, value scale}.
+// Elementwise fp32 difference of two groups of eight bf16 values.
+struct F8 { float v[8]; };
+__device__ __forceinline__ F8 widen8(const uint4& w)
+{
+    const uint32_t d[4] = {w.x, w.y, w.z, w.w};
+    F8 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o.v[2 * i] = bf16lo_to_f32(d[i]);
+        o.v[2 * i + 1] = bf16hi_to_f32(d[i]);
+    }
+    return o;
+}
+__device__ __forceinline__ float absmax8(const F8& x)
+{
+    float a = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a = fmaxf(a, fabsf(x.v[i]));
+    return a;
+}
+__device__ __forceinline__ uint2 e4m3_codes8(const F8& x, float scale)
+{
+    // (the quotient of the row's largest entry may exceed 448 by an ulp: clamp, so that the conversion never overflows)
+    auto q = [&](float v) { return fminf(fmaxf(v / scale, -448.f), 448.f); };
+    int out[2] = {0, 0};
+    out[0] = __builtin_amdgcn_cvt_pk_fp8_f32(q(x.v[0]), q(x.v[1]), out[0], false);
+    out[0] = __builtin_amdgcn_cvt_pk_fp8_f32(q(x.v[2]), q(x.v[3]), out[0], true);
+    out[1] = __builtin_amdgcn_cvt_pk_fp8_f32(q(x.v[4]), q(x.v[5]), out[1], false);
+    out[1] = __builtin_amdgcn_cvt_pk_fp8_f32(q(x.v[6]), q(x.v[7]), out[1], true);
+    return make_uint2((uint32_t)out[0], (uint32_t)out[1]);
+}
+__global__ void gather_quantize_rows_kernel(const uint4* __restrict__ srcK, const uint4* __restrict__ srcV,
+                                            long long src_unit_rows, const int32_t* __restrict__ list,
+                                            long long list_stride, const int32_t* __restrict__ ids, long long ids_stride,
+                                            const uint4* __restrict__ Kc, long long kc_unit_rows, int n,
+                                            uint2* __restrict__ dstK, uint2* __restrict__ dstV,
+                                            float2* __restrict__ scales, long long dst_unit_rows, int dst_row0)
+{
+    const int u = blockIdx.y;
+    const long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long p = g >> 4;
+    const int c = (int)(g & 15);
+    if (p >= n) return;   // (all sixteen threads of a row leave together)
+    const long long s = list[u * list_stride + p];
+    const long long f = ids[u * ids_stride + s];
+    F8 k = widen8(srcK[((long long)u * src_unit_rows + s) * 16 + c]);
+    const F8 cen = widen8(Kc[((long long)u * kc_unit_rows + f) * 16 + c]);
+    const F8 v = widen8(srcV[((long long)u * src_unit_rows + s) * 16 + c]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) k.v[i] -= cen.v[i];
+    float ka = absmax8(k), va = absmax8(v);
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) {
+        ka = fmaxf(ka, __shfl_xor(ka, off, 64));
+        va = fmaxf(va, __shfl_xor(va, off, 64));
+    }
+    const float ks = ka > 0.f ? ka / 448.f : 1.f, vs = va > 0.f ? va / 448.f : 1.f;
+    const long long row = (long long)u * dst_unit_rows + dst_row0 + p;
+    dstK[row * 16 + c] = e4m3_codes8(k, ks);
+    dstV[row * 16 + c] = e4m3_codes8(v, vs);
+    if (c == 0) scales[row] = make_float2(ks, vs);
+}
+
 // One wave per cluster of [k0, k): fp64 sum of the member rows in list order, mean rounded once to bf16.
 // Lane l owns dims 2l and 2l+1.  Empty cluster: `fallback` row if given (else zeros).
 // mean_out row index = out_row0 + cluster id.  count_out optional.
@@ -440,6 +510,20 @@ hipError_t launch_gather_rows(const void* srcK, const void* srcV, long long src_
     hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((threads + 255) / 256), U), dim3(256), 0, s,
                        (const uint4*)srcK, (const uint4*)srcV, src_unit_rows, list, list_stride, n, (uint4*)dstK,
                        (uint4*)dstV, dst_unit_rows, dst_row0);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_quantize_rows(const void* srcK, const void* srcV, long long src_unit_rows, const int32_t* list,
+                                       long long list_stride, const int32_t* ids, long long ids_stride,
+                                       const uint16_t* Kc, long long kc_unit_rows, int n, int U, void* dstK, void* dstV,
+                                       float* scales, long long dst_unit_rows, int dst_row0, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    const long long threads = (long long)n * 16;
+    hipLaunchKernelGGL(gather_quantize_rows_kernel, dim3((unsigned)((threads + 255) / 256), U), dim3(256), 0, s,
+                       (const uint4*)srcK, (const uint4*)srcV, src_unit_rows, list, list_stride, ids, ids_stride,
+                       (const uint4*)Kc, kc_unit_rows, n, (uint2*)dstK, (uint2*)dstV, (float2*)scales, dst_unit_rows,
+                       dst_row0);
     return hipGetLastError();
 }
 

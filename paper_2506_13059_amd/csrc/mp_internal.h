@@ -14,7 +14,7 @@ constexpr int kChunkRowsMin = 512;     // smallest chunk of the dense kernel: 4 
 constexpr int kPartStride = 132;       // floats per (unit, chunk, head): m, l, pad, pad, acc[128]
 constexpr int kMaxSources = 4;
 
-// One stream of rows.  Row j of unit u lives at K + (u*unit_rows + idx)*128 where idx = rows ?
+// One stream of rows.  Row j of unit u lives at K + (u*unit_rows + idx)*128 (elements) where idx = rows ?
 // rows[u*rows_stride + j] : j.  The number of rows is *count_dev (clamped to count_max) or count_max.
 struct RowSource {
     const uint16_t* K;         // bf16 keys; unused when scores != nullptr
@@ -25,6 +25,13 @@ struct RowSource {
     const int32_t* count_dev;  // optional per-unit row count on the device
     int32_t count_max;         // upper bound of the row count (fixes the chunk count)
     const float* scores;       // optional [U, rows_stride, G] ready-made logits in log2 units
+    // optional, all three or none: K and V hold 128-byte rows of e4m3 codes; the value row idx stands for
+    // code * row_scale[idx][1], the key row for (its cluster's centroid) + code * row_scale[idx][0], and the
+    // centroid's share of the logit is read ready-made: slot_base[row_slot[j]] for list position j
+    const float* row_scale;    // [U, unit_rows, 2]
+    const int32_t* row_slot;   // [U, rows_stride]
+    const float* slot_base;    // [U, base_stride, 8] log2 units, column layout as written by the scoring kernel
+    long long base_stride;
     int32_t chunk0;            // first chunk id of this source inside a unit
     int32_t n_chunks;          // ceil(count_max / chunk_rows)
     int32_t chunk_rows;        // rows per workgroup of this source, a multiple of 64
@@ -88,6 +95,11 @@ struct ScoreParams {
     int32_t* rows;              // [U, rows_stride] stored rows of the selected keys
     long long rows_stride;
     int32_t* n_rows;            // [U]
+    // optional (both or none; keys stored as residuals from their cluster's centroid): per selected cluster, in
+    // the order of a compact list, q . centroid in log2 units, eight columns (see fine_epilogue), and per row of
+    // `rows` the position of its cluster in that list
+    float* sel_base;            // [U, f_stride, 8]
+    int32_t* row_slot;          // [U, rows_stride]
     int32_t* mp_rows;           // [U, mp_stride] centroid-table row of each centroid term
     float* mp_scores;           // [U, mp_stride, G] (l + ln N) * log2(e)
     long long mp_stride;
@@ -141,6 +153,14 @@ hipError_t launch_member_lists(const int32_t* ids, long long ids_stride, const i
 hipError_t launch_gather_rows(const void* srcK, const void* srcV, long long src_unit_rows, const int32_t* list,
                               long long list_stride, int n, int U, void* dstK, void* dstV, long long dst_unit_rows,
                               int dst_row0, hipStream_t s);
+// The same into 8-bit storage: dstK / dstV receive 128 e4m3 codes per row, scales [U, dst_unit_rows, 2] the
+// rows' fp32 scales {key, value} (scale = max|x| / 448, 1 for a zero row; code = round-to-nearest-even(x / scale)).
+// For a value row x is the row; for a key row x = fp32(key) - fp32(Kc[ids[point]]), the residual from the key
+// centroid of the point's fine cluster (ids [U, ids_stride] by local point, Kc [U, kc_unit_rows, 128] bf16).
+hipError_t launch_gather_quantize_rows(const void* srcK, const void* srcV, long long src_unit_rows, const int32_t* list,
+                                       long long list_stride, const int32_t* ids, long long ids_stride,
+                                       const uint16_t* Kc, long long kc_unit_rows, int n, int U, void* dstK, void* dstV,
+                                       float* scales, long long dst_unit_rows, int dst_row0, hipStream_t s);
 hipError_t launch_cluster_means(const uint16_t* X, long long x_unit_rows, const int32_t* list, long long list_stride,
                                 const int32_t* start, long long start_stride, int k0, int k, int U,
                                 uint16_t* mean_out, long long out_unit_rows, int out_row0, const uint16_t* fallback,

@@ -925,6 +925,19 @@ __device__ __forceinline__ void fine_epilogue(const ScoreParams& p, const Arrays
         if (sel) {
             sel_rc[packed & 0xffffu] = make_int2(r0, (int)w);
             sel_off[packed & 0xffffu] = (int32_t)off;
+            if (p.sel_base) {
+                // q . centroid of a selected cluster, log2 units, for a value pass over keys stored as residuals
+                // from it: eight columns per cluster, head h in column h (groups of up to five heads) or, for
+                // larger groups, which the value pass splits over two waves, in column 4 * half + h % ceil(G / 2)
+                constexpr int kHalf = G > 5 ? (G + 1) / 2 : 8;
+                float b[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int h = 0; h < G; ++h)
+                    b[h < kHalf ? h : 4 + h - kHalf] = (float)(F.lg[h * F.lg_stride + i] * 1.4426950408889634);
+                float4* dst = reinterpret_cast<float4*>(p.sel_base + ((long long)u * p.f_stride + (packed & 0xffffu)) * 8);
+                dst[0] = make_float4(b[0], b[1], b[2], b[3]);
+                dst[1] = make_float4(b[4], b[5], b[6], b[7]);
+            }
         }
         if (emit) emit_term<G>(p, F, u, i, two ? F.ids[i] : i, n_terms + (packed >> 16));
     }
@@ -933,6 +946,7 @@ __device__ __forceinline__ void fine_epilogue(const ScoreParams& p, const Arrays
     phase_sync<kLds>();
     // expansion: one row of 16 lanes per selected cluster, the next cluster's entry fetched early
     int32_t* ro = p.rows + (long long)u * p.rows_stride;
+    int32_t* so = p.row_slot ? p.row_slot + (long long)u * p.rows_stride : nullptr;   // compact slot of each row's cluster
     const int grp = tid >> 4, sub = tid & 15;
     int2 rc_n = make_int2(0, 0);
     int off_n = 0;
@@ -949,6 +963,8 @@ __device__ __forceinline__ void fine_epilogue(const ScoreParams& p, const Arrays
             off_n = sel_off[kn];
         }
         for (int j = sub; j < rc.y; j += 16) ro[off + j] = rc.x + j;
+        if (so)
+            for (int j = sub; j < rc.y; j += 16) so[off + j] = (int32_t)k;
     }
     if (tid == 0) {
         p.n_rows[u] = (int32_t)total;

@@ -12,6 +12,12 @@
 // instruction of the wave covers eight full 128-byte lines.  A query-key product is 8 packed bf16
 // dot instructions per head followed by a 3-step DPP sum over the 8 lanes; the value update keeps
 // 16 fp32 accumulators per head and lane.  All G heads of the group share every loaded row.
+//
+// 8-bit rows (a source with row_scale): a row is 128 one-byte e4m3 codes and lane c holds the 16
+// contiguous dims [16c, 16c+16) of it, one 16-byte load for the key and one for the value.  Key
+// codes are widened to bf16 pairs (exact: a code has four significant bits) and go through the same
+// packed dot instructions; value codes are widened to fp32.  The row's two fp32 scales multiply the
+// logit and the probability that weighs the value row, so the arithmetic equals that on code * scale.
 #include "mp_device.h"
 #include "mp_internal.h"
 
@@ -110,10 +116,12 @@ __device__ __forceinline__ void accumulate_v(HeadState<G>& st, const RowRegs& t,
     }
 }
 
-// Online-softmax update with the scores of two rows (s0, s1) and their value rows.
+// Online-softmax bookkeeping for the scores of two rows: running maximum and denominator of `st` are
+// brought up to date (accumulators rescaled when the maximum moves) and the rows' probabilities
+// relative to that maximum are returned.
 template <int G>
-__device__ __forceinline__ void softmax_step(HeadState<G>& st, const float (&s0)[G], const float (&s1)[G],
-                                             const RowRegs& t0, const RowRegs& t1)
+__device__ __forceinline__ void softmax_probs(HeadState<G>& st, const float (&s0)[G], const float (&s1)[G], float (&p0)[G],
+                                              float (&p1)[G])
 {
     float mn[G];
     bool grow = false;
@@ -133,7 +141,6 @@ __device__ __forceinline__ void softmax_step(HeadState<G>& st, const float (&s0)
             st.m[h] = mn[h];
         }
     }
-    float p0[G], p1[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
         const float ms = (st.m[h] == -INFINITY) ? 0.f : st.m[h];
@@ -141,10 +148,191 @@ __device__ __forceinline__ void softmax_step(HeadState<G>& st, const float (&s0)
         p1[h] = __builtin_amdgcn_exp2f(s1[h] - ms);
         st.l[h] += p0[h] + p1[h];
     }
+}
+
+// Online-softmax update with the scores of two rows (s0, s1) and their value rows.
+template <int G>
+__device__ __forceinline__ void softmax_step(HeadState<G>& st, const float (&s0)[G], const float (&s1)[G],
+                                             const RowRegs& t0, const RowRegs& t1)
+{
+    float p0[G], p1[G];
+    softmax_probs<G>(st, s0, s1, p0, p1);
     accumulate_v<G>(st, t0, p0);
     accumulate_v<G>(st, t1, p1);
 }
 
+// ---- 8-bit rows -------------------------------------------------------------------------------
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void issue_load8(u32x2& d, const void* p)
+{
+    asm volatile("global_load_dwordx2 %0, %1, off" : "=&v"(d) : "v"(p) : "memory");
+}
+// kBase: 16-byte loads of ready-made logit shares per row (1 for up to four heads, 2 for five).
+template <int N, int kBase>
+__device__ __forceinline__ void wait_rows8(u32x4 (&b)[4], u32x2 (&sc)[2], u32x4 (&bs)[2 * kBase])
+{
+    if constexpr (kBase == 1)
+        asm volatile("s_waitcnt vmcnt(%8)"
+                     : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(sc[0]), "+v"(sc[1]), "+v"(bs[0]), "+v"(bs[1])
+                     : "n"(N));
+    else
+        asm volatile("s_waitcnt vmcnt(%10)"
+                     : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(sc[0]), "+v"(sc[1]), "+v"(bs[0]), "+v"(bs[1]),
+                       "+v"(bs[2]), "+v"(bs[3])
+                     : "n"(N));
+}
+
+// Two e4m3 codes (the low or the high half of w) as one dword of two bf16 values.
+template <bool kHigh>
+__device__ __forceinline__ uint32_t e4m3_pair_to_bf16(uint32_t w)
+{
+    const auto f = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, kHigh);
+    return __builtin_amdgcn_perm(__float_as_uint(f[1]), __float_as_uint(f[0]), 0x07060302u);   // upper halves of both
+}
+
+// Logits of one 8-bit key row (16 codes per lane) against the G queries; qa / qb hold this lane's
+// dims [16c, 16c+8) and [16c+8, 16c+16) of every query.  `scale` already includes the row's key scale;
+// base[h] is the share of the row's cluster centroid (the codes are the key's residual from it).
+template <int G>
+__device__ __forceinline__ void qk_scores8(const u32x4& kc, const uint4 (&qa)[G], const uint4 (&qb)[G], float scale,
+                                           const float (&base)[G], bool valid, float (&s)[G])
+{
+    const uint32_t k0 = e4m3_pair_to_bf16<false>(kc.x), k1 = e4m3_pair_to_bf16<true>(kc.x);
+    const uint32_t k2 = e4m3_pair_to_bf16<false>(kc.y), k3 = e4m3_pair_to_bf16<true>(kc.y);
+    const uint32_t k4 = e4m3_pair_to_bf16<false>(kc.z), k5 = e4m3_pair_to_bf16<true>(kc.z);
+    const uint32_t k6 = e4m3_pair_to_bf16<false>(kc.w), k7 = e4m3_pair_to_bf16<true>(kc.w);
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        float a = 0.f;
+        a = dot2_bf16(k0, qa[h].x, a);
+        a = dot2_bf16(k1, qa[h].y, a);
+        a = dot2_bf16(k2, qa[h].z, a);
+        a = dot2_bf16(k3, qa[h].w, a);
+        a = dot2_bf16(k4, qb[h].x, a);
+        a = dot2_bf16(k5, qb[h].y, a);
+        a = dot2_bf16(k6, qb[h].z, a);
+        a = dot2_bf16(k7, qb[h].w, a);
+        a = sum8(a);
+        s[h] = valid ? fmaf(a, scale, base[h]) : -INFINITY;
+    }
+}
+
+// acc += (p * vscale) * value codes; accumulator e of a lane is dim 16c + e.
+template <int G>
+__device__ __forceinline__ void accumulate_v8(HeadState<G>& st, const u32x4& vc, const float (&p)[G], float vscale)
+{
+    float pv[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) pv[h] = p[h] * vscale;
+    const uint32_t w[4] = {vc.x, vc.y, vc.z, vc.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);
+        const auto hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            st.acc[h][4 * i] = fmaf(pv[h], lo[0], st.acc[h][4 * i]);
+            st.acc[h][4 * i + 1] = fmaf(pv[h], lo[1], st.acc[h][4 * i + 1]);
+            st.acc[h][4 * i + 2] = fmaf(pv[h], hi[0], st.acc[h][4 * i + 2]);
+            st.acc[h][4 * i + 3] = fmaf(pv[h], hi[1], st.acc[h][4 * i + 3]);
+        }
+    }
+}
+
+// The 8-bit counterpart of stream_rows<G, false, kIters> below: same strips, same masking, a software
+// pipeline of kStages stages.  Loads per iteration (two rows): key codes, value codes, the two scales
+// and the cluster's ready-made logit shares of each row, 6 + 2 * kBase in all.
+template <int G, int kIters>
+__device__ __forceinline__ void stream_rows8(HeadState<G>& st, const RowSource& S, const ValuePassParams& p, int u,
+                                             int w0, int w1, int end, int r, int c, int lane, int gt, int h0)
+{
+    auto head = [&](int h) { return h0 + h < gt ? h0 + h : gt - 1; };
+    const uint8_t* __restrict__ Kb = reinterpret_cast<const uint8_t*>(S.K) + (long long)u * S.unit_rows * kHeadDim;
+    const uint8_t* __restrict__ Vb = reinterpret_cast<const uint8_t*>(S.V) + (long long)u * S.unit_rows * kHeadDim;
+    const float* __restrict__ Sb = S.row_scale + (long long)u * S.unit_rows * 2;
+    const int32_t* __restrict__ rows = S.rows + (long long)u * S.rows_stride;
+    const int32_t* __restrict__ slots = S.row_slot + (long long)u * S.rows_stride;
+    // this wave's columns of the logit-share table: the second half of a split group starts at column 4
+    const float* __restrict__ Bb = S.slot_base + (long long)u * S.base_stride * 8 + (h0 > 0 ? 4 : 0);
+    constexpr int kStrip = 16 * kIters;
+    constexpr int kBase = (G + 3) / 4;
+    constexpr int kLoads = 6 + 2 * kBase;
+    uint4 qa[G], qb[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        const uint4* qp = reinterpret_cast<const uint4*>(p.q + ((long long)u * gt + head(h)) * kHeadDim) + 2 * c;
+        qa[h] = qp[0];
+        qb[h] = qp[1];
+    }
+    const float scale = p.scale_log2e;
+    auto strip_rows = [&](int j0, int& ia, int& ib, int& sa, int& sb) {
+        int pa = j0 + lane, pb = j0 + 64 + lane;
+        pa = pa < end ? pa : end - 1;
+        pb = pb < end ? pb : end - 1;
+        ia = rows[pa];
+        ib = rows[pb];
+        sa = slots[pa];
+        sb = slots[pb];
+    };
+    int na, nb, nsa, nsb;
+    strip_rows(w0, na, nb, nsa, nsb);
+    constexpr int kStages = G <= 3 ? 4 : (G == 4 ? 3 : 2);     // as deep as two waves per SIMD allow
+    for (int j0 = w0; j0 < w1; j0 += kStrip) {
+        const int ia = na, ib = nb, sa = nsa, sb = nsb;
+        if (j0 + kStrip < w1) strip_rows(j0 + kStrip, na, nb, nsa, nsb);
+        u32x4 buf[kStages][4];
+        u32x2 scl[kStages][2];
+        u32x4 bas[kStages][2 * kBase];
+        auto issue = [&](int it, u32x4 (&b)[4], u32x2 (&sc)[2], u32x4 (&bs)[2 * kBase]) {
+            const int slot = it * 16 + r;
+            const bool first = slot < 64;                 // resolved at compile time after unrolling
+            const long long i0 = __shfl(first ? ia : ib, slot & 63, 64);
+            const long long i1 = __shfl(first ? ia : ib, (slot + 8) & 63, 64);
+            const long long s0 = __shfl(first ? sa : sb, slot & 63, 64);
+            const long long s1 = __shfl(first ? sa : sb, (slot + 8) & 63, 64);
+            issue_load16(b[0], reinterpret_cast<const uint4*>(Kb + i0 * kHeadDim) + c);
+            issue_load16(b[1], reinterpret_cast<const uint4*>(Vb + i0 * kHeadDim) + c);
+            issue_load8(sc[0], Sb + i0 * 2);
+#pragma unroll
+            for (int k = 0; k < kBase; ++k) issue_load16(bs[k], Bb + s0 * 8 + 4 * k);
+            issue_load16(b[2], reinterpret_cast<const uint4*>(Kb + i1 * kHeadDim) + c);
+            issue_load16(b[3], reinterpret_cast<const uint4*>(Vb + i1 * kHeadDim) + c);
+            issue_load8(sc[1], Sb + i1 * 2);
+#pragma unroll
+            for (int k = 0; k < kBase; ++k) issue_load16(bs[kBase + k], Bb + s1 * 8 + 4 * k);
+        };
+#pragma unroll
+        for (int it = 0; it < kStages - 1; ++it)
+            if (it < kIters) issue(it, buf[it], scl[it], bas[it]);
+#pragma unroll
+        for (int it = 0; it < kIters; ++it) {
+            const int jj = j0 + it * 16;
+            constexpr int kA = kStages - 1;
+            if (it + kA < kIters) issue(it + kA, buf[(it + kA) % kStages], scl[(it + kA) % kStages], bas[(it + kA) % kStages]);
+            u32x4(&b)[4] = buf[it % kStages];
+            u32x2(&sc)[2] = scl[it % kStages];
+            u32x4(&bs)[2 * kBase] = bas[it % kStages];
+            // loads issued after this iteration's: kLoads for each later iteration already under way
+            if (kStages > 3 && it + 3 < kIters) wait_rows8<3 * kLoads, kBase>(b, sc, bs);
+            else if (kStages > 2 && it + 2 < kIters) wait_rows8<2 * kLoads, kBase>(b, sc, bs);
+            else if (it + 1 < kIters) wait_rows8<kLoads, kBase>(b, sc, bs);
+            else wait_rows8<0, kBase>(b, sc, bs);
+            if (jj < w1) {
+                float s0[G], s1[G], p0[G], p1[G], b0[G], b1[G];
+#pragma unroll
+                for (int h = 0; h < G; ++h) {
+                    b0[h] = __uint_as_float(bs[h >> 2][h & 3]);
+                    b1[h] = __uint_as_float(bs[kBase + (h >> 2)][h & 3]);
+                }
+                qk_scores8<G>(b[0], qa, qb, scale * __uint_as_float(sc[0].x), b0, jj + r < w1, s0);
+                qk_scores8<G>(b[2], qa, qb, scale * __uint_as_float(sc[1].x), b1, jj + 8 + r < w1, s1);
+                softmax_probs<G>(st, s0, s1, p0, p1);
+                accumulate_v8<G>(st, b[1], p0, __uint_as_float(sc[0].y));
+                accumulate_v8<G>(st, b[3], p1, __uint_as_float(sc[1].y));
+            }
+        }
+    }
+}
 
 // Stream the rows [w0, w1) of a source through one wave, 16 rows per iteration (two per group of 8
 // lanes), in strips of 128 rows whose row numbers are fetched with two coalesced loads.
@@ -287,7 +475,9 @@ __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S
     }
 }
 
-template <int G>
+// kBytes: the launch has a source of 8-bit rows.  Such launches get a kernel of their own, so that
+// the registers of one row format's pipeline never cost the other its second wave per SIMD.
+template <int G, bool kBytes>
 __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p)
 {
     constexpr int HB = G < 4 ? G : 4;   // heads combined per round of the epilogue
@@ -343,12 +533,22 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
     const int w0 = begin + (kSplit ? wave >> 1 : wave) * wave_rows;
     const int w1 = (w0 + wave_rows < end) ? w0 + wave_rows : end;
     const int h0 = half * GH;
-    if (S.scores != nullptr)
+    const bool bytes = kBytes && S.row_scale != nullptr;   // 8-bit rows: accumulator e of lane c is dim 16c + e
+    if (S.scores != nullptr) {
         stream_rows<GH, true, 8>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
-    else if (chunk_rows >= 512)
-        stream_rows<GH, false, 8>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
-    else
-        stream_rows<GH, false, 2>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
+    } else if constexpr (kBytes) {
+        if (bytes && chunk_rows >= 512)
+            stream_rows8<GH, 8>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
+        else if (bytes)
+            stream_rows8<GH, 2>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
+        else   // (the bf16 rows of such a launch are the short unclustered tail)
+            stream_rows<GH, false, 2>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
+    } else {
+        if (chunk_rows >= 512)
+            stream_rows<GH, false, 8>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
+        else
+            stream_rows<GH, false, 2>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
+    }
 
     // -------- combine the 32 row groups of the workgroup (4 waves x 8 groups), HB heads per round ----
     float* sm_m = smem;             // [32][HB]
@@ -376,10 +576,11 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
                     sm_l[sid * HB + hh] = own ? hl : 0.f;
                 }
                 float4* dst = reinterpret_cast<float4*>(sm_acc + ((sid * HB + hh) * kHeadDim));
-                dst[2 * c] = make_float4(a[0], a[1], a[2], a[3]);
-                dst[2 * c + 1] = make_float4(a[4], a[5], a[6], a[7]);
-                dst[16 + 2 * c] = make_float4(a[8], a[9], a[10], a[11]);
-                dst[16 + 2 * c + 1] = make_float4(a[12], a[13], a[14], a[15]);
+                const int lo = bytes ? 4 * c : 2 * c, hi = bytes ? 4 * c + 2 : 16 + 2 * c;
+                dst[lo] = make_float4(a[0], a[1], a[2], a[3]);
+                dst[lo + 1] = make_float4(a[4], a[5], a[6], a[7]);
+                dst[hi] = make_float4(a[8], a[9], a[10], a[11]);
+                dst[hi + 1] = make_float4(a[12], a[13], a[14], a[15]);
             }
         }
         __syncthreads();
@@ -483,7 +684,12 @@ hipError_t launch_vp(const ValuePassParams& p, hipStream_t stream)
     const size_t smem = sizeof(float) * (size_t)(400 + 32 * HB * kHeadDim);
     const long long blocks = (long long)p.n_units * p.chunks_per_unit;
     if (blocks <= 0) return hipSuccess;
-    hipLaunchKernelGGL(value_pass_kernel<G>, dim3((unsigned)blocks), dim3(256), smem, stream, p);
+    bool bytes = false;
+    for (int i = 0; i < p.n_sources; ++i) bytes |= p.src[i].row_scale != nullptr;
+    if (bytes)
+        hipLaunchKernelGGL((value_pass_kernel<G, true>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
+    else
+        hipLaunchKernelGGL((value_pass_kernel<G, false>), dim3((unsigned)blocks), dim3(256), smem, stream, p);
     return hipGetLastError();
 }
 

@@ -64,3 +64,26 @@ def test_dequantised_rows_are_close_and_exactly_representable():
     bound = np.maximum(np.abs(X) * 2.0 ** -4, 2.0 ** -10 * scale[:, None]) * (1 + 1e-6)
     assert (err <= bound).all()
     assert (D.astype(np.float32).astype(np.float64) * 0 == 0).all()
+
+
+def test_key_residuals_use_the_cluster_centroid_and_shrink_the_error():
+    rng = np.random.default_rng(2)
+    cen = _bf16(rng.normal(size=(8, 128)) * 20)                      # far-apart cluster centroids
+    which = rng.integers(0, 8, size=300)
+    K = _bf16(cen[which] + rng.normal(size=(300, 128)) * 0.3)
+    codes, scale = O.quantize_keys_e4m3(K, cen[which])
+    # the codes are those of the fp32 difference, by the library's conversion
+    r = torch.tensor(K, dtype=torch.float32) - torch.tensor(cen[which], dtype=torch.float32)
+    y = r / torch.tensor(scale)[:, None]
+    ref = y.to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert ((codes == ref) | (((codes & 0x7f) == 0) & ((ref & 0x7f) == 0))).all()
+    np.testing.assert_array_equal(scale, (r.abs().amax(1) / 448).numpy())
+    D = O.dequantize_keys_e4m3(codes, scale, cen[which])
+    np.testing.assert_array_equal(D - cen[which], O.dequantize_rows_e4m3(codes, scale))
+    # the error is a sixteenth of the residual, not of the key
+    direct = O.dequantize_rows_e4m3(*O.quantize_rows_e4m3(K))
+    assert np.abs(D - K).max() < 0.15 and np.abs(direct - K).max() > 1.0
+    # a key that equals its centroid is stored exactly
+    codes0, scale0 = O.quantize_keys_e4m3(cen[:3], cen[:3])
+    assert (codes0 & 0x7f == 0).all() and (scale0 == 1).all()
+    np.testing.assert_array_equal(O.dequantize_keys_e4m3(codes0, scale0, cen[:3]), cen[:3])
