@@ -409,13 +409,20 @@ static mp_status decode_impl(mp_ctx* ctx, const void* q, const void* q_lookup, c
     const int main_max = std::min(key_budget, ctx->n_tokens);
     int ns = 0, chunk0 = 0;
     // order: centroid terms, tail, selected keys -- the longest stream goes last (see the kernel's block mapping)
+    // The centroid terms ride along with the selected keys where there are any: shared out over that
+    // stream's workgroups they cost each a few per cent more rows, instead of workgroups of their own -- most of
+    // them empty, since only the host-known upper bound of their number can size the grid -- that take their
+    // turn on the compute units before the long streams start.
+    const bool terms_ride = use_mp && main_max > 0;
+    int terms_src = -1;         // (the terms are the launch's first source: what a rider has to be)
     if (use_mp) {
         const int mp_max = ctx->n_fine + ctx->n_coarse;
         const int cr = pick_stream_chunk_rows(mp_max, U, 512);
+        terms_src = ns;
         RowSource& r = vp.src[ns++];
         r.K = nullptr; r.V = ctx->Vc; r.unit_rows = ctx->tab_rows; r.rows = ctx->mp_rows; r.rows_stride = ctx->tab_rows;
         r.count_dev = ctx->n_mp; r.count_max = mp_max; r.scores = ctx->mp_scores; r.chunk0 = chunk0;
-        r.chunk_rows = cr; r.row0 = 0; r.n_chunks = ceil_div(mp_max, cr); chunk0 += r.n_chunks;
+        r.chunk_rows = cr; r.row0 = 0; r.n_chunks = terms_ride ? 0 : ceil_div(mp_max, cr); chunk0 += r.n_chunks;
     }
     if (n_tail > 0) {
         const int cr = pick_stream_chunk_rows(n_tail, U, 512);
@@ -435,6 +442,7 @@ static mp_status decode_impl(mp_ctx* ctx, const void* q, const void* q_lookup, c
         r.unit_rows = ctx->Ncap; r.rows = ctx->rows; r.rows_stride = ctx->Ncap;
         r.count_dev = ctx->n_rows; r.count_max = main_max; r.scores = nullptr; r.chunk0 = chunk0;
         r.chunk_rows = crm; r.row0 = 0; r.n_chunks = ceil_div(main_max, crm); chunk0 += r.n_chunks;
+        r.guest = (terms_ride && terms_src == 0) ? 1 : 0;
     }
     vp.n_sources = ns;
     vp.chunks_per_unit = chunk0;

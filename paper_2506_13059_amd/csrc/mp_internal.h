@@ -36,6 +36,8 @@ struct RowSource {
     int32_t n_chunks;          // ceil(count_max / chunk_rows)
     int32_t chunk_rows;        // rows per workgroup of this source, a multiple of 64
     int32_t row0;              // first list position this source covers: [row0, row0 + count_max)
+    int32_t guest;             // 1: src[0] of the launch, a scored source with n_chunks == 0, rides along: its rows
+                               // are shared out evenly over this source's chunks
 };
 
 struct ValuePassParams {

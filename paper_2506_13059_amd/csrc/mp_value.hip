@@ -66,11 +66,20 @@ __device__ __forceinline__ void load_row(RowRegs& t, const uint16_t* __restrict_
     t.vhi = vp[8];
 }
 
+// kWide: the lane holds the 16 contiguous dims [16c, 16c+16) of the row (the layout of a workgroup
+// that streams 8-bit rows) instead of [8c, 8c+8) and [64+8c, 64+8c+8).
+template <bool kWide>
 __device__ __forceinline__ void load_vrow(RowRegs& t, const uint16_t* __restrict__ V, long long row, int c)
 {
-    const uint4* vp = reinterpret_cast<const uint4*>(V + row * kHeadDim) + c;
-    t.vlo = vp[0];
-    t.vhi = vp[8];
+    if constexpr (kWide) {
+        const uint4* vp = reinterpret_cast<const uint4*>(V + row * kHeadDim) + 2 * c;
+        t.vlo = vp[0];
+        t.vhi = vp[1];
+    } else {
+        const uint4* vp = reinterpret_cast<const uint4*>(V + row * kHeadDim) + c;
+        t.vlo = vp[0];
+        t.vhi = vp[8];
+    }
 }
 
 template <int G>
@@ -347,7 +356,7 @@ __device__ __forceinline__ void stream_rows8(HeadState<G>& st, const RowSource& 
 // only the value-centroid row is loaded; this stream is short and uses plain loads.
 // The G heads of `st` are the heads h0, h0 + 1, ... of the unit's gt heads (clamped to the last one:
 // a wave that owns fewer than G heads computes the last one again and its caller drops the copy).
-template <int G, bool kScored, int kIters>
+template <int G, bool kScored, int kIters, bool kWide = false>
 __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S, const ValuePassParams& p, int u,
                                             int w0, int w1, int end, int r, int c, int lane, int gt, int h0)
 {
@@ -363,8 +372,8 @@ __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S
             const int pa = va ? ja : w1 - 1, pb = vb ? jb : w1 - 1;
             const int ia = rows ? rows[pa] : pa, ib = rows ? rows[pb] : pb;
             RowRegs t0, t1;
-            load_vrow(t0, Vb, ia, c);
-            load_vrow(t1, Vb, ib, c);
+            load_vrow<kWide>(t0, Vb, ia, c);
+            load_vrow<kWide>(t1, Vb, ib, c);
             float s0[G], s1[G];
 #pragma unroll
             for (int h = 0; h < G; ++h) {
@@ -506,7 +515,22 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
     const int begin = S.row0 + (cidx - S.chunk0) * chunk_rows;
     const int end = (begin + chunk_rows < count) ? begin + chunk_rows : count;
     float* part = p.partials + ((long long)u * p.chunks_per_unit + cidx) * G * kPartStride;
-    if (begin >= end) {   // nothing to do for this chunk: an empty partial
+    // A scored source may ride along instead of having workgroups of its own: its rows are shared out
+    // evenly over this source's chunks and go through the same online softmax after the chunk's own rows.
+    const bool bytes = kBytes && S.row_scale != nullptr;   // 8-bit rows: accumulator e of lane c is dim 16c + e
+    const RowSource* T = S.guest ? &p.src[0] : nullptr;     // (always the launch's first source)
+    int g0 = 0, g1 = 0;
+    if (T) {
+        int nt = T->count_max;
+        if (T->count_dev) {
+            const int cd = T->count_dev[u];
+            nt = cd < nt ? cd : nt;
+        }
+        const long long k = cidx - S.chunk0;
+        g0 = (int)(nt * k / S.n_chunks);
+        g1 = (int)(nt * (k + 1) / S.n_chunks);
+    }
+    if (begin >= end && g0 >= g1) {   // nothing to do for this chunk: an empty partial
         if (tid < G) {
             part[tid * kPartStride + 0] = -INFINITY;
             part[tid * kPartStride + 1] = 0.f;
@@ -533,8 +557,9 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
     const int w0 = begin + (kSplit ? wave >> 1 : wave) * wave_rows;
     const int w1 = (w0 + wave_rows < end) ? w0 + wave_rows : end;
     const int h0 = half * GH;
-    const bool bytes = kBytes && S.row_scale != nullptr;   // 8-bit rows: accumulator e of lane c is dim 16c + e
-    if (S.scores != nullptr) {
+    if (begin >= end) {
+        // (only the guest's rows)
+    } else if (S.scores != nullptr) {
         stream_rows<GH, true, 8>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
     } else if constexpr (kBytes) {
         if (bytes && chunk_rows >= 512)
@@ -548,6 +573,19 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
             stream_rows<GH, false, 8>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
         else
             stream_rows<GH, false, 2>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
+    }
+
+    if (g0 < g1) {
+        const int streams = kSplit ? 2 : 4, wi = kSplit ? wave >> 1 : wave;
+        const int per = (((g1 - g0) + streams - 1) / streams + 15) & ~15;
+        const int a = g0 + wi * per, b = (a + per < g1) ? a + per : g1;
+        if (a < b) {
+            if (bytes) {
+                if constexpr (kBytes) stream_rows<GH, true, 8, true>(st, *T, p, u, a, b, g1, r, c, lane, G, h0);
+            } else {
+                stream_rows<GH, true, 8>(st, *T, p, u, a, b, g1, r, c, lane, G, h0);
+            }
+        }
     }
 
     // -------- combine the 32 row groups of the workgroup (4 waves x 8 groups), HB heads per round ----

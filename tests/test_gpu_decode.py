@@ -87,9 +87,10 @@ def _check_tables(ctx, K, V, cls, levels):
 CASES = [
     # B, Hq, Hkv, n, modes, levels, n_fine, n_coarse, budgets [(key, coarse)], n_tail
     dict(name="cfg0", B=1, Hq=4, Hkv=1, n=4096, modes=64, levels=1, nf=64, nc=0,
-         budgets=[(256, 0), (0, 0), (4096, 0), (1000, 0)], tail=0),
+         budgets=[(256, 0), (0, 0), (4096, 0), (1000, 0), (1, 0)], tail=0),
+    # (a key budget below the smallest cluster: nothing is selected, the selected-key workgroups carry only centroid terms)
     dict(name="two_level_ragged", B=1, Hq=8, Hkv=2, n=3001, modes=96, levels=2, nf=96, nc=12,
-         budgets=[(400, 1200), (0, 0), (3001, 3001), (700, 300), (150, 3001)], tail=37),
+         budgets=[(400, 1200), (0, 0), (3001, 3001), (700, 300), (150, 3001), (2, 3001)], tail=37),
     dict(name="group5", B=2, Hq=5, Hkv=1, n=1500, modes=48, levels=2, nf=48, nc=6,
          budgets=[(200, 600), (64, 5000)], tail=130),
     dict(name="group8_one_level", B=1, Hq=8, Hkv=1, n=2100, modes=32, levels=1, nf=70, nc=0,

@@ -69,7 +69,7 @@ CASES = [
     dict(name="one_level_g4", B=1, Hq=4, Hkv=1, n=4096, modes=64, levels=1, nf=64, nc=0,
          budgets=[(256, 0), (0, 0), (4096, 0), (1000, 0)], tail=0),
     dict(name="two_level_ragged_g4", B=1, Hq=8, Hkv=2, n=3001, modes=96, levels=2, nf=96, nc=12,
-         budgets=[(400, 1200), (0, 0), (3001, 3001), (150, 3001)], tail=37),
+         budgets=[(400, 1200), (0, 0), (3001, 3001), (150, 3001), (2, 3001)], tail=37),
     dict(name="group5", B=2, Hq=5, Hkv=1, n=1500, modes=48, levels=2, nf=48, nc=6, budgets=[(200, 600)], tail=130),
     dict(name="group8", B=1, Hq=8, Hkv=1, n=2100, modes=32, levels=1, nf=70, nc=0, budgets=[(300, 0), (2100, 0)], tail=5),
     dict(name="group1_many_units", B=3, Hq=3, Hkv=3, n=900, modes=30, levels=2, nf=40, nc=5, budgets=[(100, 400)], tail=0),
