@@ -67,7 +67,6 @@ int pick_chunk_rows(long long n_rows_per_unit, int n_units)
 int pick_stream_chunk_rows(int rows_max, int n_units, int largest)
 {
     static const int kChoices[] = {2048, 512, 256, 128};
-    if (const char* e = getenv("MP_CHUNK_PROBE")) { const int v = atoi(e); if (v >= 128 && v <= largest) return v; }
     for (int c : kChoices)
         if (c <= largest && (long long)n_units * ((rows_max + c - 1) / c) >= kResidentWgs) return c;
     return 128;

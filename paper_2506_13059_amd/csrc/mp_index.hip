@@ -208,8 +208,9 @@ __global__ void gather_rows_kernel(const uint4* __restrict__ srcK, const uint4* 
     const int c = (int)(g & 15);
     if (p >= n) return;
     const long long s = list[u * list_stride + p];
-    dstK[((long long)u * dst_unit_rows + dst_row0 + p) * 16 + c] = srcK[((long long)u * src_unit_rows + s) * 16 + c];
-    dstV[((long long)u * dst_unit_rows + dst_row0 + p) * 16 + c] = srcV[((long long)u * src_unit_rows + s) * 16 + c];
+    // (a pure stream: every line is read once and written once)
+    store_once(&dstK[((long long)u * dst_unit_rows + dst_row0 + p) * 16 + c], load_once(&srcK[((long long)u * src_unit_rows + s) * 16 + c]));
+    store_once(&dstV[((long long)u * dst_unit_rows + dst_row0 + p) * 16 + c], load_once(&srcV[((long long)u * src_unit_rows + s) * 16 + c]));
 }
 
 // The same gather into 8-bit storage.  A value row becomes 128 e4m3 codes (OCP format: bias 7,
@@ -313,7 +314,7 @@ __global__ __launch_bounds__(256) void cluster_mean_kernel(const uint16_t* __res
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const long long r = __builtin_amdgcn_readlane(mine, (m + q) & 63);
-                w[q] = (m + q < nm) ? Xu[r * 64 + lane] : 0u;
+                w[q] = (m + q < nm) ? load_once(&Xu[r * 64 + lane]) : 0u;
             }
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
