@@ -61,17 +61,6 @@ __device__ __forceinline__ RowRegs as_row(const u32x4& klo, const u32x4& khi, co
     return t;
 }
 
-__device__ __forceinline__ void load_row(RowRegs& t, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-                                         long long row, int c)
-{
-    const uint4* kp = reinterpret_cast<const uint4*>(K + row * kHeadDim) + c;
-    const uint4* vp = reinterpret_cast<const uint4*>(V + row * kHeadDim) + c;
-    t.klo = kp[0];
-    t.khi = kp[8];
-    t.vlo = vp[0];
-    t.vhi = vp[8];
-}
-
 // kWide: the lane holds the 16 contiguous dims [16c, 16c+16) of the row (the layout of a workgroup
 // that streams 8-bit rows) instead of [8c, 8c+8) and [64+8c, 64+8c+8).
 template <bool kWide>
@@ -357,8 +346,8 @@ __device__ __forceinline__ void stream_rows8(HeadState<G>& st, const RowSource& 
 // Stream the rows [w0, w1) of a source through one wave, 16 rows per iteration (two per group of 8
 // lanes), in strips of 128 rows whose row numbers are fetched with two coalesced loads.
 //
-// kScored = false (exact rows, the hot path): a software pipeline of three stages (two for groups
-// of five heads, none for larger groups: no registers).  The loads of
+// kScored = false (exact rows, the hot path): a software pipeline of three stages (two for a wave
+// that holds five heads; a wave never holds more, larger groups are split over two waves).  The loads of
 // iterations it+1 and it+2 are in flight while iteration it is consumed; they are issued through
 // inline assembly and waited for by count, because the compiler would otherwise sink each load
 // next to its use.  All eight iterations of a strip issue their loads (rows past the end are
@@ -417,7 +406,8 @@ __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S
         for (int j0 = w0; j0 < w1; j0 += kStrip) {
             const int ia = na, ib = nb;
             if (j0 + kStrip < w1) strip_rows(j0 + kStrip, na, nb);
-            if constexpr (G <= 5) {
+            static_assert(G <= 5, "a wave holds at most five heads (larger groups are split over two waves)");
+            {
                 // loads of kStages - 1 later iterations are in flight while one is consumed: three
                 // stages where the registers allow it, two for the group of five
                 constexpr int kStages = G <= 4 ? 3 : 2;
@@ -457,37 +447,6 @@ __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S
                         qk_scores<G>(cur0, qlo, qhi, scale, jj + r < w1, s0);
                         qk_scores<G>(cur1, qlo, qhi, scale, jj + 8 + r < w1, s1);
                         softmax_step<G>(st, s0, s1, cur0, cur1);
-                    }
-                }
-            } else {
-                // larger groups leave no registers for the hand-scheduled pipeline (the compiler would have
-                // to spill registers that are still in flight): plain loads, one iteration ahead
-                RowRegs cur0, cur1, nx0, nx1;
-                {
-                    const int i0 = __shfl(ia, r, 64), i1 = __shfl(ia, 8 + r, 64);
-                    load_row(cur0, Kb, Vb, i0, c);
-                    load_row(cur1, Kb, Vb, i1, c);
-                }
-#pragma unroll
-                for (int it = 0; it < kIters; ++it) {
-                    const int jj = j0 + it * 16;
-                    if (jj >= w1) break;
-                    const bool more = (it + 1 < kIters) && (jj + 16 < w1);
-                    if (more) {
-                        const int slot = (it + 1) * 16 + r;
-                        const int src_reg = (slot < 64) ? ia : ib;   // resolved at compile time after unrolling
-                        const int i0 = __shfl(src_reg, slot & 63, 64);
-                        const int i1 = __shfl(src_reg, (slot + 8) & 63, 64);
-                        load_row(nx0, Kb, Vb, i0, c);
-                        load_row(nx1, Kb, Vb, i1, c);
-                    }
-                    float s0[G], s1[G];
-                    qk_scores<G>(cur0, qlo, qhi, scale, jj + r < w1, s0);
-                    qk_scores<G>(cur1, qlo, qhi, scale, jj + 8 + r < w1, s1);
-                    softmax_step<G>(st, s0, s1, cur0, cur1);
-                    if (more) {
-                        cur0 = nx0;
-                        cur1 = nx1;
                     }
                 }
             }

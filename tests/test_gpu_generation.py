@@ -9,9 +9,11 @@ import torch
 pytestmark = pytest.mark.gpu
 
 
-def _loop(levels, steps, L, n_sink, n_recent0, lookup=False):
+def _loop(levels, steps, L, n_sink, n_recent0, lookup=False, eight_bit=False):
     """lookup: the stored keys carry a rotary embedding of their own position, the lookup keys and
-    the lookup query one of a fixed position (Sec. 3.1, last paragraph)."""
+    the lookup query one of a fixed position (Sec. 3.1, last paragraph).
+    eight_bit: the clustered cache holds e4m3 codes; the oracle then attends the dequantised rows
+    (keys = their fine cluster's key centroid + dequantised residual), the buffer stays bf16."""
     from paper_2506_13059_amd import binding as mp, inputs
     from oracle import mp_oracle as O
     from tests.gpu_util import f64, check_output, sets_match, rope
@@ -20,6 +22,14 @@ def _loop(levels, steps, L, n_sink, n_recent0, lookup=False):
         if not lookup:
             return X, None
         return rope(X, pos0 + torch.arange(X.shape[-2])), rope(X, torch.full((X.shape[-2],), 4096))
+    def attended(cl):
+        if not eight_bit:
+            return cl
+        cen = cl["Kc_f"][cl["fine_of_token"]]
+        view = dict(cl)
+        view["K"] = O.dequantize_keys_e4m3(*O.quantize_keys_e4m3(cl["K"], cen), cen)
+        view["V"] = O.dequantize_rows_e4m3(*O.quantize_rows_e4m3(cl["V"]))
+        return view
     B, Hq, Hkv, n0, W, alpha = 1, 4, 2, 700, 512, 256
     nf, nc = 44, 6
     U, G = B * Hkv, Hq // Hkv
@@ -32,7 +42,7 @@ def _loop(levels, steps, L, n_sink, n_recent0, lookup=False):
     cap = n0 + steps + 2 * L
     ctx = mp.MpContext(B, Hq, Hkv, max_tokens=cap, levels=levels, max_fine=nf + 8 * (steps // L + 2),
                        max_coarse=(nc + 2 * (steps // L + 2)) if levels == 2 else 0, block_w=W, block_alpha=alpha,
-                       max_tail=n_sink + 2 * L, lookup_keys=lookup)
+                       max_tail=n_sink + 2 * L, lookup_keys=lookup, kv_format=mp.MP_KV_E4M3 if eight_bit else mp.MP_KV_BF16)
     ctx.mp_cluster_kv(K.view(B, Hkv, n0, 128), V.view(B, Hkv, n0, 128), nf, nc, iters=4, init_fine=init_f,
                       init_coarse=init_c if levels == 2 else None, k_lookup=KL.view(B, Hkv, n0, 128) if lookup else None)
     K64, V64 = f64(K), f64(V)
@@ -90,7 +100,7 @@ def _loop(levels, steps, L, n_sink, n_recent0, lookup=False):
                 rec_kl[u].append(knl64[u])
             Kx = np.concatenate([sink_k[u], np.stack(rec_k[u])]) if n_sink else np.stack(rec_k[u])
             Vx = np.concatenate([sink_v[u], np.stack(rec_v[u])]) if n_sink else np.stack(rec_v[u])
-            res = O.decode_unit(q64[u], cls[u], kb, cb, Kx, Vx, q_lookup=ql64[u])
+            res = O.decode_unit(q64[u], attended(cls[u]), kb, cb, Kx, Vx, q_lookup=ql64[u])
             check_output(f64(out).reshape(U, G, 128)[u], res["out"], f"step {t} unit {u}")
             np.testing.assert_allclose(lse.view(U, G)[u].cpu().numpy(), res["lse"], rtol=3e-5, atol=3e-4)
             if sel is not None:
@@ -115,6 +125,11 @@ def test_generation_two_levels_with_sinks_and_a_split():
     # one block of 700 tokens (W = 512, alpha = 256) grows by 16 per refresh; the fifth refresh makes it
     # reach W + alpha = 768 tokens and splits it
     refreshes, sizes = _loop(levels=2, steps=80, L=16, n_sink=3, n_recent0=20)
+    assert refreshes == 5 and sizes["n_blocks"] == 2
+
+
+def test_generation_with_the_8bit_cache_through_refreshes_and_a_split():
+    refreshes, sizes = _loop(levels=2, steps=80, L=16, n_sink=3, n_recent0=20, eight_bit=True)
     assert refreshes == 5 and sizes["n_blocks"] == 2
 
 
