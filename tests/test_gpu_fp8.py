@@ -78,6 +78,14 @@ CASES = [
     dict(name="long_g4", B=1, Hq=4, Hkv=1, n=20000, modes=200, levels=2, nf=400, nc=40,
          budgets=[(6000, 12000), (20000, 20000)], tail=0),
     dict(name="long_g2", B=1, Hq=2, Hkv=1, n=9000, modes=100, levels=1, nf=150, nc=0, budgets=[(5000, 0)], tail=0),
+    dict(name="group3", B=1, Hq=3, Hkv=1, n=1000, modes=40, levels=1, nf=50, nc=0, budgets=[(200, 0)], tail=0),
+    dict(name="group7", B=1, Hq=7, Hkv=1, n=1000, modes=40, levels=1, nf=50, nc=0, budgets=[(333, 0)], tail=9),
+    # more entries per level than the scoring kernel keeps in LDS: its working arrays, and the logit shares it
+    # hands to the value pass, come from the global-memory instantiation
+    dict(name="one_level_1300_clusters", B=1, Hq=4, Hkv=1, n=5200, modes=400, levels=1, nf=1300, nc=0,
+         budgets=[(700, 0), (5200, 0)], tail=0),
+    dict(name="two_level_1300_candidates", B=1, Hq=4, Hkv=1, n=7800, modes=500, levels=2, nf=2600, nc=40,
+         budgets=[(900, 3900), (300, 7800)], tail=9),
 ]
 
 
