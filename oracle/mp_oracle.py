@@ -9,6 +9,12 @@ import this module.  It imports nothing from the GPU package.
 
 All arrays are float64 numpy arrays holding bf16-representable values (inputs are bf16 tensors
 widened exactly); cluster ids are int32.
+
+Also here: the quantiser of the 8-bit cache (e4m3 codes with one fp32 scale a row, keys as residuals
+from their cluster's centroid).  The paper names no storage format (Sec. 2.3 only calls KV
+quantisation complementary), so the choice of format is "parity unpinned" by the paper; the
+arithmetic of the format itself is pinned against the library's float8 conversion
+(tests/test_oracle_fp8.py).
 """
 from __future__ import annotations
 
