@@ -473,9 +473,20 @@ def error_study(mp, inputs, dev, context=32768, n_fine=4096, n_coarse=512, modes
                            max_coarse=n_coarse if levels == 2 else 0, block_w=8192, block_alpha=4096)
         ctx.mp_cluster_kv(K, V, n_fine, n_coarse if levels == 2 else 0, iters=10, init_fine=init_f,
                           init_coarse=init_c if levels == 2 else None)
+        # the same index over the 8-bit cache (e4m3 codes, keys as residuals from their cluster's centroid)
+        ctx8 = mp.MpContext(B, Hq, Hkv, max_tokens=context, levels=levels, max_fine=n_fine,
+                            max_coarse=n_coarse if levels == 2 else 0, block_w=8192, block_alpha=4096,
+                            kv_format=mp.MP_KV_E4M3)
+        ctx8.mp_cluster_kv(K, V, n_fine, n_coarse if levels == 2 else 0, iters=10, init_fine=init_f,
+                           init_coarse=init_c if levels == 2 else None)
         for sf, Q, dense in zip(softness, Qs, denses):
             for kb in budgets:
                 rec = dict(levels=levels, softness=sf, key_budget=kb)
+                err8 = 0.0
+                for i in range(n_sets):
+                    out = ctx8.mp_decode_attention(Q[i], kb, 4 * kb if levels == 2 else 0).float()
+                    err8 += float(((out - dense[i]).norm(dim=-1) / dense[i].norm(dim=-1)).mean())
+                rec["multipole_8bit_cache_rel_err"] = round(err8 / n_sets, 5)
                 for name, flags in (("multipole", 0), ("retrieval_only", 1)):
                     err, keys, scored = 0.0, 0.0, 0.0
                     for i in range(n_sets):
@@ -489,6 +500,7 @@ def error_study(mp, inputs, dev, context=32768, n_fine=4096, n_coarse=512, modes
                     rec["centroids_scored"] = round(scored / n_sets, 1)
                 rows.append(rec)
         ctx.close()
+        ctx8.close()
 
     # Sweeps at a fixed key budget (context / 16), one level and two levels: tokens per fine centroid
     # (the centroid ratio) and the clustering block length W (alpha = W / 2; 0 = the whole sequence as one
