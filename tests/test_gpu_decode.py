@@ -203,7 +203,8 @@ def test_tail_in_a_buffer_of_fixed_capacity():
     ctx.close()
 
 
-def test_decode_step_in_a_hip_graph():
+@pytest.mark.parametrize("eight_bit", [False, True], ids=["bf16_cache", "8bit_cache"])
+def test_decode_step_in_a_hip_graph(eight_bit):
     """A decode step allocates nothing and never waits for the GPU, so it can be captured once and
     replayed: every replay, with eager work and synchronisations in between, must give the bits of
     an eager call on the same inputs."""
@@ -213,7 +214,8 @@ def test_decode_step_in_a_hip_graph():
     g = torch.Generator(device="cuda").manual_seed(32)
     fot = torch.randint(0, 80, (B * Hkv, n), generator=g, device="cuda").to(torch.int32)
     cof = (torch.arange(80, device="cuda", dtype=torch.int32) // 10)[None].repeat(B * Hkv, 1).contiguous()
-    ctx = mp.MpContext(B, Hq, Hkv, max_tokens=n, levels=2, max_fine=80, max_coarse=8, max_tail=16)
+    ctx = mp.MpContext(B, Hq, Hkv, max_tokens=n, levels=2, max_fine=80, max_coarse=8, max_tail=16,
+                       kv_format=mp.MP_KV_E4M3 if eight_bit else mp.MP_KV_BF16)
     ctx.mp_set_clustering(K, V, fot, 80, cof, 8)
     kt = torch.randn(B, Hkv, 16, 128, generator=g, device="cuda").to(torch.bfloat16)
     vt = torch.randn(B, Hkv, 16, 128, generator=g, device="cuda").to(torch.bfloat16)
