@@ -220,7 +220,9 @@ mp_status mp_update_clusters(mp_ctx* ctx, const void* k_new, const void* k_new_l
  *                   (Sec. 3.1, last paragraph: a query rotated to the fixed position that matches
  *                   the lookup keys).  It gives every centroid logit, including those of the Eq. 2
  *                   terms (Sec. 4: the replacement stage reuses the lookup's products); q itself
- *                   meets the stored keys and the tail.
+ *                   meets the stored keys and the tail.  Must be NULL for a context with
+ *                   MP_KV_E4M3 (MP_EINVAL): its stored keys are residuals from the centroids, and
+ *                   the centroid's share of an exact logit is the lookup's product.
  *   k_tail, v_tail  device bf16 [B, Hkv, tail_stride, 128], of which the first n_tail rows of every
  *                   unit are used: newest tokens that are not clustered yet (the local buffer of
  *                   Sec. 4); always attended exactly; NULL with n_tail == 0.

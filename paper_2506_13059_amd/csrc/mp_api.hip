@@ -375,6 +375,8 @@ static mp_status decode_impl(mp_ctx* ctx, const void* q, const void* q_lookup, c
     if (tail_stride != 0 && tail_stride < n_tail) return fail(ctx, MP_EINVAL, "mp_decode_attention: tail_stride %d < n_tail %d", tail_stride, n_tail);
     if (n_tail > ctx->Tcap) return fail(ctx, MP_ECAPACITY, "mp_decode_attention: n_tail %d > max_tail %d", n_tail, ctx->Tcap);
     if (flags & ~MP_DECODE_NO_MULTIPOLE) return fail(ctx, MP_EINVAL, "mp_decode_attention: unknown flags 0x%x", flags);
+    if (q_lookup && ctx->cfg.kv_format == MP_KV_E4M3)
+        return fail(ctx, MP_EINVAL, "mp_decode_attention: a lookup query cannot be combined with 8-bit keys (residuals from the centroids q itself must meet)");
     hipStream_t s = (hipStream_t)stream;
     const int U = ctx->U, G = ctx->G;
     const bool two = ctx->cfg.levels == 2;

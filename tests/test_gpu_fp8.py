@@ -197,8 +197,17 @@ def test_full_size_decode_on_8bit_rows_sampled_units_match_oracle(kb):
     ctx.close()
 
 
-def test_8bit_context_refuses_lookup_keys():
+def test_8bit_context_refuses_lookup_keys_and_a_lookup_query():
     from paper_2506_13059_amd import binding as mp
+    from tests.test_gpu_decode import _mk
     with pytest.raises(mp.MpError) as e:
         mp.MpContext(1, 2, 1, max_tokens=300, levels=1, max_fine=8, kv_format=mp.MP_KV_E4M3, lookup_keys=True)
     assert e.value.status == 1
+    K, V, q = _mk(1, 2, 1, 300, 8, seed=3)
+    ctx = mp.MpContext(1, 2, 1, max_tokens=300, levels=1, max_fine=8, kv_format=mp.MP_KV_E4M3)
+    ctx.mp_cluster_kv(K, V, 8, iters=1, seed=1)
+    with pytest.raises(mp.MpError) as e:
+        ctx.mp_decode_attention(q[0].contiguous(), 100, q_lookup=q[0].contiguous())
+    assert e.value.status == 1
+    ctx.mp_decode_attention(q[0].contiguous(), 100)
+    ctx.close()

@@ -10,7 +10,7 @@ import torch
 pytestmark = pytest.mark.gpu
 
 
-def _case(seed):
+def _case(seed, eight_bit=False):
     from paper_2506_13059_amd import binding as mp, inputs
     from tests.gpu_util import compare_decode
     rng = np.random.default_rng(1000 + seed)
@@ -41,13 +41,18 @@ def _case(seed):
         kt = torch.randn(B, Hkv, n_tail, 128, generator=g, device="cuda").to(torch.bfloat16)
         vt = torch.randn(B, Hkv, n_tail, 128, generator=g, device="cuda").to(torch.bfloat16)
     ql = None
-    if rng.integers(0, 3) == 0:
+    if rng.integers(0, 3) == 0 and not eight_bit:      # (8-bit keys take no lookup query)
         ql = (q.float() + 0.2 * torch.randn(q.shape, generator=g, device="cuda")).to(torch.bfloat16)
     desc = f"seed {seed}: B={B} Hkv={Hkv} G={G} n={n} levels={levels} nf={nf} nc={nc} tail={n_tail} flags={flags} " \
            f"soft={softness} lookup_query={ql is not None}"
     print(desc, flush=True)
-    ctx = mp.MpContext(B, Hq, Hkv, max_tokens=n, levels=levels, max_fine=nf, max_coarse=nc, max_tail=max(n_tail, 0))
+    ctx = mp.MpContext(B, Hq, Hkv, max_tokens=n, levels=levels, max_fine=nf, max_coarse=nc, max_tail=max(n_tail, 0),
+                       kv_format=mp.MP_KV_E4M3 if eight_bit else mp.MP_KV_BF16)
     ctx.mp_set_clustering(K, V, fot, nf, cof, nc)
+    if eight_bit:       # the oracle attends what the 8-bit cache stands for
+        from tests.test_gpu_fp8 import _check_codes, _dequantised
+        _check_codes(ctx, K, V)
+        K, V = _dequantised(ctx, K, V)
     exempt = 0
     for kb, cb in [(0, 0), (int(rng.integers(1, n + 1)), int(rng.integers(1, 2 * n + 1))), (n, n), (n + 5, 3 * n),
                    (max(1, n // 8), max(1, n // 3))]:
@@ -62,3 +67,9 @@ def _case(seed):
 def test_random_configurations(block):
     exempt = sum(_case(seed) for seed in range(8 * block, 8 * block + 8))
     assert exempt <= 2          # units compared only up to a near-tie at the cut
+
+
+@pytest.mark.parametrize("block", range(2))
+def test_random_configurations_8bit_cache(block):
+    exempt = sum(_case(seed, eight_bit=True) for seed in range(100 + 8 * block, 100 + 8 * block + 8))
+    assert exempt <= 1
