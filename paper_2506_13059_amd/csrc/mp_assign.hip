@@ -589,7 +589,7 @@ hipError_t launch_assign(const uint16_t* X, long long x_unit_rows, const int32_t
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int z = std::min(128, (max_pts + 3) / 4);
+    const int z = std::min(32, (max_pts + 3) / 4);      // (deeper grids only add workgroups that find nothing to do)
     hipLaunchKernelGGL(assign_recheck_kernel, dim3(nb, U, z), dim3(256), 0, s, X, x_unit_rows,
                        blocks_dev, C, c_unit_rows, assign, assign_stride, amb_list, list_stride, amb_cnt, cnt_stride);
     return hipGetLastError();

@@ -303,21 +303,24 @@ __global__ __launch_bounds__(256) void cluster_mean_kernel(const uint16_t* __res
     const uint32_t* Xu = reinterpret_cast<const uint32_t*>(X + (long long)u * x_unit_rows * kHeadDim);
     const int32_t* lp = list ? list + u * list_stride : nullptr;
     double a0 = 0.0, a1 = 0.0;
-    // 64 member indices at a time (one per lane), then their rows eight at a time: the row numbers
-    // reach every lane through a lane broadcast, so that eight row loads are in flight at once while
-    // the additions keep the members' order
+    // 64 member indices at a time (one per lane), then their rows kBatch at a time: the row numbers
+    // reach every lane through a lane broadcast, so that kBatch row loads are in flight at once while
+    // the additions keep the members' order (a wave's time is the number of trips to memory it makes:
+    // with 8 rows a trip the means of coarse clusters of some hundred rows took 160 us per call in an
+    // online refresh, with 32 rows a trip a third of that)
+    constexpr int kBatch = 32;
     for (int base = s0; base < s1; base += 64) {
         const int nm = (s1 - base < 64) ? s1 - base : 64;
         const int mine = (lane < nm) ? (lp ? lp[base + lane] : base + lane) : 0;
-        for (int m = 0; m < nm; m += 8) {
-            uint32_t w[8];
+        for (int m = 0; m < nm; m += kBatch) {
+            uint32_t w[kBatch];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
+            for (int q = 0; q < kBatch; ++q) {
                 const long long r = __builtin_amdgcn_readlane(mine, (m + q) & 63);
                 w[q] = (m + q < nm) ? load_once(&Xu[r * 64 + lane]) : 0u;
             }
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
+            for (int q = 0; q < kBatch; ++q) {
                 if (m + q < nm) {
                     a0 += (double)bf16lo_to_f32(w[q]);
                     a1 += (double)bf16hi_to_f32(w[q]);
