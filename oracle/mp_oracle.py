@@ -344,6 +344,19 @@ def _mean_bf16(S, cnt):
     return out
 
 
+def sums_of_children(S_f, N_f, coarse_of_fine, kc):
+    """Member sums and counts of the coarse clusters from those of their fine clusters: the children's
+    fp64 sums are added one after the other in ascending fine id, starting from zero (Sec. 3.4: a
+    coarse centroid is the mean of all keys below it; the order of the additions is this reading's)."""
+    S_c = np.zeros((kc, S_f.shape[1]), dtype=np.float64)
+    N_c = np.zeros(kc, dtype=np.int32)
+    for f in range(S_f.shape[0]):
+        c = int(coarse_of_fine[f])
+        S_c[c] = S_c[c] + S_f[f]
+        N_c[c] += int(N_f[f])
+    return S_c, N_c
+
+
 def finalize_block(Kb, Vb, a_fine, Cf_kmeans, parent, kc, Cc_kmeans):
     """Renumber a block's fine clusters so that the children of each coarse cluster are contiguous
     (stable in the old id), and compute the stored tables: key/value centroid = mean of the member
@@ -365,12 +378,10 @@ def finalize_block(Kb, Vb, a_fine, Cf_kmeans, parent, kc, Cc_kmeans):
     res = dict(fine_of_token=a_new, Kc_f=Kc_f, Vc_f=Vc_f, N_f=N_f, Sk_f=Sk, Sv_f=Sv)
     if parent is not None:
         cof = parent[order].astype(np.int32)
-        a_coarse = cof[a_new]
-        # member sums of a coarse cluster run over its rows as stored: fine cluster after fine cluster
-        # (ascending new id), sequence order inside a fine cluster
-        stored = np.argsort(a_new, kind="stable")
-        Skc, N_c = member_sums(Kb[stored], a_coarse[stored], kc)
-        Svc, _ = member_sums(Vb[stored], a_coarse[stored], kc)
+        # member sums of a coarse cluster: its fine clusters' sums (each in sequence order), added in
+        # ascending (new) fine id
+        Skc, N_c = sums_of_children(Sk, N_f, cof, kc)
+        Svc, _ = sums_of_children(Sv, N_f, cof, kc)
         Kc_c = _mean_bf16(Skc, N_c)
         Kc_c[N_c == 0] = Cc_kmeans[N_c == 0]
         Vc_c = _mean_bf16(Svc, N_c)
@@ -439,10 +450,8 @@ def clustering_from_assignment(K, V, fine_of_token, n_fine, coarse_of_fine=None,
               blocks=[dict(t0=0, t1=K.shape[0], f0=0, f1=n_fine, c0=0, c1=n_coarse)])
     if coarse_of_fine is not None:
         cof = _i32(coarse_of_fine)
-        ac = cof[fot]
-        stored = np.argsort(fot, kind="stable")      # coarse sums run over the rows as stored (see finalize_block)
-        Skc, N_c = member_sums(KL[stored], ac[stored], n_coarse)
-        Svc, _ = member_sums(V[stored], ac[stored], n_coarse)
+        Skc, N_c = sums_of_children(Sk, N_f, cof, n_coarse)      # (see finalize_block)
+        Svc, _ = sums_of_children(Sv, N_f, cof, n_coarse)
         cl.update(coarse_of_fine=cof, Kc_c=_mean_bf16(Skc, N_c), Vc_c=_mean_bf16(Svc, N_c), N_c=N_c)
     if K_lookup is not None:
         cl["KL"] = KL

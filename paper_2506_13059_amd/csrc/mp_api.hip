@@ -205,7 +205,8 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     if (c.kv_format == MP_KV_E4M3) { A(Kq, U * N * D); A(Vq, U * N * D); A(kv_scale, U * N * 2); A(sel_base, U * F * 8); A(row_slot, U * N); }
     else { A(Kp, U * N * D); A(Vp, U * N * D); }
     A(perm, U * N); A(fot, U * N);
-    A(fstart, U * (F + 1)); A(cof, U * F); A(cstart, U * (Cc + 1)); A(crow, U * (Cc + 1));
+    A(fstart, U * (F + 1)); A(cof, U * F); A(cstart, U * (Cc + 1));
+    if (c.levels == 2) { A(sumK, U * F * D); A(sumV, U * F * D); }
     A(Kc, U * T * D); A(Vc, U * T * D); A(Ncl, U * T);
     A(Kfb, U * (size_t)ctx->FBcap * D); A(Vfb, U * (size_t)ctx->FBcap * D);
     if (c.lookup_keys) A(Kfs, U * (size_t)ctx->FBcap * D);

@@ -176,6 +176,8 @@ struct Problem {
     long long cnt_stride;
     int k_first;                  // first cluster id of the blocks
     int p_first;                  // first point index of the blocks
+    double* sum_out;              // optional [U, sum_unit_rows, 128]: the fp64 member sums behind the new centroids
+    long long sum_unit_rows;
 };
 
 mp_status launch_assign(mp_ctx* ctx, const Problem& pr, hipStream_t s)
@@ -196,7 +198,9 @@ mp_status build_lists(mp_ctx* ctx, const Problem& pr, hipStream_t s)
 }
 
 // One Lloyd iteration: assign, member lists, centroid <- bf16(mean of members); empty keeps.
-mp_status lloyd_iteration(mp_ctx* ctx, const Problem& pr, hipStream_t s)
+// keep_sums: also store the member sums (pr.sum_out), which the coarse tables are built from when this was
+// the last iteration.
+mp_status lloyd_iteration(mp_ctx* ctx, const Problem& pr, bool keep_sums, hipStream_t s)
 {
     mp_status st = launch_assign(ctx, pr, s);
     if (st != MP_OK) return st;
@@ -204,7 +208,7 @@ mp_status lloyd_iteration(mp_ctx* ctx, const Problem& pr, hipStream_t s)
     if (st != MP_OK) return st;
     MP_HIPC(launch_cluster_means(pr.X, pr.x_unit_rows, pr.list, pr.list_stride, pr.start, pr.cnt_stride + 1,
                                  pr.k_first, pr.k_total, ctx->U, pr.C, pr.c_unit_rows, 0, pr.C, pr.c_unit_rows,
-                                 nullptr, 0, 0, s));
+                                 nullptr, 0, 0, keep_sums ? pr.sum_out : nullptr, pr.sum_unit_rows, s));
     return MP_OK;
 }
 
@@ -285,9 +289,11 @@ void upload_descs(const Range& r, int max_blocks, std::vector<int32_t>& bd, int&
 // Stored layout and tables of a range from: ids (final fine id of each local point), ctx->cof for
 // [f0,f1) (non-decreasing per block), and -- for empty clusters -- the key centroids already sitting
 // in ctx->Kc when key_fallback is set.  Block descriptors of the range must be in blocks_dev slot 1.
+// fine_keys_are_means: the fine key centroids in ctx->Kc are the member means already and ctx->sumK holds the
+// member sums behind them, at the fine ids of before the renumbering when sum_map (new id - f0 -> old id) is given.
 mp_status finalize_range(mp_ctx* ctx, const void* Xk, const void* Xs, const void* Xv, long long x_unit_rows, int pt0,
                          int n_pts, const int32_t* ids, long long ids_stride, int f0, int f1, int c0, int c1, int nb,
-                         int max_kf, bool key_fallback, bool fine_keys_are_means, hipStream_t s)
+                         int max_kf, bool key_fallback, bool fine_keys_are_means, const int32_t* sum_map, hipStream_t s)
 {
     const int U = ctx->U;
     const long long Ncap = ctx->Ncap, tab = ctx->tab_rows;
@@ -303,32 +309,25 @@ mp_status finalize_range(mp_ctx* ctx, const void* Xk, const void* Xs, const void
         MP_HIPC(launch_gather_rows(Xs, Xv, x_unit_rows, ctx->km_list, Ncap, n_pts, U, ctx->Kp, ctx->Vp, Ncap, pt0, s));
     // (after a Lloyd iteration the working centroids already sitting in ctx->Kc ARE the member means of the
     // final assignment -- same members, same order of summation, same rounding: nothing to recompute)
+    const bool two = ctx->cfg.levels == 2;
     if (!fine_keys_are_means)
         MP_HIPC(launch_cluster_means((const uint16_t*)Xk, x_unit_rows, ctx->km_list, Ncap, ctx->km_start, tab + 1, f0, f1, U,
-                                     ctx->Kc, tab, 0, key_fallback ? ctx->Kc : nullptr, tab, nullptr, 0, 0, s));
+                                     ctx->Kc, tab, 0, key_fallback ? ctx->Kc : nullptr, tab, nullptr, 0, 0,
+                                     two ? ctx->sumK : nullptr, ctx->Fcap, s));
     MP_HIPC(launch_cluster_means((const uint16_t*)Xv, x_unit_rows, ctx->km_list, Ncap, ctx->km_start, tab + 1, f0, f1, U,
-                                 ctx->Vc, tab, 0, nullptr, 0, ctx->Ncl, tab, 0, s));
+                                 ctx->Vc, tab, 0, nullptr, 0, ctx->Ncl, tab, 0, two ? ctx->sumV : nullptr, ctx->Fcap, s));
     if (bytes)   // (8-bit keys are residuals from the fine key centroids, which are final only now)
         MP_HIPC(launch_gather_quantize_rows(Xs, Xv, x_unit_rows, ctx->km_list, Ncap, ids, ids_stride, ctx->Kc, tab, n_pts, U,
                                             ctx->Kq, ctx->Vq, ctx->kv_scale, Ncap, pt0, s));
-    if (ctx->cfg.levels == 2) {
+    if (two) {
+        // the coarse tables: sums of the children's sums, in ascending fine id (no further pass over the rows)
         MP_HIPC(launch_coarse_start(ctx->cof, ctx->Fcap, f0, f1, c0, c1, U, ctx->cstart, ctx->Ccap + 1, s));
-        MP_HIPC(launch_coarse_row_start(ctx->cstart, ctx->Ccap + 1, ctx->fstart, ctx->Fcap + 1, c0, c1, U, ctx->crow,
-                                        ctx->Ccap + 1, s));
         const uint16_t* kfb = key_fallback ? ctx->Kc + (long long)ctx->Fcap * kHeadDim : nullptr;
-        if (Xs == Xk && !bytes)   // the stored rows of a coarse cluster are contiguous: sum them where they lie
-            MP_HIPC(launch_cluster_means(ctx->Kp, Ncap, nullptr, 0, ctx->crow, ctx->Ccap + 1, c0, c1, U, ctx->Kc, tab, ctx->Fcap,
-                                         kfb, tab, nullptr, 0, 0, s));
-        else                // lookup keys are not stored, 8-bit rows are not the originals: the same rows, in the
-                            // same order, through the member list
-            MP_HIPC(launch_cluster_means((const uint16_t*)Xk, x_unit_rows, ctx->km_list - pt0, Ncap, ctx->crow, ctx->Ccap + 1,
-                                         c0, c1, U, ctx->Kc, tab, ctx->Fcap, kfb, tab, nullptr, 0, 0, s));
-        if (!bytes)
-            MP_HIPC(launch_cluster_means(ctx->Vp, Ncap, nullptr, 0, ctx->crow, ctx->Ccap + 1, c0, c1, U, ctx->Vc, tab,
-                                         ctx->Fcap, nullptr, 0, ctx->Ncl, tab, ctx->Fcap, s));
-        else
-            MP_HIPC(launch_cluster_means((const uint16_t*)Xv, x_unit_rows, ctx->km_list - pt0, Ncap, ctx->crow, ctx->Ccap + 1,
-                                         c0, c1, U, ctx->Vc, tab, ctx->Fcap, nullptr, 0, ctx->Ncl, tab, ctx->Fcap, s));
+        const int32_t* kmap = fine_keys_are_means ? sum_map : nullptr;
+        MP_HIPC(launch_coarse_from_children(ctx->sumK, ctx->Fcap, kmap, ctx->Fcap, f0, ctx->cstart, ctx->Ccap + 1, ctx->Ncl, tab,
+                                            c0, c1, U, ctx->Kc, tab, ctx->Fcap, kfb, tab, nullptr, 0, s));
+        MP_HIPC(launch_coarse_from_children(ctx->sumV, ctx->Fcap, nullptr, 0, f0, ctx->cstart, ctx->Ccap + 1, ctx->Ncl, tab,
+                                            c0, c1, U, ctx->Vc, tab, ctx->Fcap, nullptr, 0, ctx->Ncl, ctx->Fcap, s));
     }
     return MP_OK;
 }
@@ -359,7 +358,7 @@ mp_status coarse_and_finalize(mp_ctx* ctx, const Range& r, int coarse_iters, boo
             MP_HIPC(hipGetLastError());
         }
         for (int it = 0; it < coarse_iters; ++it) {
-            const mp_status st = lloyd_iteration(ctx, pc, s);
+            const mp_status st = lloyd_iteration(ctx, pc, false, s);
             if (st != MP_OK) return st;
         }
         // km_plist[0..kf) = fine ids of the range grouped by coarse cluster (ascending inside): new order
@@ -386,7 +385,7 @@ mp_status coarse_and_finalize(mp_ctx* ctx, const Range& r, int coarse_iters, boo
         MP_HIPC(hipGetLastError());
     }
     return finalize_range(ctx, r.Xk, r.Xs, r.Xv, r.x_unit_rows, r.pt0, r.n_pts, ctx->km_assign, ctx->Ncap, r.f0, r.f1, r.c0,
-                          r.c1, nb, max_kf, true, fine_keys_are_means, s);
+                          r.c1, nb, max_kf, true, fine_keys_are_means, two ? ctx->km_plist : nullptr, s);
 }
 
 // Fresh clustering of a range: seeds are on the device (km_seed_f / km_seed_c at the range's ids).
@@ -406,8 +405,9 @@ mp_status cluster_range(mp_ctx* ctx, const Range& r, int iters, hipStream_t s)
     hipLaunchKernelGGL(init_centroids_kernel, dim3(nb, U), dim3(256), 0, s, pf.X, pf.x_unit_rows, pf.blocks_dev,
                        ctx->km_seed_f, (long long)ctx->Fcap, pf.C, pf.c_unit_rows);
     MP_HIPC(hipGetLastError());
+    pf.sum_out = ctx->sumK; pf.sum_unit_rows = ctx->Fcap;
     for (int it = 0; it < iters; ++it) {
-        const mp_status st = lloyd_iteration(ctx, pf, s);
+        const mp_status st = lloyd_iteration(ctx, pf, it == iters - 1, s);
         if (st != MP_OK) return st;
     }
     return coarse_and_finalize(ctx, r, iters, true, iters > 0, max_kf, max_kc, s);
@@ -499,7 +499,7 @@ mp_status set_clustering_impl(mp_ctx* ctx, const void* k, const void* k_lookup, 
                   ctx->stage_blocks2.size() * sizeof(int32_t), s));
     const void* xk = k_lookup ? k_lookup : k;
     const mp_status st = finalize_range(ctx, xk, k, v, n_tokens, 0, n_tokens, ctx->fot, ctx->Ncap, 0, n_fine, 0, n_coarse, 1,
-                                        max_kf, false, false, s);
+                                        max_kf, false, false, nullptr, s);
     if (st != MP_OK) return st;
     if (n_tokens <= ctx->FBcap) {
         const size_t row = kHeadDim * sizeof(uint16_t);
@@ -648,8 +648,9 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* k_new
     pf.max_pts = nb; pf.max_k = kf; pf.k_total = f1; pf.k_first = f0; pf.C = ctx->km_Cf; pf.c_unit_rows = Fcap;
     pf.assign = ctx->km_assign; pf.assign_stride = Ncap; pf.list = ctx->km_list; pf.list_stride = Ncap;
     pf.cnt = ctx->km_cnt; pf.start = ctx->km_start; pf.cnt_stride = ctx->tab_rows;
+    pf.sum_out = ctx->sumK; pf.sum_unit_rows = ctx->Fcap;
     for (int it = 0; it < refine_iters; ++it) {
-        const mp_status st = lloyd_iteration(ctx, pf, s);
+        const mp_status st = lloyd_iteration(ctx, pf, it == refine_iters - 1, s);
         if (st != MP_OK) return st;
     }
     // ---- coarse level: stored coarse key centroids, plus seeds taken from the new fine centroids ----

@@ -78,7 +78,8 @@ struct mp_ctx {
     int32_t* fstart = nullptr;     // [U, Fcap+1] first stored row of each fine cluster
     int32_t* cof = nullptr;        // [U, Fcap] coarse cluster of each fine cluster
     int32_t* cstart = nullptr;     // [U, Ccap+1] first fine cluster of each coarse cluster
-    int32_t* crow = nullptr;       // [U, Ccap+1] first stored row of each coarse cluster
+    double* sumK = nullptr;        // fp64 [U, Fcap, 128] member sums of the fine clusters (two levels: what the coarse
+    double* sumV = nullptr;        // tables are added up from); sumK may sit at the ids of before a renumbering
     uint16_t* Kc = nullptr;        // bf16 [U, tab_rows, 128] key centroids: fine rows, coarse rows from Fcap
     uint16_t* Vc = nullptr;        // bf16 [U, tab_rows, 128] value centroids
     int32_t* Ncl = nullptr;        // [U, tab_rows] member counts

@@ -293,7 +293,8 @@ __global__ __launch_bounds__(256) void cluster_mean_kernel(const uint16_t* __res
                                                            long long out_unit_rows, int out_row0,
                                                            const uint16_t* __restrict__ fallback,
                                                            long long fb_unit_rows, int32_t* __restrict__ count_out,
-                                                           long long count_stride, int count_off)
+                                                           long long count_stride, int count_off,
+                                                           double* __restrict__ sum_out, long long sum_unit_rows)
 {
     const int u = blockIdx.y;
     const int f = k0 + blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -340,6 +341,68 @@ __global__ __launch_bounds__(256) void cluster_mean_kernel(const uint16_t* __res
     }
     reinterpret_cast<uint32_t*>(mean_out + ((long long)u * out_unit_rows + out_row0 + f) * kHeadDim)[lane] = outw;
     if (count_out && lane == 0) count_out[u * count_stride + count_off + f] = n;
+    if (sum_out) reinterpret_cast<double2*>(sum_out + ((long long)u * sum_unit_rows + f) * kHeadDim)[lane] = make_double2(a0, a1);
+}
+
+// Stored tables of the coarse clusters [c0, c1) from those of their fine clusters (Sec. 3.4: a coarse
+// centroid is the mean of all rows below it): one wave per coarse cluster adds its children's fp64 member
+// sums in ascending fine id, starting from zero, divides by the children's member count and rounds once
+// to bf16.  The sum of fine cluster f is row (map ? map[f - map_f0] : f) of `sums` (sums taken before a
+// renumbering sit at the old ids).  Empty cluster: `fallback` row if given (else zeros).  Lane l owns
+// dims 2l and 2l+1, as in cluster_mean_kernel.
+__global__ __launch_bounds__(256) void coarse_from_children_kernel(const double* __restrict__ sums, long long sum_unit_rows,
+                                                                   const int32_t* __restrict__ map, long long map_stride,
+                                                                   int map_f0, const int32_t* __restrict__ cstart,
+                                                                   long long cstart_stride,
+                                                                   const int32_t* __restrict__ fine_count,
+                                                                   long long count_stride, int c0, int c1,
+                                                                   uint16_t* __restrict__ mean_out, long long out_unit_rows,
+                                                                   int out_row0, const uint16_t* __restrict__ fallback,
+                                                                   long long fb_unit_rows, int32_t* __restrict__ count_out,
+                                                                   int count_off)
+{
+    const int u = blockIdx.y;
+    const int c = c0 + blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (c >= c1) return;
+    const int f_begin = cstart[u * cstart_stride + c], f_end = cstart[u * cstart_stride + c + 1];
+    const double2* Su = reinterpret_cast<const double2*>(sums + (long long)u * sum_unit_rows * kHeadDim);
+    double a0 = 0.0, a1 = 0.0;
+    long long n = 0;
+    for (int base = f_begin; base < f_end; base += 8) {      // eight children's rows in flight, added in order
+        double2 w[8];
+        int cnt[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int f = base + q;
+            w[q] = make_double2(0.0, 0.0);
+            cnt[q] = 0;
+            if (f < f_end) {
+                const long long src = map ? map[u * map_stride + (f - map_f0)] : f;
+                w[q] = Su[src * 64 + lane];
+                cnt[q] = fine_count[u * count_stride + f];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            if (base + q < f_end) {
+                a0 += w[q].x;
+                a1 += w[q].y;
+                n += cnt[q];
+            }
+        }
+    }
+    uint32_t outw;
+    if (n > 0) {
+        const double inv = (double)n;
+        outw = (uint32_t)f64_to_bf16_rne(a0 / inv) | ((uint32_t)f64_to_bf16_rne(a1 / inv) << 16);
+    } else if (fallback) {
+        outw = reinterpret_cast<const uint32_t*>(fallback + ((long long)u * fb_unit_rows + c) * kHeadDim)[lane];
+    } else {
+        outw = 0u;
+    }
+    reinterpret_cast<uint32_t*>(mean_out + ((long long)u * out_unit_rows + out_row0 + c) * kHeadDim)[lane] = outw;
+    if (count_out && lane == 0) count_out[u * count_stride + count_off + c] = (int32_t)n;
 }
 
 // For the fine range [f0, f1) whose coarse ids lie in [c0, c1) and are non-decreasing in the fine id:
@@ -353,17 +416,6 @@ __global__ void coarse_start_kernel(const int32_t* __restrict__ cof, long long c
     const int cur = (f < f1) ? cof[u * cof_stride + f] : c1;
     const int prev = (f > f0) ? cof[u * cof_stride + f - 1] : c0 - 1;
     for (int c = prev + 1; c <= cur; ++c) cstart[u * cstart_stride + c] = f;
-}
-
-// Row ranges of the coarse clusters [c0, c1] in the stored order: rstart[u][c] = fstart[u][cstart[u][c]].
-__global__ void coarse_row_start_kernel(const int32_t* __restrict__ cstart, long long cstart_stride,
-                                        const int32_t* __restrict__ fstart, long long fstart_stride, int c0, int c1,
-                                        int32_t* __restrict__ rstart, long long rstart_stride)
-{
-    const int u = blockIdx.y;
-    const int c = c0 + blockIdx.x * blockDim.x + threadIdx.x;
-    if (c > c1) return;
-    rstart[u * rstart_stride + c] = fstart[u * fstart_stride + cstart[u * cstart_stride + c]];
 }
 
 // Stored-order tables from member lists built on local point indices:
@@ -535,12 +587,25 @@ hipError_t launch_cluster_means(const uint16_t* X, long long x_unit_rows, const 
                                 const int32_t* start, long long start_stride, int k0, int k, int U,
                                 uint16_t* mean_out, long long out_unit_rows, int out_row0, const uint16_t* fallback,
                                 long long fb_unit_rows, int32_t* count_out, long long count_stride, int count_off,
-                                hipStream_t s)
+                                double* sum_out, long long sum_unit_rows, hipStream_t s)
 {
     if (k <= k0) return hipSuccess;
     hipLaunchKernelGGL(cluster_mean_kernel, dim3((k - k0 + 3) / 4, U), dim3(256), 0, s, X, x_unit_rows, list,
                        list_stride, start, start_stride, k0, k, mean_out, out_unit_rows, out_row0, fallback,
-                       fb_unit_rows, count_out, count_stride, count_off);
+                       fb_unit_rows, count_out, count_stride, count_off, sum_out, sum_unit_rows);
+    return hipGetLastError();
+}
+
+hipError_t launch_coarse_from_children(const double* sums, long long sum_unit_rows, const int32_t* map, long long map_stride,
+                                       int map_f0, const int32_t* cstart, long long cstart_stride,
+                                       const int32_t* fine_count, long long count_stride, int c0, int c1, int U,
+                                       uint16_t* mean_out, long long out_unit_rows, int out_row0, const uint16_t* fallback,
+                                       long long fb_unit_rows, int32_t* count_out, int count_off, hipStream_t s)
+{
+    if (c1 <= c0) return hipSuccess;
+    hipLaunchKernelGGL(coarse_from_children_kernel, dim3((c1 - c0 + 3) / 4, U), dim3(256), 0, s, sums, sum_unit_rows, map,
+                       map_stride, map_f0, cstart, cstart_stride, fine_count, count_stride, c0, c1, mean_out, out_unit_rows,
+                       out_row0, fallback, fb_unit_rows, count_out, count_off);
     return hipGetLastError();
 }
 
@@ -549,15 +614,6 @@ hipError_t launch_coarse_start(const int32_t* cof, long long cof_stride, int f0,
 {
     hipLaunchKernelGGL(coarse_start_kernel, dim3((f1 - f0 + 1 + 255) / 256, U), dim3(256), 0, s, cof, cof_stride, f0,
                        f1, c0, c1, cstart, cstart_stride);
-    return hipGetLastError();
-}
-
-hipError_t launch_coarse_row_start(const int32_t* cstart, long long cstart_stride, const int32_t* fstart,
-                                   long long fstart_stride, int c0, int c1, int U, int32_t* rstart,
-                                   long long rstart_stride, hipStream_t s)
-{
-    hipLaunchKernelGGL(coarse_row_start_kernel, dim3((c1 - c0 + 1 + 255) / 256, U), dim3(256), 0, s, cstart,
-                       cstart_stride, fstart, fstart_stride, c0, c1, rstart, rstart_stride);
     return hipGetLastError();
 }
 

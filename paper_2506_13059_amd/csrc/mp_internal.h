@@ -163,16 +163,22 @@ hipError_t launch_gather_quantize_rows(const void* srcK, const void* srcV, long 
                                        long long list_stride, const int32_t* ids, long long ids_stride,
                                        const uint16_t* Kc, long long kc_unit_rows, int n, int U, void* dstK, void* dstV,
                                        float* scales, long long dst_unit_rows, int dst_row0, hipStream_t s);
+// mean_out row (out_row0 + id) = bf16(fp64 sum of the member rows in list order / count); sum_out (optional)
+// receives the fp64 sums themselves, row = id.
 hipError_t launch_cluster_means(const uint16_t* X, long long x_unit_rows, const int32_t* list, long long list_stride,
                                 const int32_t* start, long long start_stride, int k0, int k, int U,
                                 uint16_t* mean_out, long long out_unit_rows, int out_row0, const uint16_t* fallback,
                                 long long fb_unit_rows, int32_t* count_out, long long count_stride, int count_off,
-                                hipStream_t s);
+                                double* sum_out, long long sum_unit_rows, hipStream_t s);
+// Coarse clusters [c0, c1) from their children: sums [U, sum_unit_rows, 128] fp64 member sums of the fine clusters
+// (row = map ? map[f - map_f0] : f), cstart = first child of each coarse cluster, fine_count[f] members.
+hipError_t launch_coarse_from_children(const double* sums, long long sum_unit_rows, const int32_t* map, long long map_stride,
+                                       int map_f0, const int32_t* cstart, long long cstart_stride,
+                                       const int32_t* fine_count, long long count_stride, int c0, int c1, int U,
+                                       uint16_t* mean_out, long long out_unit_rows, int out_row0, const uint16_t* fallback,
+                                       long long fb_unit_rows, int32_t* count_out, int count_off, hipStream_t s);
 hipError_t launch_coarse_start(const int32_t* cof, long long cof_stride, int f0, int f1, int c0, int c1, int U,
                                int32_t* cstart, long long cstart_stride, hipStream_t s);
-hipError_t launch_coarse_row_start(const int32_t* cstart, long long cstart_stride, const int32_t* fstart,
-                                   long long fstart_stride, int c0, int c1, int U, int32_t* rstart,
-                                   long long rstart_stride, hipStream_t s);
 hipError_t launch_offset_lists(const int32_t* start, long long start_stride, int f0, int f1, const int32_t* list,
                                long long list_stride, int n_pts, int pt0, int U, int32_t* fstart,
                                long long fstart_stride, int32_t* perm, long long perm_stride, hipStream_t s);

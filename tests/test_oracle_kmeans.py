@@ -179,3 +179,26 @@ def test_fine_assignment_is_the_nearest_kmeans_centroid_of_the_last_iteration():
     Cc, ac, _ = O.lloyd_from(X, C2, 1)
     np.testing.assert_array_equal(ac, a3)
     np.testing.assert_array_equal(Cc, C3)
+
+
+def test_coarse_sums_are_the_childrens_sums_added_in_fine_id_order():
+    """The coarse tables come from the fine clusters' fp64 member sums, added in ascending fine id from
+    zero.  Magnitudes chosen so that the order shows: fine cluster 0 holds 2^60 and 1, fine cluster 1
+    holds -2^60 and 1 (all exact in bf16).  Each child's sum loses its 1 to rounding (2^60 + 1 is not a
+    double), so the coarse sum is 0; adding the four rows one after the other would give 1, the exact
+    sum is 2."""
+    K = np.zeros((4, 128))
+    K[:, 0] = [2.0 ** 60, 1.0, -2.0 ** 60, 1.0]
+    K[:, 1] = [1.0, 2.0, 3.0, 4.0]                     # an ordinary dimension beside it
+    V = np.ones((4, 128))
+    fot = np.array([0, 0, 1, 1], dtype=np.int32)
+    cl = O.clustering_from_assignment(K, V, fot, 2, coarse_of_fine=np.array([0, 0], dtype=np.int32), n_coarse=1)
+    assert cl["N_c"][0] == 4
+    assert cl["Kc_c"][0, 0] == 0.0
+    assert cl["Kc_c"][0, 1] == 2.5
+    np.testing.assert_array_equal(cl["Vc_c"][0], np.ones(128))
+    # the helper itself: zero start, ascending id, counts added up
+    S_f = np.array([[1.0, 2.0 ** 60], [2.0, 1.0], [4.0, -2.0 ** 60]])
+    S_c, N_c = O.sums_of_children(S_f, np.array([3, 0, 5]), np.array([1, 1, 1]), 2)
+    np.testing.assert_array_equal(S_c, [[0.0, 0.0], [7.0, 0.0]])      # (2^60 + 1) - 2^60 = 0 in fp64, in this order
+    np.testing.assert_array_equal(N_c, [0, 8])
