@@ -52,7 +52,7 @@ def test_create_rejects_bad_configs_without_a_gpu(lib):
     bad = [dict(batch=0), dict(n_q_heads=5, n_kv_heads=2), dict(head_dim=64), dict(n_q_heads=9, n_kv_heads=1),
            dict(levels=3), dict(max_tokens=0), dict(max_fine=0), dict(max_fine=10 ** 6), dict(max_coarse=0),
            dict(max_coarse=17), dict(block_w=-1), dict(block_w=8, block_alpha=9), dict(max_tail=-1),
-           dict(softmax_scale=-1.0)]
+           dict(softmax_scale=-1.0), dict(kv_format=2), dict(kv_format=mp.MP_KV_E4M3, lookup_keys=True)]
     for b in bad:
         with pytest.raises(mp.MpError) as e:
             mp.MpContext(**{**good, **b})
@@ -66,6 +66,7 @@ def test_null_context_calls_fail_cleanly(lib):
     assert lib.mp_cluster_kv(None, None, None, None, 1, 1, 0, 1, 0, None, None, None) == mp.MP_EINVAL
     assert lib.mp_update_clusters(None, None, None, None, 1, 0, 0, 0, 1, 0, None, None) == mp.MP_EINVAL
     assert lib.mp_dense_attention(None, None, None, 1, 1, 1, 1, 0.0, None, None, None, 0, None) == mp.MP_EINVAL
+    assert lib.mp_get_kv_codes(None, None, None, None, None) == mp.MP_EINVAL
     assert b"null" in lib.mp_last_error(None)
     lib.mp_destroy(None)
     assert lib.mp_device_bytes(None) == 0
