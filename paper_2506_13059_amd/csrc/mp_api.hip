@@ -213,7 +213,7 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     A(km_assign, U * N); A(km_list, U * N); A(km_cnt, U * T); A(km_start, U * (T + 2));
     A(km_Cf, U * F * D); A(km_Cc, U * Cc * D); A(km_parent, U * F); A(km_plist, U * F); A(km_newid, U * F);
     A(km_seed_f, U * F); A(km_seed_c, U * Cc); A(blocks_dev, 3 * (size_t)ctx->max_blocks * 4);
-    A(km_amb, U * (size_t)ctx->max_blocks);
+    A(km_amb, 2 * U * (size_t)ctx->max_blocks);
     ctx->Lcap = (int32_t)std::max(F, Cc);
     const size_t Lc = ctx->Lcap;
     A(lg, U * G * Lc); A(sc_keys, U * Lc); A(sc_wts, U * Lc); A(sc_ids, U * Lc); A(sc_aux, U * Lc); A(sc_aux2, U * Lc);
@@ -234,6 +234,7 @@ mp_status mp_create(const mp_config* cfg, mp_ctx** out)
     }
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->pin_ev, hipEventDisableTiming);
     if (e == hipSuccess) e = hipMemset(ctx->counters, 0, U * 4 * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMemset(ctx->km_amb, 0, 2 * U * (size_t)ctx->max_blocks * sizeof(int32_t));
     if (e == hipSuccess) e = hipMemset(ctx->n_mp, 0, U * sizeof(int32_t));
     if (e == hipSuccess) e = hipMemset(ctx->n_rows, 0, U * sizeof(int32_t));
     if (e == hipSuccess) e = hipMemset(ctx->n_cand, 0, U * sizeof(int32_t));

@@ -433,13 +433,17 @@ __global__ __launch_bounds__(256) void assign_recheck_kernel(const uint16_t* __r
                                                              const uint16_t* __restrict__ C, long long c_unit_rows,
                                                              int32_t* __restrict__ assign, long long assign_stride,
                                                              const int32_t* __restrict__ amb_list, long long list_stride,
-                                                             const int32_t* __restrict__ amb_cnt, int cnt_stride)
+                                                             const int32_t* __restrict__ amb_cnt, int cnt_stride,
+                                                             int32_t* __restrict__ cnt_next)
 {
     __shared__ __align__(16) uint16_t xrow[4][kHeadDim];
     __shared__ int cand[4][kCandCap];
     __shared__ int ncand[4];
     __shared__ float sc_cache[4][kScoreCache];
     const int b = blockIdx.x, u = blockIdx.y;
+    // the counters the next assignment step will count into (nobody reads them in this launch): all of the unit's
+    if (b == 0 && blockIdx.z == 0)
+        for (int i = threadIdx.x; i < cnt_stride; i += blockDim.x) cnt_next[u * cnt_stride + i] = 0;
     const int x0 = blocks[4 * b + 0], x1 = blocks[4 * b + 1], k0 = blocks[4 * b + 2], k1 = blocks[4 * b + 3];
     int n = amb_cnt[u * cnt_stride + b];
     if (n > x1 - x0) n = x1 - x0;
@@ -562,12 +566,11 @@ __global__ __launch_bounds__(256) void assign_recheck_kernel(const uint16_t* __r
 hipError_t launch_assign(const uint16_t* X, long long x_unit_rows, const int32_t* blocks_dev, int nb, int max_pts,
                          int max_k, int U, const uint16_t* C, long long c_unit_rows, int32_t* assign,
                          long long assign_stride, int32_t* amb_list, long long list_stride, int32_t* amb_cnt,
-                         int cnt_stride, hipStream_t s)
+                         int32_t* amb_cnt_next, int cnt_stride, hipStream_t s)
 {
     if (nb <= 0 || max_pts <= 0 || U <= 0) return hipSuccess;
     if (nb > cnt_stride || U > 65535) return hipErrorInvalidValue;
-    hipError_t e = launch_fill_i32(amb_cnt, (long long)U * cnt_stride, 0, s);
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
     const int n_chunks = (max_pts + kPtsPerWg - 1) / kPtsPerWg;
     if (max_k > 0 && max_k <= kResidentK && n_chunks >= 4) {
         // enough workgroups to fill the chip, several chunks each where the blocks are long enough
@@ -591,7 +594,8 @@ hipError_t launch_assign(const uint16_t* X, long long x_unit_rows, const int32_t
     if (e != hipSuccess) return e;
     const int z = std::min(32, (max_pts + 3) / 4);      // (deeper grids only add workgroups that find nothing to do)
     hipLaunchKernelGGL(assign_recheck_kernel, dim3(nb, U, z), dim3(256), 0, s, X, x_unit_rows,
-                       blocks_dev, C, c_unit_rows, assign, assign_stride, amb_list, list_stride, amb_cnt, cnt_stride);
+                       blocks_dev, C, c_unit_rows, assign, assign_stride, amb_list, list_stride, amb_cnt, cnt_stride,
+                       amb_cnt_next);
     return hipGetLastError();
 }
 

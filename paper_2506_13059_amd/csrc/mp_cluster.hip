@@ -180,11 +180,19 @@ struct Problem {
     long long sum_unit_rows;
 };
 
+// The counter array of the near-tie lists to use now (which = 0) and the one to leave zeroed for the next step (1).
+inline int32_t* amb_counters(mp_ctx* ctx, int which)
+{
+    return ctx->km_amb + (size_t)((ctx->amb_turn ^ which) & 1) * ctx->U * ctx->max_blocks;
+}
+
 mp_status launch_assign(mp_ctx* ctx, const Problem& pr, hipStream_t s)
 {
     // the member-list array is free during the assignment step and holds the points of the exact pass
     MP_HIPC(mp::launch_assign(pr.X, pr.x_unit_rows, pr.blocks_dev, pr.nb, pr.max_pts, pr.max_k, ctx->U, pr.C, pr.c_unit_rows,
-                              pr.assign, pr.assign_stride, pr.list, pr.list_stride, ctx->km_amb, ctx->max_blocks, s));
+                              pr.assign, pr.assign_stride, pr.list, pr.list_stride, amb_counters(ctx, 0), amb_counters(ctx, 1),
+                              ctx->max_blocks, s));
+    ctx->amb_turn ^= 1;
     return MP_OK;
 }
 
@@ -636,7 +644,9 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* k_new
     }
     // ---- one-shot assignment of the appended tokens + running mean of the touched centroids ----
     MP_HIPC(mp::launch_assign(ctx->Kfb, (long long)ctx->FBcap, ctx->blocks_dev, 1, n_new, 0, U, ctx->km_Cf, Fcap,
-                              ctx->km_assign, Ncap, ctx->km_list, Ncap, ctx->km_amb, ctx->max_blocks, s));
+                              ctx->km_assign, Ncap, ctx->km_list, Ncap, amb_counters(ctx, 0), amb_counters(ctx, 1),
+                              ctx->max_blocks, s));
+    ctx->amb_turn ^= 1;
     MP_HIPC(hipMemcpy2DAsync(ctx->km_assign, (size_t)Ncap * 4, ctx->fot + t0, (size_t)Ncap * 4, (size_t)nb_old * 4, U,
                              hipMemcpyDeviceToDevice, s));
     hipLaunchKernelGGL(running_mean_kernel, dim3((kf + 3) / 4, U), dim3(256), 0, s, ctx->Kfb, (long long)ctx->FBcap,

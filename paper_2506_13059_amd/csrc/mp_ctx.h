@@ -92,7 +92,8 @@ struct mp_ctx {
     // ---- k-means workspace ----
     int32_t* km_assign = nullptr;  // [U, Ncap] block-local cluster of each point
     int32_t* km_list = nullptr;    // [U, Ncap] member lists (during an assignment step: points of the exact pass)
-    int32_t* km_amb = nullptr;     // [U, max_blocks] number of such points per block
+    int32_t* km_amb = nullptr;     // [2][U, max_blocks] number of such points per block: two arrays used in turn, the one
+    int amb_turn = 0;              // not in use is all zero (see launch_assign)
     int32_t* km_cnt = nullptr;     // [U, tab_rows]
     int32_t* km_start = nullptr;   // [U, tab_rows + 2]
     uint16_t* km_Cf = nullptr;     // bf16 [U, Fcap, 128] fine k-means centroids

@@ -13,13 +13,6 @@ namespace mp {
 
 namespace {
 
-__global__ void fill_i32_kernel(int32_t* __restrict__ p, long long n, int32_t v)
-{
-    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long long step = (long long)gridDim.x * blockDim.x;
-    for (; i < n; i += step) p[i] = v;
-}
-
 // cnt[u][id[u][t]] += 1
 __global__ void histogram_kernel(const int32_t* __restrict__ ids, long long ids_stride, int n,
                                  int32_t* __restrict__ cnt, long long cnt_stride)
@@ -500,15 +493,6 @@ hipError_t launch_scatter_selection(const int32_t* cand, long long cand_stride, 
 }
 
 // ---- host launchers ----------------------------------------------------------------------------
-hipError_t launch_fill_i32(int32_t* p, long long n, int32_t v, hipStream_t s)
-{
-    if (n <= 0) return hipSuccess;
-    long long blocks = (n + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, n, v);
-    return hipGetLastError();
-}
-
 hipError_t launch_histogram(const int32_t* ids, long long ids_stride, int n, int U, int32_t* cnt,
                             long long cnt_stride, hipStream_t s)
 {

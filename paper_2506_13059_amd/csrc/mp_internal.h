@@ -128,16 +128,17 @@ size_t score_smem_bytes(int G, int cap);
 // ------------------------------------------------------------------------------------------------
 // Index construction helpers (member lists, gathers, per-cluster means)
 // ------------------------------------------------------------------------------------------------
-hipError_t launch_fill_i32(int32_t* p, long long n, int32_t v, hipStream_t s);
 // Nearest-centroid assignment (fp64 definition, lowest index among equal distances) of the points of
 // nb blocks per unit.  blocks_dev: int32 [nb][4] = {first point, end point, first centroid, end
 // centroid}; assign[u][t] receives the centroid row of point t.  amb_list [U, list_stride] (at least
-// as long as the point range) and amb_cnt [U, cnt_stride >= nb] are workspace.  max_pts / max_k: the
+// as long as the point range) and amb_cnt [U, cnt_stride >= nb] are workspace; amb_cnt must be all zero on
+// entry, and the call leaves amb_cnt_next [U, cnt_stride] all zero for the next one (two arrays used in turn
+// save a fill launch per step).  max_pts / max_k: the
 // largest point / centroid count of a block (max_k = 0: not known; it only selects the kernel).
 hipError_t launch_assign(const uint16_t* X, long long x_unit_rows, const int32_t* blocks_dev, int nb, int max_pts,
                          int max_k, int U, const uint16_t* C, long long c_unit_rows, int32_t* assign,
                          long long assign_stride, int32_t* amb_list, long long list_stride, int32_t* amb_cnt,
-                         int cnt_stride, hipStream_t s);
+                         int32_t* amb_cnt_next, int cnt_stride, hipStream_t s);
 hipError_t launch_histogram(const int32_t* ids, long long ids_stride, int n, int U, int32_t* cnt,
                             long long cnt_stride, hipStream_t s);
 hipError_t launch_exclusive_scan(const int32_t* cnt, long long cnt_stride, int k, int U, int32_t* start,
