@@ -113,6 +113,12 @@ __global__ __launch_bounds__(256) void running_mean_kernel(const uint16_t* __res
         if (e_ != hipSuccess) return fail(ctx, MP_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
+#define MP_TRY(expr)                       \
+    do {                                   \
+        const mp_status st_ = (expr);      \
+        if (st_ != MP_OK) return st_;      \
+    } while (0)
+
 inline unsigned blocks_for(long long n, int per) { return (unsigned)((n + per - 1) / per); }
 
 // Start of an entry point that uploads small host arrays: the pinned staging buffer may be reused
@@ -124,25 +130,64 @@ mp_status stage_open(mp_ctx* ctx)
         ctx->pin_pending = false;
     }
     ctx->pin_used = 0;
+    ctx->n_up = 0;
     return MP_OK;
 }
 
 // Host -> device copy of `height` rows of `width` bytes.  What fits goes through the pinned staging
 // buffer (packed there at once, so the caller's array is free again on return; the copy itself is
 // asynchronous); larger arrays are copied directly from the caller's memory.
+struct UploadBatch { mp_ctx::UploadSeg seg[mp_ctx::kMaxUploadSegs]; };
+
+// grid = (word blocks, segments): row r of segment g goes from the pinned buffer to dst + r * dpitch.
+__global__ void scatter_uploads_kernel(const char* __restrict__ pin, const UploadBatch b)
+{
+    const mp_ctx::UploadSeg sg = b.seg[blockIdx.y];
+    const unsigned wpr = sg.width / 4;                                   // words per row
+    const unsigned long long n = (unsigned long long)wpr * sg.height;
+    for (unsigned long long i = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (unsigned long long)gridDim.x * blockDim.x) {
+        const unsigned long long r = i / wpr, c = i - r * wpr;
+        reinterpret_cast<uint32_t*>(static_cast<char*>(sg.dst) + r * sg.dpitch)[c] =
+            reinterpret_cast<const uint32_t*>(pin + sg.src_off + r * sg.width)[c];
+    }
+}
+
+// Carry out the uploads staged so far (before the first kernel that reads them is launched).
+mp_status flush_uploads(mp_ctx* ctx, hipStream_t s)
+{
+    if (ctx->n_up == 0) return MP_OK;
+    UploadBatch b{};
+    unsigned long long most = 0;
+    for (int i = 0; i < ctx->n_up; ++i) {
+        b.seg[i] = ctx->up_seg[i];
+        most = std::max<unsigned long long>(most, (unsigned long long)(b.seg[i].width / 4) * b.seg[i].height);
+    }
+    const unsigned gx = (unsigned)std::min<unsigned long long>(64, (most + 255) / 256);
+    hipLaunchKernelGGL(scatter_uploads_kernel, dim3(std::max(gx, 1u), ctx->n_up), dim3(256), 0, s, ctx->pin, b);
+    ctx->n_up = 0;
+    MP_HIPC(hipGetLastError());
+    MP_HIPC(hipEventRecord(ctx->pin_ev, s));
+    ctx->pin_pending = true;
+    return MP_OK;
+}
+
+// Stage a small host array (rows of `width` bytes, a multiple of 4) for the device; it arrives with the
+// next flush_uploads.  What does not fit the pinned buffer is copied the ordinary way at once.
 mp_status upload_2d(mp_ctx* ctx, void* dst, size_t dpitch, const void* src, size_t spitch, size_t width, size_t height,
                     hipStream_t s)
 {
     if (width == 0 || height == 0) return MP_OK;
     const size_t bytes = width * height;
-    if (ctx->pin && ctx->pin_used + bytes <= ctx->pin_bytes) {
+    if (ctx->pin && ctx->pin_used + bytes <= ctx->pin_bytes && width % 4 == 0 && dpitch % 4 == 0) {
+        if (ctx->n_up == mp_ctx::kMaxUploadSegs) MP_TRY(flush_uploads(ctx, s));
         char* p = ctx->pin + ctx->pin_used;
         for (size_t r = 0; r < height; ++r) memcpy(p + r * width, (const char*)src + r * spitch, width);
+        ctx->up_seg[ctx->n_up++] = mp_ctx::UploadSeg{dst, (unsigned long long)dpitch, (unsigned long long)ctx->pin_used,
+                                                     (unsigned)width, (unsigned)height};
         ctx->pin_used += (bytes + 255) & ~(size_t)255;
-        MP_HIPC(hipMemcpy2DAsync(dst, dpitch, p, width, width, height, hipMemcpyHostToDevice, s));
-        MP_HIPC(hipEventRecord(ctx->pin_ev, s));
-        ctx->pin_pending = true;
     } else {
+        MP_TRY(flush_uploads(ctx, s));      // (keeps the order of the writes)
         MP_HIPC(hipMemcpy2DAsync(dst, dpitch, src, spitch, width, height, hipMemcpyHostToDevice, s));
     }
     return MP_OK;
@@ -151,12 +196,6 @@ mp_status upload(mp_ctx* ctx, void* dst, const void* src, size_t bytes, hipStrea
 {
     return upload_2d(ctx, dst, bytes, src, bytes, bytes, 1, s);
 }
-#define MP_TRY(expr)                       \
-    do {                                   \
-        const mp_status st_ = (expr);      \
-        if (st_ != MP_OK) return st_;      \
-    } while (0)
-
 struct Problem {
     const uint16_t* X;
     long long x_unit_rows;
@@ -405,6 +444,7 @@ mp_status cluster_range(mp_ctx* ctx, const Range& r, int iters, hipStream_t s)
     upload_descs(r, ctx->max_blocks, ctx->stage_blocks2, max_pts, max_kf, max_kc);
     int32_t* bdev_f = ctx->blocks_dev + 4 * (size_t)ctx->max_blocks;
     MP_TRY(upload(ctx, bdev_f, ctx->stage_blocks2.data(), ctx->stage_blocks2.size() * sizeof(int32_t), s));
+    MP_TRY(flush_uploads(ctx, s));      // (the seeds staged by the caller included)
     Problem pf{};
     pf.X = r.Xk; pf.x_unit_rows = r.x_unit_rows; pf.n_points = r.n_pts; pf.p_first = 0; pf.blocks_dev = bdev_f; pf.nb = nb;
     pf.max_pts = max_pts; pf.max_k = max_kf; pf.k_total = r.f1; pf.k_first = r.f0; pf.C = ctx->km_Cf; pf.c_unit_rows = ctx->Fcap;
@@ -505,6 +545,7 @@ mp_status set_clustering_impl(mp_ctx* ctx, const void* k, const void* k_lookup, 
     upload_descs(r, ctx->max_blocks, ctx->stage_blocks2, max_pts, max_kf, max_kc);
     MP_TRY(upload(ctx, ctx->blocks_dev + 4 * (size_t)ctx->max_blocks, ctx->stage_blocks2.data(),
                   ctx->stage_blocks2.size() * sizeof(int32_t), s));
+    MP_TRY(flush_uploads(ctx, s));
     const void* xk = k_lookup ? k_lookup : k;
     const mp_status st = finalize_range(ctx, xk, k, v, n_tokens, 0, n_tokens, ctx->fot, ctx->Ncap, 0, n_fine, 0, n_coarse, 1,
                                         max_kf, false, false, nullptr, s);
@@ -632,6 +673,7 @@ mp_status update_clusters_impl(mp_ctx* ctx, const void* k_new, const void* k_new
     sd[4] = nb_old; sd[5] = nb; sd[6] = lb.f1; sd[7] = f1;          // new fine centroids seeded from appended points
     sd[8] = lb.f1; sd[9] = f1; sd[10] = lb.c1; sd[11] = c1;         // new coarse centroids seeded from new fine centroids
     MP_TRY(upload(ctx, ctx->blocks_dev, sd.data(), sd.size() * sizeof(int32_t), s));
+    MP_TRY(flush_uploads(ctx, s));
 
     // ---- working fine centroids: the stored key centroids, then the new seeds ----
     hipLaunchKernelGGL(gather1_rows_kernel, dim3(blocks_for((long long)kf_old * 16, 256), U), dim3(256), 0, s,

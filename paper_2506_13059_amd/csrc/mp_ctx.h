@@ -163,6 +163,12 @@ struct mp_ctx {
     size_t pin_bytes = 0, pin_used = 0;
     hipEvent_t pin_ev = nullptr;
     bool pin_pending = false;
+    // Uploads staged there are carried out together, by one kernel that reads the pinned buffer itself
+    // (a refresh's four small host-to-device copies took 60 us of idle stream between them).
+    struct UploadSeg { void* dst; unsigned long long dpitch, src_off; unsigned width, height; };   // bytes, multiples of 4
+    static constexpr int kMaxUploadSegs = 8;
+    UploadSeg up_seg[kMaxUploadSegs];
+    int n_up = 0;
 };
 
 namespace mp {
