@@ -34,15 +34,19 @@ struct RowRegs {
 // must be preceded by wait_rows<N>(), N = number of such loads issued after the ones needed
 // (vector memory loads return in order).
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-// Cache policy of the row loads: non-temporal.  A key or value row is used once per step, and loads
-// marked so move 7 % more bytes per second in the dense kernel (5.9 -> 6.3 TB/s) and 12 % more over
-// the scattered runs of selected keys than plain loads; the scope bits (sc0, sc1) change nothing.
+// Cache policy of the row loads: non-temporal where a row is used once per step (kOnce).  Loads marked
+// so move 7 % more bytes per second in the dense kernel (5.9 -> 6.3 TB/s) and 12 % more over the
+// scattered runs of selected keys than plain loads; the scope bits (sc0, sc1) change nothing.  Where two
+// waves ask for the same row (groups of more than five heads, split over pairs of waves) the row has to
+// stay for the second request: plain loads there (4.8 against 3.7 TB/s at eight heads).
 #ifndef MP_LOAD_BITS
 #define MP_LOAD_BITS " nt"
 #endif
+template <bool kOnce = true>
 __device__ __forceinline__ void issue_load16(u32x4& d, const void* p)
 {
-    asm volatile("global_load_dwordx4 %0, %1, off" MP_LOAD_BITS : "=&v"(d) : "v"(p) : "memory");
+    if constexpr (kOnce) asm volatile("global_load_dwordx4 %0, %1, off" MP_LOAD_BITS : "=&v"(d) : "v"(p) : "memory");
+    else asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(d) : "v"(p) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_rows(u32x4 (&b)[8])
@@ -251,7 +255,7 @@ __device__ __forceinline__ void accumulate_v8(HeadState<G>& st, const u32x4& vc,
 // The 8-bit counterpart of stream_rows<G, false, kIters> below: same strips, same masking, a software
 // pipeline of kStages stages (the loads of the next iteration are in flight while one is consumed).  Loads per iteration (two rows): key codes, value codes, the two scales
 // and the cluster's ready-made logit shares of each row, 6 + 2 * kBase in all.
-template <int G, int kIters>
+template <int G, int kIters, bool kOnce>
 __device__ __forceinline__ void stream_rows8(HeadState<G>& st, const RowSource& S, const ValuePassParams& p, int u,
                                              int w0, int w1, int end, int r, int c, int lane, int gt, int h0)
 {
@@ -299,13 +303,13 @@ __device__ __forceinline__ void stream_rows8(HeadState<G>& st, const RowSource& 
             const long long i1 = __shfl(first ? ia : ib, (slot + 8) & 63, 64);
             const long long s0 = __shfl(first ? sa : sb, slot & 63, 64);
             const long long s1 = __shfl(first ? sa : sb, (slot + 8) & 63, 64);
-            issue_load16(b[0], reinterpret_cast<const uint4*>(Kb + i0 * kHeadDim) + c);
-            issue_load16(b[1], reinterpret_cast<const uint4*>(Vb + i0 * kHeadDim) + c);
+            issue_load16<kOnce>(b[0], reinterpret_cast<const uint4*>(Kb + i0 * kHeadDim) + c);
+            issue_load16<kOnce>(b[1], reinterpret_cast<const uint4*>(Vb + i0 * kHeadDim) + c);
             issue_load8(sc[0], Sb + i0 * 2);
 #pragma unroll
             for (int k = 0; k < kBase; ++k) issue_load16_shared(bs[k], Bb + s0 * 8 + 4 * k);
-            issue_load16(b[2], reinterpret_cast<const uint4*>(Kb + i1 * kHeadDim) + c);
-            issue_load16(b[3], reinterpret_cast<const uint4*>(Vb + i1 * kHeadDim) + c);
+            issue_load16<kOnce>(b[2], reinterpret_cast<const uint4*>(Kb + i1 * kHeadDim) + c);
+            issue_load16<kOnce>(b[3], reinterpret_cast<const uint4*>(Vb + i1 * kHeadDim) + c);
             issue_load8(sc[1], Sb + i1 * 2);
 #pragma unroll
             for (int k = 0; k < kBase; ++k) issue_load16_shared(bs[kBase + k], Bb + s1 * 8 + 4 * k);
@@ -356,7 +360,7 @@ __device__ __forceinline__ void stream_rows8(HeadState<G>& st, const RowSource& 
 // only the value-centroid row is loaded; this stream is short and uses plain loads.
 // The G heads of `st` are the heads h0, h0 + 1, ... of the unit's gt heads (clamped to the last one:
 // a wave that owns fewer than G heads computes the last one again and its caller drops the copy).
-template <int G, bool kScored, int kIters, bool kWide = false>
+template <int G, bool kScored, int kIters, bool kWide = false, bool kOnce = true>
 __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S, const ValuePassParams& p, int u,
                                             int w0, int w1, int end, int r, int c, int lane, int gt, int h0)
 {
@@ -421,14 +425,14 @@ __device__ __forceinline__ void stream_rows(HeadState<G>& st, const RowSource& S
                     const uint4* v0 = reinterpret_cast<const uint4*>(Vb + i0 * kHeadDim) + c;
                     const uint4* k1 = reinterpret_cast<const uint4*>(Kb + i1 * kHeadDim) + c;
                     const uint4* v1 = reinterpret_cast<const uint4*>(Vb + i1 * kHeadDim) + c;
-                    issue_load16(b[0], k0);
-                    issue_load16(b[1], k0 + 8);
-                    issue_load16(b[2], v0);
-                    issue_load16(b[3], v0 + 8);
-                    issue_load16(b[4], k1);
-                    issue_load16(b[5], k1 + 8);
-                    issue_load16(b[6], v1);
-                    issue_load16(b[7], v1 + 8);
+                    issue_load16<kOnce>(b[0], k0);
+                    issue_load16<kOnce>(b[1], k0 + 8);
+                    issue_load16<kOnce>(b[2], v0);
+                    issue_load16<kOnce>(b[3], v0 + 8);
+                    issue_load16<kOnce>(b[4], k1);
+                    issue_load16<kOnce>(b[5], k1 + 8);
+                    issue_load16<kOnce>(b[6], v1);
+                    issue_load16<kOnce>(b[7], v1 + 8);
                 };
                 issue(0, buf[0]);
                 if (kStages > 2 && kIters > 1) issue(1, buf[1 % kStages]);
@@ -533,16 +537,16 @@ __global__ __launch_bounds__(256) void value_pass_kernel(const ValuePassParams p
         stream_rows<GH, true, 8>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
     } else if constexpr (kBytes) {
         if (bytes && chunk_rows >= 512)
-            stream_rows8<GH, 8>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
+            stream_rows8<GH, 8, !kSplit>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
         else if (bytes)
-            stream_rows8<GH, 2>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
+            stream_rows8<GH, 2, !kSplit>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
         else   // (the bf16 rows of such a launch are the short unclustered tail)
-            stream_rows<GH, false, 2>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
+            stream_rows<GH, false, 2, false, !kSplit>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
     } else {
         if (chunk_rows >= 512)
-            stream_rows<GH, false, 8>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
+            stream_rows<GH, false, 8, false, !kSplit>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
         else
-            stream_rows<GH, false, 2>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
+            stream_rows<GH, false, 2, false, !kSplit>(st, S, p, u, w0, w1, end, r, c, lane, G, h0);
     }
 
     if (g0 < g1) {
