@@ -149,6 +149,26 @@ def main():
     dense_bytes = 2 * K.numel() * 2
     dense_gbps = dense_bytes / dense_us / 1e3
 
+    # the same dense kernel with other numbers of query heads per KV head on the same cache (random queries): how
+    # the row stream scales with the arithmetic per row (groups above five heads are split over pairs of waves)
+    dense_by_g = {}
+    if not args.no_others:
+        for Gx in (1, 2, 4, 5, 8):
+            hq = w.n_kv_heads * Gx
+            qx = torch.randn(w.batch, hq, 128, device=dev).to(torch.bfloat16)
+            ox = torch.empty_like(qx)
+            wsx = torch.empty(max(mp.mp_dense_workspace_bytes(w.batch, hq, w.n_kv_heads, w.context), 16), dtype=torch.uint8, device=dev)
+            for _ in range(2):
+                mp.mp_dense_attention(qx, K, V, out=ox, workspace=wsx)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(5):
+                mp.mp_dense_attention(qx, K, V, out=ox, workspace=wsx)
+            e1.record()
+            torch.cuda.synchronize()
+            dense_by_g[str(Gx)] = round(dense_bytes / (e0.elapsed_time(e1) / 5 * 1e3) / 1e3, 1)
+            del qx, ox, wsx
+
     r0 = results[kb0]
 
     cpu = None
@@ -196,6 +216,7 @@ def main():
         "graph_replay_us_per_step": round(graph_us, 2),
         "dense_us_per_step": round(dense_us, 2),
         "dense_hbm_gbps": round(dense_gbps, 1),
+        "dense_hbm_gbps_by_group_size": dense_by_g or None,
         "speedup_vs_dense": round(dense_us / r0["us"], 3),
         "other_budgets": {str(kb): {"us_per_step": round(r["us"], 2), "achieved_hbm_gbps": round(r["gbps"], 1),
                                     "stage_us": {k_: round(v, 2) for k_, v in r["stage_us"].items()},
